@@ -1,0 +1,296 @@
+"""CPU oracle for Gaussian speculative decoding of patch-autoregressive forecasters.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain statement of what the GPU library
+must compute.  Only the test-suite, the smoke check and the benchmark's CPU-baseline leg may
+import it; the product path never does, and this module imports nothing from the product.
+
+Everything is float64 numpy, one series at a time, with NO KV cache: every model evaluation is
+a full causal forward over the whole current history, so the "one pass equals K+1 passes"
+property (Sec. "Single-Pass Verification") is something the tests can check rather than assume.
+
+What the paper fixes and what it leaves open
+  * fixed by the paper: the patch-autoregressive loop (Eq. 1), Gaussian surrogate heads
+    (Eq. 4), the 1/d-scaled log-ratio statistic (Eq. 5) and its mean-propagating special case
+    (Eq. 6), target-mean fallback, bonus patch on full acceptance, single causal verification
+    pass, normalisation frozen on the context, and the order of steps of one round
+    (Algorithm "One speculative round").
+  * open in the paper, fixed here (same choices as the GPU library's header documents):
+    the transformer's internals (pre-norm RMSNorm eps 1e-6, half-split RoPE base 10000,
+    tanh-GELU, no biases, softmax-router top-2 MoE with renormalised gates), instance
+    normalisation (mean / population std with eps 1e-5 under the root), the uniform draw
+    (Philox4x32-10 keyed by seed, counter = (series, round, position, 0), 23-bit mid-point
+    lattice), "u <= alpha" evaluated as log u <= min(0, ell), truncation of commits at
+    T = ceil(H / P).
+
+Pins (tests/test_oracle_*.py): Philox known-answer vectors; closed forms of Eq. 5 / Eq. 6 and
+of the fidelity identity (Eq. 9); the model collapsing to a two-matmul closed form when the
+mixing matrices are zero; causality; single pass == K+1 passes; brute force over accept
+patterns; draft == target; sigma -> 0; the capped-geometric block-length law (Eq. 7).
+The full transformer forward has no external reference value to compare against: beyond
+those structural pins it is "parity unpinned".
+"""
+import math
+
+import numpy as np
+
+RMS_EPS = 1e-6      # inside the root of RMSNorm
+NORM_EPS = 1e-5     # inside the root of the instance normalisation
+ROPE_BASE = 10000.0
+
+# ----------------------------------------------------------------------------------------------
+# Counter-based uniforms: Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11)
+# ----------------------------------------------------------------------------------------------
+_PHILOX_M0 = 0xD2511F53
+_PHILOX_M1 = 0xCD9E8D57
+_PHILOX_W0 = 0x9E3779B9
+_PHILOX_W1 = 0xBB67AE85
+_MASK32 = 0xFFFFFFFF
+
+
+def philox4x32_10(counter, key):
+    """Ten rounds of Philox-4x32 on python ints.  counter: 4 words, key: 2 words -> 4 words."""
+    c0, c1, c2, c3 = (int(c) & _MASK32 for c in counter)
+    k0, k1 = (int(k) & _MASK32 for k in key)
+    for _ in range(10):
+        p0 = _PHILOX_M0 * c0
+        p1 = _PHILOX_M1 * c2
+        c0, c1, c2, c3 = (p1 >> 32) ^ c1 ^ k0, p1 & _MASK32, (p0 >> 32) ^ c3 ^ k1, p0 & _MASK32
+        k0 = (k0 + _PHILOX_W0) & _MASK32
+        k1 = (k1 + _PHILOX_W1) & _MASK32
+    return c0, c1, c2, c3
+
+
+def philox4x32_10_bulk(c0, c1, c2, c3, key):
+    """Vectorised form of `philox4x32_10` over uint64 arrays of counters (word 0 only)."""
+    c0, c1, c2, c3 = (np.asarray(c, dtype=np.uint64) & np.uint64(_MASK32) for c in np.broadcast_arrays(c0, c1, c2, c3))
+    k0, k1 = int(key[0]) & _MASK32, int(key[1]) & _MASK32
+    m32 = np.uint64(_MASK32)
+    s32 = np.uint64(32)
+    for _ in range(10):
+        p0 = np.uint64(_PHILOX_M0) * c0
+        p1 = np.uint64(_PHILOX_M1) * c2
+        c0, c1, c2, c3 = (p1 >> s32) ^ c1 ^ np.uint64(k0), p1 & m32, (p0 >> s32) ^ c3 ^ np.uint64(k1), p0 & m32
+        k0 = (k0 + _PHILOX_W0) & _MASK32
+        k1 = (k1 + _PHILOX_W1) & _MASK32
+    return c0
+
+
+def word_to_uniform(w):
+    """Top 23 bits of a 32-bit word, placed at cell mid-points: exact in fp32, strictly in (0, 1)."""
+    return ((int(w) >> 9) + 0.5) * 2.0 ** -23
+
+
+def uniform(seed, b, r, i):
+    """The uniform of Algorithm "One speculative round" for series b, that series' round r
+    (from 0) and proposal position i (1-based).  Key = (low, high) 32 bits of the seed."""
+    w = philox4x32_10((b, r, i, 0), (seed & _MASK32, (seed >> 32) & _MASK32))
+    return word_to_uniform(w[0])
+
+
+# ----------------------------------------------------------------------------------------------
+# Model: decoder-only causal patch transformer with a point head (Sec. "Preliminaries", Eq. 1)
+# ----------------------------------------------------------------------------------------------
+def rmsnorm(x, g):
+    return x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + RMS_EPS) * g
+
+
+def gelu_tanh(z):
+    return 0.5 * z * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (z + 0.044715 * z ** 3)))
+
+
+def rope(x, pos):
+    """Rotary embedding, half-split pairing.  x: [n, heads, hd]; pos: [n] absolute token index.
+    Pair (i, i + hd/2) is rotated by the angle pos * base^(-2 i / hd)."""
+    hd = x.shape[-1]
+    half = hd // 2
+    inv_freq = ROPE_BASE ** (-2.0 * np.arange(half) / hd)
+    ang = np.asarray(pos, dtype=np.float64)[:, None, None] * inv_freq[None, None, :]
+    c, s = np.cos(ang), np.sin(ang)
+    x1, x2 = x[..., :half], x[..., half:]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def softmax(z, axis=-1):
+    z = z - np.max(z, axis=axis, keepdims=True)
+    e = np.exp(z)
+    return e / np.sum(e, axis=axis, keepdims=True)
+
+
+def attention(q, k, v):
+    """Causal multi-head attention.  q, k, v: [n, heads, hd] -> [n, heads * hd]."""
+    n, H, hd = q.shape
+    out = np.empty((n, H, hd))
+    mask = np.tril(np.ones((n, n), dtype=bool))        # key index <= query index
+    for h in range(H):
+        s = q[:, h, :] @ k[:, h, :].T / math.sqrt(hd)
+        s = np.where(mask, s, -np.inf)
+        out[:, h, :] = softmax(s, axis=-1) @ v[:, h, :]
+    return out.reshape(n, H * hd)
+
+
+def ffn_dense(b, W, l):
+    return gelu_tanh(b @ W[f"l{l}.W_1"]) @ W[f"l{l}.W_2"]
+
+
+def ffn_routed(b, W, l, m):
+    """Softmax router over all experts, top-k by probability (ties -> lower index), the chosen
+    probabilities renormalised to sum to one, no capacity limit."""
+    probs = softmax(b @ W[f"l{l}.W_r"], axis=-1)                   # [n, E]
+    out = np.zeros_like(b)
+    for t in range(b.shape[0]):
+        order = sorted(range(m.n_experts), key=lambda e: (-probs[t, e], e))[: m.top_k]
+        z = sum(probs[t, e] for e in order)
+        for e in order:
+            y = gelu_tanh(b[t] @ W[f"l{l}.e{e}.W_1"]) @ W[f"l{l}.e{e}.W_2"]
+            out[t] += (probs[t, e] / z) * y
+    return out
+
+
+def forward(W, m, tokens):
+    """Full causal forward.  tokens: [n, P] normalised patches at positions 0..n-1.
+    Returns mu: [n, P]; row j is the predicted mean of patch j + 1 given patches 0..j."""
+    tokens = np.asarray(tokens, dtype=np.float64)
+    n = tokens.shape[0]
+    H, hd = m.n_heads, m.d_model // m.n_heads
+    pos = np.arange(n)
+    x = tokens @ W["W_e"]
+    for l in range(m.n_layers):
+        a = rmsnorm(x, W[f"l{l}.g1"])
+        q = rope((a @ W[f"l{l}.W_q"]).reshape(n, H, hd), pos)
+        k = rope((a @ W[f"l{l}.W_k"]).reshape(n, H, hd), pos)
+        v = (a @ W[f"l{l}.W_v"]).reshape(n, H, hd)
+        x = x + attention(q, k, v) @ W[f"l{l}.W_o"]
+        b = rmsnorm(x, W[f"l{l}.g2"])
+        x = x + (ffn_routed(b, W, l, m) if m.n_experts > 0 else ffn_dense(b, W, l))
+    return rmsnorm(x, W["g_f"]) @ W["W_h"]
+
+
+def as_f64(weights):
+    return {k: np.asarray(v, dtype=np.float64) for k, v in weights.items()}
+
+
+# ----------------------------------------------------------------------------------------------
+# Frozen instance normalisation (Sec. "Single-Pass Verification": statistics from the context only)
+# ----------------------------------------------------------------------------------------------
+def context_stats(context):
+    context = np.asarray(context, dtype=np.float64)
+    m = context.mean()
+    s = math.sqrt(context.var() + NORM_EPS)
+    return m, s
+
+
+# ----------------------------------------------------------------------------------------------
+# Acceptance statistic (Eq. 5) and one round (Algorithm "One speculative round")
+# ----------------------------------------------------------------------------------------------
+def energy(u):
+    """Per-dimension energy ||u||_d^2 = ||u||_2^2 / d."""
+    u = np.asarray(u, dtype=np.float64)
+    return float(np.dot(u, u)) / u.size
+
+
+def log_ratio(x, mu_p, mu_q, sigma_p, sigma_q):
+    """Eq. 5: the 1/d-scaled Gaussian log likelihood ratio of target over draft at x."""
+    x = np.asarray(x, dtype=np.float64)
+    return (-energy(x - mu_p) / (2.0 * sigma_p ** 2)
+            + energy(x - mu_q) / (2.0 * sigma_q ** 2)
+            + 0.5 * math.log(sigma_q ** 2 / sigma_p ** 2))
+
+
+def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True, alpha_override=None):
+    """One speculative round for one series.
+
+    hist: [n, P] normalised history (context patches then committed patches).
+    u_fn(i) -> the uniform for proposal position i (1-based).
+    alpha_override: if not None, the acceptance probability of every position is this constant
+        (used to test the block-length law under an i.i.d. acceptance rate).
+    Returns a dict with X, mu_q [K, P], mu_p [K+1, P], ell, logu [K] (nan where untested),
+    n (accepted count) and commits [n + 1, P].
+    """
+    hist = np.asarray(hist, dtype=np.float64)
+    P = hist.shape[1]
+    X = np.empty((K, P))
+    mu_q = np.empty((K, P))
+    cur = hist
+    for i in range(K):                               # K sequential draft passes, mean proposals
+        mu_q[i] = forward(Wd, md, cur)[-1]
+        X[i] = mu_q[i]
+        cur = np.vstack([cur, X[i][None, :]])
+    n0 = hist.shape[0]
+    if single_pass:                                  # one causal pass, read at the K+1 boundaries
+        mu_p = forward(Wt, mt, cur)[n0 - 1: n0 + K]
+    else:                                            # definitional: K+1 separate passes
+        mu_p = np.stack([forward(Wt, mt, cur[: n0 + i])[-1] for i in range(K + 1)])
+    ell = np.full(K, np.nan)
+    logu = np.full(K, np.nan)
+    n = 0
+    for i in range(K):                               # left to right, stop at the first rejection
+        ell[i] = log_ratio(X[i], mu_p[i], mu_q[i], sigma_p, sigma_q)
+        logu[i] = math.log(u_fn(i + 1))
+        thresh = math.log(alpha_override) if alpha_override is not None else min(0.0, ell[i])
+        if logu[i] <= thresh:
+            n += 1
+        else:
+            break
+    commits = np.vstack([X[:n], mu_p[n][None, :]])   # fallback (n < K) or bonus (n == K)
+    return dict(X=X, mu_q=mu_q, mu_p=mu_p, ell=ell, logu=logu, n=n, commits=commits)
+
+
+def forecast_spec(Wt, mt, Wd, md, series_context, P, horizon, K, sigma_p, sigma_q, seed, b,
+                  single_pass=True, alpha_override=None, u_fn=None, trace=None):
+    """Speculative forecast of one series.  series_context: raw context steps (length N * P).
+    Returns (forecast [horizon] in raw units, stats dict).  `trace`, if a list, receives each
+    round's record."""
+    ctx = np.asarray(series_context, dtype=np.float64)
+    m, s = context_stats(ctx)
+    hist = ((ctx - m) / s).reshape(-1, P)
+    T = -(-horizon // P)
+    Y = np.empty((0, P))
+    stats = dict(rounds=0, tested=0, accepted=0, committed=0, lengths=[])
+    r = 0
+    while Y.shape[0] < T:
+        draw = (lambda i, r=r: u_fn(b, r, i)) if u_fn is not None else (lambda i, r=r: uniform(seed, b, r, i))
+        rec = spec_round(Wt, mt, Wd, md, np.vstack([hist, Y]), K, sigma_p, sigma_q, draw,
+                         single_pass=single_pass, alpha_override=alpha_override)
+        if trace is not None:
+            trace.append(rec)
+        n = rec["n"]
+        stats["rounds"] += 1
+        stats["tested"] += n + (1 if n < K else 0)
+        stats["accepted"] += n
+        stats["lengths"].append(n + 1)
+        Y = np.vstack([Y, rec["commits"]])[:T]       # whole patches, never more than T
+        r += 1
+    stats["committed"] = Y.shape[0]
+    return (Y.reshape(-1) * s + m)[:horizon], stats
+
+
+def forecast_target_only(Wt, mt, series_context, P, horizon):
+    """Eq. 1: T = ceil(H / P) sequential target passes, each committing the target's mean patch."""
+    ctx = np.asarray(series_context, dtype=np.float64)
+    m, s = context_stats(ctx)
+    hist = ((ctx - m) / s).reshape(-1, P)
+    T = -(-horizon // P)
+    for _ in range(T):
+        hist = np.vstack([hist, forward(Wt, mt, hist)[-1][None, :]])
+    return (hist[-T:].reshape(-1) * s + m)[:horizon]
+
+
+# ----------------------------------------------------------------------------------------------
+# Throughput law (Eq. 7, Eq. 8, marginal-gain criterion for K)
+# ----------------------------------------------------------------------------------------------
+def block_length_pmf(alpha, K):
+    """P(L = l), l = 1..K+1, under an i.i.d. per-position acceptance rate alpha."""
+    return np.array([(1 - alpha) * alpha ** (l - 1) for l in range(1, K + 1)] + [alpha ** K])
+
+
+def expected_block_length(alpha, K):
+    return float(K + 1) if alpha == 1.0 else (1 - alpha ** (K + 1)) / (1 - alpha)
+
+
+def predicted_speedup(alpha, K, c, v):
+    return expected_block_length(alpha, K) / (c * K + v)
+
+
+def next_position_pays(alpha, K, c, v):
+    """S(K+1) >= S(K)  iff  alpha^(K+1) (cK + v) >= c E[L_K]."""
+    return alpha ** (K + 1) * (c * K + v) >= c * expected_block_length(alpha, K)
