@@ -1,0 +1,202 @@
+/*
+ * tsd.h -- C ABI of libtsd: batched Gaussian speculative decoding rounds for continuous
+ * patch-autoregressive time-series transformers on AMD MI355X (gfx950).
+ *
+ * The method (arXiv 2511.18191): a cheap draft model proposes K future patches, the target
+ * model scores all K+1 prefix boundaries in ONE causal pass, each proposal passes a log-domain
+ * Gaussian likelihood-ratio test, the first rejection is replaced by the target's own mean, a
+ * bonus patch is committed on full acceptance, and the round ends.  This library runs that
+ * round for a whole batch of independent series with per-series ragged accepted lengths, over
+ * a paged per-series KV cache, entirely in hand-written HIP kernels.
+ *
+ * Conventions
+ *   - Every function returns TSD_OK (0) or a negative TSD_E_* code; nothing throws or aborts.
+ *     Arguments are validated on the host before anything is launched.  tsd_last_error()
+ *     returns a human-readable message for the most recent failure on that handle (or, with a
+ *     NULL handle, for the most recent failure of a call that had no handle).
+ *   - Pointers named *_dev are DEVICE pointers, *_host are HOST pointers.  The caller owns all
+ *     device memory (arena, weight blobs, I/O buffers); the library owns only the opaque
+ *     handle and never frees or allocates device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All calls are
+ *     asynchronous on that stream except where stated.  Calls on one handle must be issued
+ *     from one thread at a time and on one stream at a time.
+ *   - All arrays are dense row-major.  Patches live in NORMALISED space (per-series mean/std
+ *     of the context, frozen at prefill: Sec. "Single-Pass Verification"); only
+ *     tsd_get_forecast() de-normalises.
+ *   - dtype TSD_F32: weights, activations and KV in fp32.  dtype TSD_BF16: weights, KV and
+ *     GEMM operands in bf16, accumulation / norms / softmax / RoPE / residual stream / model
+ *     outputs / acceptance in fp32.
+ *
+ * Model evaluated (the paper fixes a decoder-only causal transformer with a point head and
+ * the layer/width/head/FFN counts; the rest is this library's documented choice):
+ *   e_j = patch_j W_e; per layer: a = RMSNorm(x; g1, eps 1e-6); q,k,v = a W_q, a W_k, a W_v;
+ *   half-split RoPE (base 10000, position = absolute token index) on q,k; causal softmax
+ *   attention with scale 1/sqrt(head_dim); x += attn W_o; b = RMSNorm(x; g2);
+ *   dense: x += GELU_tanh(b W_1) W_2;  routed: softmax router over n_experts, top_k by
+ *   probability (ties to the lower index), gates renormalised to sum 1, x += sum gate_e FFN_e(b);
+ *   mu_j = RMSNorm(x_j; g_f) W_h = predicted mean of patch j+1.  No biases.
+ */
+#ifndef TSD_H
+#define TSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TSD_OK 0
+#define TSD_E_INVALID_ARG (-1)  /* NULL pointer, bad size, unsupported shape               */
+#define TSD_E_BAD_STATE (-2)    /* call made out of order (e.g. round before prefill)      */
+#define TSD_E_OUT_OF_RANGE (-3) /* batch / tokens exceed what the handle was created for   */
+#define TSD_E_HIP (-4)          /* a HIP runtime call failed; see tsd_last_error()         */
+
+#define TSD_F32 0
+#define TSD_BF16 1
+
+#define TSD_TARGET 0
+#define TSD_DRAFT 1
+
+/* flags */
+#define TSD_FLAG_SCRAMBLE_PAGES 1u /* assign physical KV pages by a pseudo-random permutation */
+#define TSD_FLAG_NO_TEMPERING 2u   /* ablation: use d * ell (drop the 1/d scaling of Eq. 5)    */
+
+typedef struct tsd_ctx tsd_ctx; /* opaque */
+
+typedef struct {
+  int32_t n_layers, d_model, n_heads, d_ff;
+  int32_t n_experts; /* 0 = dense FFN */
+  int32_t top_k;     /* used when n_experts > 0 */
+} tsd_model_cfg;
+
+typedef struct {
+  tsd_model_cfg target, draft;
+  int32_t patch;       /* P: steps per patch (= acceptance dimension d, one channel per series) */
+  int32_t K;           /* proposals per round, 1..16                                            */
+  int32_t max_batch;   /* largest B accepted by tsd_prefill                                     */
+  int32_t max_tokens;  /* largest N + ceil(H/P) + K accepted by tsd_prefill                     */
+  int32_t dtype;       /* TSD_F32 | TSD_BF16                                                    */
+  int32_t page_tokens; /* tokens per KV page (power of two, 1..64)                              */
+  float sigma_p;       /* acceptance temperature of the target surrogate (Eq. 4)                */
+  float sigma_q;       /* ... of the draft surrogate; equal to sigma_p in the deployed scheme   */
+  float fallback_r;    /* fallback noise; must be 0 (target-mean fallback)                      */
+  uint32_t flags;
+  uint64_t seed;       /* Philox key = (low 32 bits, high 32 bits)                              */
+} tsd_config;
+
+typedef struct {
+  int64_t rounds;     /* series-rounds executed (one per active series per round)            */
+  int64_t tested;     /* proposals that met the acceptance test                              */
+  int64_t accepted;   /* proposals accepted by the test (before any forced length)           */
+  int64_t committed;  /* patches committed (after truncation at T)                           */
+  int64_t near_ties;  /* tested proposals with |min(0, ell) - log u| < 1e-4                   */
+} tsd_stats;
+
+/* Bytes of device memory tsd_create needs for `cfg` (weights in internal layout, rotary
+ * tables, both paged KV pools, page table, per-series state, activation workspace).
+ * Host-only; never touches the GPU. */
+int tsd_workspace_bytes(const tsd_config* cfg, size_t* bytes_host);
+
+/* Number of float32 elements of one model's weight blob (`which` = TSD_TARGET | TSD_DRAFT).
+ * Blob order: W_e [P,D]; per layer: g1 [D], W_q, W_k, W_v, W_o [D,D], g2 [D], then
+ * dense: W_1 [D,F], W_2 [F,D]; routed: W_r [D,E], then per expert W_1 [D,F], W_2 [F,D];
+ * finally g_f [D], W_h [D,P].  Matrices are stored as used in y = x W (row-major [in,out]).
+ * Host-only. */
+int tsd_weights_count(const tsd_config* cfg, int which, size_t* n_floats_host);
+
+/* Create a handle over caller-owned device memory `arena_dev` (256-byte aligned, at least
+ * tsd_workspace_bytes).  The arena must outlive the handle.  Fills the rotary tables
+ * (synchronous host-to-device copies). */
+int tsd_create(const tsd_config* cfg, void* arena_dev, size_t arena_bytes, tsd_ctx** out);
+
+/* Release the handle (host memory only).  Synchronises the device first. */
+int tsd_destroy(tsd_ctx* ctx);
+
+/* Convert one model's float32 blob (device memory, order above) into the internal layout
+ * (transposed, RMSNorm gains folded into the following matrix, rounded to bf16 when
+ * dtype = TSD_BF16).  The blob may be freed once the stream has passed this call. */
+int tsd_load_weights(tsd_ctx* ctx, int which, const float* blob_dev, size_t n_floats, void* stream);
+
+/* Start a forecast for B series.  series_dev: [B, n_ctx_patches * P] raw context steps.
+ * Computes the frozen per-series statistics (mean, sqrt(population variance + 1e-5)),
+ * normalises, runs target and draft over context patches 0..N-2 to fill both KV caches, and
+ * keeps patch N-1 as the pending (not yet ingested) token.  Requires n_ctx_patches >= 2,
+ * B <= max_batch, n_ctx_patches + ceil(horizon_steps / P) + K <= max_tokens. */
+int tsd_prefill(tsd_ctx* ctx, const float* series_dev, int32_t B, int32_t n_ctx_patches, int32_t horizon_steps,
+                void* stream);
+
+/* Rewind to the state right after tsd_prefill (KV entries of the context are kept, everything
+ * committed since is dropped, statistics zeroed).  Lets one prefill serve several decodes. */
+int tsd_reset_decode(tsd_ctx* ctx, void* stream);
+
+/* Algorithm "One speculative round", first loop: K sequential draft passes; proposal i is the
+ * draft's mean given the history and proposals 1..i-1 (mean-propagating scheme, x_i = mu_q^(i)).
+ * Fills the internal X [B,K,P]. */
+int tsd_draft_propose(tsd_ctx* ctx, void* stream);
+
+/* Single-pass verification (Sec. "Single-Pass Verification"): one causal target pass over the
+ * pending token and x_1..x_K against the paged KV cache; the output at token j is the target
+ * mean at prefix boundary j+1.  Fills the internal mu_p [B,K+1,P]. */
+int tsd_target_verify(tsd_ctx* ctx, void* stream);
+
+/* Acceptance (Eq. 5 / Eq. 6), correction, commit and KV rollback for every active series:
+ *   ell_i = -||x_i - mu_p^(i)||_d^2 / (2 sigma_p^2) + ||x_i - mu_q^(i)||_d^2 / (2 sigma_q^2)
+ *           + (1/2) log(sigma_q^2 / sigma_p^2),     ||u||_d^2 = ||u||^2 / P;
+ *   u_i = Philox4x32-10(counter = (series, round of that series, i, 0), key = seed), word 0,
+ *         u = ((w >> 9) + 0.5) * 2^-23;   accept iff log u_i <= min(0, ell_i), left to right;
+ *   n = number of leading accepts; commit x_1..x_n then mu_p^(n+1) (fallback if n < K, bonus
+ *   if n = K), truncated at T = ceil(H/P) patches; both KV caches keep exactly the entries of
+ *   the committed history; mu_p^(n+1) becomes the pending token; a series with T patches
+ *   becomes inactive.
+ * forced_len_dev (nullable): int32 [B]; entry b in 0..K overrides n for series b after the test
+ * has been evaluated and recorded (used to keep two implementations in lock-step); -1 = free. */
+int tsd_accept_commit(tsd_ctx* ctx, const int32_t* forced_len_dev, void* stream);
+
+/* tsd_draft_propose; tsd_target_verify; tsd_accept_commit(NULL). */
+int tsd_round(tsd_ctx* ctx, void* stream);
+
+/* Target-only autoregressive baseline (Eq. 1) from the same kernels: one target pass over the
+ * pending token, whose output is committed for every active series. */
+int tsd_target_step(tsd_ctx* ctx, void* stream);
+
+/* Number of series that still need patches.  Synchronises `stream`. */
+int tsd_num_active(tsd_ctx* ctx, int32_t* out_host, void* stream);
+
+/* De-normalised forecast, out_dev: [B, horizon_steps] (first H steps of the committed patches;
+ * positions not yet committed are written as 0). */
+int tsd_get_forecast(tsd_ctx* ctx, float* out_dev, void* stream);
+
+/* Parity taps: copies of the last round's tensors.  Any pointer may be NULL.
+ * X, mu_q: [B,K,P]; mu_p: [B,K+1,P]; n_acc: int32 [B] accepted count found by the test (-1 for
+ * inactive series); ell, logu: [B,K] (NaN where a position was not tested). */
+int tsd_get_round_io(tsd_ctx* ctx, float* X_dev, float* mu_q_dev, float* mu_p_dev, int32_t* n_acc_dev,
+                     float* ell_dev, float* logu_dev, void* stream);
+
+/* Replace the round tensors consumed by the next tsd_accept_commit (kernel-level parity: feed
+ * another implementation's X, mu_q, mu_p).  All three required, shapes as above. */
+int tsd_set_round_io(tsd_ctx* ctx, const float* X_dev, const float* mu_q_dev, const float* mu_p_dev, void* stream);
+
+/* Per-series state: len int32 [B] (tokens held by the target cache = position of the pending
+ * token), committed int32 [B], pending float [B,P].  Any pointer may be NULL. */
+int tsd_get_state(tsd_ctx* ctx, int32_t* len_dev, int32_t* committed_dev, float* pending_dev, void* stream);
+
+/* Aggregate counters since prefill / reset.  Synchronises `stream`. */
+int tsd_get_stats(tsd_ctx* ctx, tsd_stats* out_host, void* stream);
+
+/* alpha in (0, 1]: every tested position is accepted with this constant probability instead of
+ * min(1, e^ell) (block-length law under an i.i.d. rate, Eq. 7).  alpha < 0 restores the rule. */
+int tsd_set_accept_override(tsd_ctx* ctx, float alpha);
+
+/* Change the acceptance temperatures (temperature sweeps without re-creating the handle). */
+int tsd_set_sigma(tsd_ctx* ctx, float sigma_p, float sigma_q);
+
+const char* tsd_last_error(tsd_ctx* ctx);
+
+/* ABI version of this header (bumped on incompatible change). */
+int tsd_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TSD_H */

@@ -1,0 +1,9 @@
+"""MI355X-native speculative decoding rounds for patch-autoregressive time-series transformers.
+
+The product is the C-ABI library `libtsd.so` (declared in include/tsd.h, implemented as HIP
+kernels for gfx950).  This package is its thin Python binding: argument marshalling only.
+"""
+from .binding import (  # noqa: F401
+    TSD_BF16, TSD_DRAFT, TSD_F32, TSD_FLAG_NO_TEMPERING, TSD_FLAG_SCRAMBLE_PAGES, TSD_TARGET, TsdConfig, TsdError,
+    TsdModelCfg, TsdStats, Session, lib, library_path, make_config,
+)

@@ -1,0 +1,221 @@
+"""ctypes binding of libtsd.so.  Every function of include/tsd.h is reachable as `lib().tsd_*`
+with plain pointers; `Session` bundles the calls with torch-owned device memory (torch is used
+for allocation and streams only; every step of the method runs inside the library's kernels)."""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+TSD_F32, TSD_BF16 = 0, 1
+TSD_TARGET, TSD_DRAFT = 0, 1
+TSD_FLAG_SCRAMBLE_PAGES, TSD_FLAG_NO_TEMPERING = 1, 2
+
+
+class TsdModelCfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ff", C.c_int32),
+                ("n_experts", C.c_int32), ("top_k", C.c_int32)]
+
+
+class TsdConfig(C.Structure):
+    _fields_ = [("target", TsdModelCfg), ("draft", TsdModelCfg), ("patch", C.c_int32), ("K", C.c_int32),
+                ("max_batch", C.c_int32), ("max_tokens", C.c_int32), ("dtype", C.c_int32), ("page_tokens", C.c_int32),
+                ("sigma_p", C.c_float), ("sigma_q", C.c_float), ("fallback_r", C.c_float), ("flags", C.c_uint32),
+                ("seed", C.c_uint64)]
+
+
+class TsdStats(C.Structure):
+    _fields_ = [("rounds", C.c_int64), ("tested", C.c_int64), ("accepted", C.c_int64), ("committed", C.c_int64),
+                ("near_ties", C.c_int64)]
+
+
+class TsdError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"libtsd error {code}: {msg}")
+        self.code = code
+
+
+SYMBOLS = {
+    "tsd_abi_version": ([], C.c_int),
+    "tsd_last_error": ([C.c_void_p], C.c_char_p),
+    "tsd_workspace_bytes": ([C.POINTER(TsdConfig), C.POINTER(C.c_size_t)], C.c_int),
+    "tsd_weights_count": ([C.POINTER(TsdConfig), C.c_int, C.POINTER(C.c_size_t)], C.c_int),
+    "tsd_create": ([C.POINTER(TsdConfig), C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)], C.c_int),
+    "tsd_destroy": ([C.c_void_p], C.c_int),
+    "tsd_load_weights": ([C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
+    "tsd_prefill": ([C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p], C.c_int),
+    "tsd_reset_decode": ([C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_draft_propose": ([C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_target_verify": ([C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_accept_commit": ([C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_round": ([C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_target_step": ([C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_num_active": ([C.c_void_p, C.POINTER(C.c_int32), C.c_void_p], C.c_int),
+    "tsd_get_forecast": ([C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_get_round_io": ([C.c_void_p] + [C.c_void_p] * 6 + [C.c_void_p], C.c_int),
+    "tsd_set_round_io": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_get_state": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_get_stats": ([C.c_void_p, C.POINTER(TsdStats), C.c_void_p], C.c_int),
+    "tsd_set_accept_override": ([C.c_void_p, C.c_float], C.c_int),
+    "tsd_set_sigma": ([C.c_void_p, C.c_float, C.c_float], C.c_int),
+}
+
+_lib = None
+
+
+def library_path():
+    return os.path.join(HERE, "libtsd.so")
+
+
+def lib():
+    """Load libtsd.so (building it first only if it does not exist).  Raises if unavailable:
+    there is no fallback implementation."""
+    global _lib
+    if _lib is None:
+        path = library_path()
+        if not os.path.exists(path):
+            from . import build as _build
+            _build.build(verbose=False)
+        handle = C.CDLL(path)
+        for name, (argtypes, restype) in SYMBOLS.items():
+            fn = getattr(handle, name)
+            fn.argtypes, fn.restype = argtypes, restype
+        _lib = handle
+    return _lib
+
+
+def make_config(target, draft, patch, K, max_batch, max_tokens, dtype, sigma_p, sigma_q=None, seed=0,
+                page_tokens=16, flags=0):
+    """target/draft: objects with n_layers, d_model, n_heads, d_ff, n_experts, top_k."""
+    mk = lambda m: TsdModelCfg(m.n_layers, m.d_model, m.n_heads, m.d_ff, getattr(m, "n_experts", 0), getattr(m, "top_k", 0))
+    dt = {"fp32": TSD_F32, "bf16": TSD_BF16}.get(dtype, dtype)
+    return TsdConfig(mk(target), mk(draft), patch, K, max_batch, max_tokens, dt, page_tokens, sigma_p,
+                     sigma_p if sigma_q is None else sigma_q, 0.0, flags, seed)
+
+
+def _check(rc, ctx=None):
+    if rc != 0:
+        msg = lib().tsd_last_error(ctx)
+        raise TsdError(rc, msg.decode() if msg else "")
+
+
+class Session:
+    """One libtsd handle plus the torch-owned device memory behind it."""
+
+    def __init__(self, cfg, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        L = lib()
+        n = C.c_size_t()
+        _check(L.tsd_workspace_bytes(C.byref(cfg), C.byref(n)))
+        self.arena_bytes = n.value
+        self.arena = torch.empty(n.value + 256, dtype=torch.uint8, device=self.device)
+        base = (self.arena.data_ptr() + 255) & ~255
+        h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(L.tsd_create(C.byref(cfg), base, n.value, C.byref(h)))
+        self.h = h
+        self.B = 0
+        self.H = 0
+
+    def _stream(self):
+        return self.torch.cuda.current_stream(self.device).cuda_stream
+
+    def close(self):
+        if self.h:
+            _check(lib().tsd_destroy(self.h))
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def weights_count(self, which):
+        n = C.c_size_t()
+        _check(lib().tsd_weights_count(C.byref(self.cfg), which, C.byref(n)))
+        return n.value
+
+    def load_weights(self, which, blob):
+        """blob: float32 torch tensor on the device (or numpy array, copied over)."""
+        torch = self.torch
+        if not isinstance(blob, torch.Tensor):
+            blob = torch.from_numpy(blob)
+        blob = blob.to(self.device, torch.float32).contiguous()
+        _check(lib().tsd_load_weights(self.h, which, blob.data_ptr(), blob.numel(), self._stream()), self.h)
+        torch.cuda.current_stream(self.device).synchronize()  # blob may be freed after this
+
+    def prefill(self, series, n_ctx_patches, horizon_steps):
+        torch = self.torch
+        if not isinstance(series, torch.Tensor):
+            series = torch.from_numpy(series)
+        self.series = series.to(self.device, torch.float32).contiguous()
+        self.B, self.H = self.series.shape[0], horizon_steps
+        _check(lib().tsd_prefill(self.h, self.series.data_ptr(), self.B, n_ctx_patches, horizon_steps, self._stream()), self.h)
+
+    def reset_decode(self):
+        _check(lib().tsd_reset_decode(self.h, self._stream()), self.h)
+
+    def draft_propose(self):
+        _check(lib().tsd_draft_propose(self.h, self._stream()), self.h)
+
+    def target_verify(self):
+        _check(lib().tsd_target_verify(self.h, self._stream()), self.h)
+
+    def accept_commit(self, forced_len=None):
+        ptr = None
+        if forced_len is not None:
+            self._forced = forced_len.to(self.device, self.torch.int32).contiguous()
+            ptr = self._forced.data_ptr()
+        _check(lib().tsd_accept_commit(self.h, ptr, self._stream()), self.h)
+
+    def round(self):
+        _check(lib().tsd_round(self.h, self._stream()), self.h)
+
+    def target_step(self):
+        _check(lib().tsd_target_step(self.h, self._stream()), self.h)
+
+    def num_active(self):
+        n = C.c_int32()
+        _check(lib().tsd_num_active(self.h, C.byref(n), self._stream()), self.h)
+        return n.value
+
+    def get_forecast(self):
+        out = self.torch.empty(self.B, self.H, dtype=self.torch.float32, device=self.device)
+        _check(lib().tsd_get_forecast(self.h, out.data_ptr(), self._stream()), self.h)
+        return out
+
+    def get_round_io(self):
+        torch, B, K, P = self.torch, self.B, self.cfg.K, self.cfg.patch
+        f = lambda *s: torch.empty(*s, dtype=torch.float32, device=self.device)
+        X, mu_q, mu_p, ell, logu = f(B, K, P), f(B, K, P), f(B, K + 1, P), f(B, K), f(B, K)
+        n_acc = torch.empty(B, dtype=torch.int32, device=self.device)
+        _check(lib().tsd_get_round_io(self.h, X.data_ptr(), mu_q.data_ptr(), mu_p.data_ptr(), n_acc.data_ptr(),
+                                      ell.data_ptr(), logu.data_ptr(), self._stream()), self.h)
+        return dict(X=X, mu_q=mu_q, mu_p=mu_p, n_acc=n_acc, ell=ell, logu=logu)
+
+    def set_round_io(self, X, mu_q, mu_p):
+        torch = self.torch
+        self._inj = [t.to(self.device, torch.float32).contiguous() for t in (X, mu_q, mu_p)]
+        _check(lib().tsd_set_round_io(self.h, *[t.data_ptr() for t in self._inj], self._stream()), self.h)
+
+    def get_state(self):
+        torch, B, P = self.torch, self.B, self.cfg.patch
+        ln = torch.empty(B, dtype=torch.int32, device=self.device)
+        cm = torch.empty(B, dtype=torch.int32, device=self.device)
+        pend = torch.empty(B, P, dtype=torch.float32, device=self.device)
+        _check(lib().tsd_get_state(self.h, ln.data_ptr(), cm.data_ptr(), pend.data_ptr(), self._stream()), self.h)
+        return dict(len=ln, committed=cm, pending=pend)
+
+    def get_stats(self):
+        s = TsdStats()
+        _check(lib().tsd_get_stats(self.h, C.byref(s), self._stream()), self.h)
+        return {k: getattr(s, k) for k, _ in TsdStats._fields_}
+
+    def set_accept_override(self, alpha):
+        _check(lib().tsd_set_accept_override(self.h, alpha), self.h)
+
+    def set_sigma(self, sigma_p, sigma_q=None):
+        _check(lib().tsd_set_sigma(self.h, sigma_p, sigma_p if sigma_q is None else sigma_q), self.h)

@@ -1,0 +1,274 @@
+// Small kernels around the transformer pass: weight packing, prefill statistics, the fused
+// acceptance / correction / commit / rollback kernel, and read-out helpers.
+#include <type_traits>
+
+#include "tsd_internal.h"
+
+namespace tsd {
+
+// ---- weight packing: out[n][k] = T(gain[k] * W[k][n]) ---------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void pack_kernel(const PackP p) {
+  __shared__ float tile[32][33];
+  const int k0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  for (int r = ty; r < 32; r += 8) {
+    int k = k0 + r, n = n0 + tx;
+    float v = 0.f;
+    if (k < p.K && n < p.N) v = p.W[(long)k * p.N + n] * (p.gain ? p.gain[k] : 1.f);
+    tile[r][tx] = v;
+  }
+  __syncthreads();
+  T* out = reinterpret_cast<T*>(p.out);
+  for (int r = ty; r < 32; r += 8) {
+    int n = n0 + r, k = k0 + tx;
+    if (k < p.K && n < p.N) out[(long)n * p.K + k] = (T)tile[tx][r];
+  }
+}
+
+hipError_t launch_pack(int dtype, const PackP& p, hipStream_t st) {
+  dim3 grid((p.N + 31) / 32, (p.K + 31) / 32), block(256);
+  if (dtype == TSD_BF16)
+    hipLaunchKernelGGL(pack_kernel<bf16>, grid, block, 0, st, p);
+  else
+    hipLaunchKernelGGL(pack_kernel<float>, grid, block, 0, st, p);
+  return hipGetLastError();
+}
+
+// ---- prefill: frozen instance statistics, normalised context, initial per-series state ------
+__device__ __forceinline__ double block_sum(double v, double* sh) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  double t = 0;
+  for (int i = 0; i < (int)(blockDim.x >> 6); ++i) t += sh[i];
+  return t;
+}
+
+__device__ __forceinline__ void init_state(const PrefillP& p, int b) {
+  p.len[b] = p.N - 1;  // context patches 0..N-2 are cached; patch N-1 is pending at position N-1
+  p.committed[b] = 0;
+  p.round[b] = 0;
+  p.active[b] = 1;
+  for (int i = 0; i < 5; ++i) p.stat[(long)b * 5 + i] = 0;
+}
+
+__global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillP p) {
+  __shared__ double sh[4];
+  const int b = blockIdx.x, n = p.N * p.P;
+  const float* x = p.series + (long)b * n;
+  double s = 0;
+  for (int i = threadIdx.x; i < n; i += 256) s += x[i];
+  const double mean = block_sum(s, sh) / n;
+  double v = 0;
+  for (int i = threadIdx.x; i < n; i += 256) {
+    double dlt = x[i] - mean;
+    v += dlt * dlt;
+  }
+  const double var = block_sum(v, sh) / n;  // population variance of the context only
+  const float mf = (float)mean, sf = (float)sqrt(var + (double)kNormEps);
+  float* z = p.znorm + (long)b * n;
+  for (int i = threadIdx.x; i < n; i += 256) z[i] = (x[i] - mf) / sf;
+  __syncthreads();
+  for (int i = threadIdx.x; i < p.P; i += 256) {
+    p.pending[(long)b * p.P + i] = z[(long)(p.N - 1) * p.P + i];
+    p.prev[(long)b * p.P + i] = z[(long)(p.N - 2) * p.P + i];
+  }
+  if (threadIdx.x == 0) {
+    p.mean[b] = mf;
+    p.sdev[b] = sf;
+    init_state(p, b);
+  }
+}
+
+__global__ __launch_bounds__(256) void reset_kernel(const PrefillP p) {
+  const int b = blockIdx.x, n = p.N * p.P;
+  const float* z = p.znorm + (long)b * n;
+  for (int i = threadIdx.x; i < p.P; i += 256) {
+    p.pending[(long)b * p.P + i] = z[(long)(p.N - 1) * p.P + i];
+    p.prev[(long)b * p.P + i] = z[(long)(p.N - 2) * p.P + i];
+  }
+  if (threadIdx.x == 0) init_state(p, b);
+}
+
+hipError_t launch_prefill_stats(const PrefillP& p, hipStream_t st) {
+  hipLaunchKernelGGL(prefill_stats_kernel, dim3(p.B), dim3(256), 0, st, p);
+  return hipGetLastError();
+}
+hipError_t launch_reset(const PrefillP& p, hipStream_t st) {
+  hipLaunchKernelGGL(reset_kernel, dim3(p.B), dim3(256), 0, st, p);
+  return hipGetLastError();
+}
+
+// ---- acceptance + correction + commit + rollback ---------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11): counter (c0..c3), key (k0, k1); returns output word 0.
+__device__ __forceinline__ unsigned philox_word0(unsigned c0, unsigned c1, unsigned c2, unsigned c3, unsigned k0,
+                                                 unsigned k1) {
+  const unsigned M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    unsigned hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+    unsigned hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0;
+    c1 = lo1;
+    c2 = n2;
+    c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return c0;
+}
+
+// One wavefront per series.  Energies are reduced across lanes per proposal, then lane i owns
+// proposal i+1: statistic, uniform, test; a ballot over the reject flags gives the first
+// rejection.  The same wavefront then writes the committed patches, the new pending / previous
+// tokens and the cache lengths (rollback is metadata only: speculative KV entries past the
+// accepted length are simply overwritten by the next round).
+__global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const int K = p.K, P = p.P;
+  const int KE = K > 0 ? K : 1;
+  if (!p.active[b]) {
+    if (lane == 0) p.n_acc[b] = -1;
+    if (lane < K) {
+      p.ell[(long)b * KE + lane] = NAN;
+      p.logu[(long)b * KE + lane] = NAN;
+    }
+    return;
+  }
+  const int r = p.round[b];
+  const float* X = p.X + (long)b * K * P;
+  const float* MQ = p.mu_q + (long)b * K * P;
+  const float* MP = p.mu_p + (long)b * (K + 1) * P;
+  float my_ep = 0.f, my_eq = 0.f;
+  for (int i = 0; i < K; ++i) {
+    float ep = 0.f, eq = 0.f;
+    for (int e = lane; e < P; e += 64) {
+      float x = X[i * P + e];
+      float dp = x - MP[i * P + e], dq = x - MQ[i * P + e];
+      ep = fmaf(dp, dp, ep);
+      eq = fmaf(dq, dq, eq);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      ep += __shfl_xor(ep, o);
+      eq += __shfl_xor(eq, o);
+    }
+    if (lane == i) {
+      my_ep = ep;
+      my_eq = eq;
+    }
+  }
+  bool reject = false;
+  float ell = NAN, logu = NAN, thr = 0.f;
+  if (lane < K) {
+    // Eq. 5 with per-dimension energies ||.||^2 / P
+    ell = p.temper * (-(my_ep / (float)P) * p.inv2sp2 + (my_eq / (float)P) * p.inv2sq2 + p.logdet);
+    unsigned w = philox_word0((unsigned)b, (unsigned)r, (unsigned)(lane + 1), 0u, p.key0, p.key1);
+    float u = ((float)(w >> 9) + 0.5f) * 1.1920928955078125e-07f;  // 2^-23; exact in fp32
+    logu = logf(u);
+    thr = (p.log_alpha_override <= 0.f) ? p.log_alpha_override : fminf(0.f, ell);
+    reject = !(logu <= thr);
+  }
+  const unsigned long long rej = __ballot(reject);
+  const int n_free = rej ? (int)__builtin_ctzll(rej) : K;  // leading accepts
+  const int tested = n_free + (n_free < K ? 1 : 0);
+  const bool is_tested = lane < tested;
+  const unsigned long long near = __ballot(is_tested && fabsf(thr - logu) < 1e-4f);
+  if (lane < K) {
+    p.ell[(long)b * KE + lane] = is_tested ? ell : NAN;
+    p.logu[(long)b * KE + lane] = is_tested ? logu : NAN;
+  }
+  int n = n_free;
+  if (p.forced) {
+    int f = p.forced[b];
+    if (f >= 0 && f <= K) n = f;
+  }
+  const int c0 = p.committed[b];
+  const int L = n + 1;
+  const int Lc = min(L, p.T - c0);
+  float* fc = p.forecast + ((long)b * p.T + c0) * P;
+  for (int j = 0; j < Lc; ++j) {
+    const float* src = (j < n) ? X + j * P : MP + n * P;
+    for (int e = lane; e < P; e += 64) fc[j * P + e] = src[e];
+  }
+  for (int e = lane; e < P; e += 64) {
+    float old_pending = p.pending[(long)b * P + e];
+    p.prev[(long)b * P + e] = (n >= 1) ? X[(n - 1) * P + e] : old_pending;
+    p.pending[(long)b * P + e] = MP[n * P + e];
+  }
+  if (lane == 0) {
+    p.n_acc[b] = n_free;
+    p.len[b] += Lc;
+    p.committed[b] = c0 + Lc;
+    p.round[b] = r + 1;
+    p.active[b] = (c0 + Lc < p.T) ? 1 : 0;
+    long long* st = p.stat + (long)b * 5;
+    st[0] += 1;
+    st[1] += tested;
+    st[2] += n_free;
+    st[3] += Lc;
+    st[4] += __popcll(near);
+  }
+}
+
+hipError_t launch_accept(const AcceptP& p, hipStream_t st) {
+  hipLaunchKernelGGL(accept_kernel, dim3(p.B), dim3(64), 0, st, p);
+  return hipGetLastError();
+}
+
+// ---- read-out helpers ------------------------------------------------------------------------
+__global__ void forecast_out_kernel(const float* forecast, const float* mean, const float* sdev, const int* committed,
+                                    float* out, int P, int T, int H) {
+  const int b = blockIdx.x;
+  const int have = committed[b] * P;
+  for (int t = threadIdx.x; t < H; t += blockDim.x)
+    out[(long)b * H + t] = t < have ? forecast[(long)b * T * P + t] * sdev[b] + mean[b] : 0.f;
+}
+hipError_t launch_forecast_out(const float* forecast, const float* mean, const float* sdev, const int* committed,
+                               float* out, int B, int P, int T, int H, hipStream_t st) {
+  hipLaunchKernelGGL(forecast_out_kernel, dim3(B), dim3(256), 0, st, forecast, mean, sdev, committed, out, P, T, H);
+  return hipGetLastError();
+}
+
+__global__ void count_active_kernel(const int* active, int B, int* out) {
+  int c = 0;
+  for (int i = threadIdx.x; i < B; i += 64) c += active[i] ? 1 : 0;
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) c += __shfl_xor(c, o);
+  if (threadIdx.x == 0) *out = c;
+}
+hipError_t launch_count_active(const int* active, int B, int* out, hipStream_t st) {
+  hipLaunchKernelGGL(count_active_kernel, dim3(1), dim3(64), 0, st, active, B, out);
+  return hipGetLastError();
+}
+
+__global__ void sum_stats_kernel(const long long* stat, int B, long long* out5) {
+  long long c[5] = {0, 0, 0, 0, 0};
+  for (int i = threadIdx.x; i < B; i += 64)
+    for (int j = 0; j < 5; ++j) c[j] += stat[(long)i * 5 + j];
+  for (int j = 0; j < 5; ++j) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) c[j] += __shfl_xor(c[j], o);
+    if (threadIdx.x == 0) out5[j] = c[j];
+  }
+}
+hipError_t launch_sum_stats(const long long* stat, int B, long long* out5, hipStream_t st) {
+  hipLaunchKernelGGL(sum_stats_kernel, dim3(1), dim3(64), 0, st, stat, B, out5);
+  return hipGetLastError();
+}
+
+__global__ void fill_nan_kernel(float* p, long n) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = NAN;
+}
+hipError_t launch_fill_nan(float* p, long n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_nan_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n);
+  return hipGetLastError();
+}
+
+}  // namespace tsd

@@ -1,0 +1,770 @@
+// Host side of libtsd: argument validation, arena carving, weight loading, and the sequencing of
+// kernel launches that make up prefill, draft proposal, single-pass verification, acceptance and
+// the target-only baseline step.  Nothing here allocates device memory.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <random>
+
+#include "tsd_internal.h"
+
+using namespace tsd;
+
+namespace {
+
+thread_local std::string g_err;  // errors of calls that have no handle
+
+struct Layer {
+  char *Wqkv, *Wo, *W1, *W2;
+};
+struct ModelDev {
+  tsd_model_cfg c;
+  int hd;
+  char* W_e;
+  char* W_h;
+  std::vector<Layer> layers;
+  float *rope_cos, *rope_sin;
+  char* kv_pool;
+  size_t layer_pool_bytes;
+  bool loaded;
+};
+
+struct Plan {  // byte offsets into the arena
+  size_t total;
+};
+
+}  // namespace
+
+struct tsd_ctx {
+  tsd_config cfg;
+  int es;  // bytes per element of the compute dtype
+  char* arena;
+  size_t arena_bytes;
+  ModelDev model[2];
+  int pages_per_series, n_pages;
+  int* page_table;
+  int *len, *committed, *round, *active, *n_acc;
+  float *mean, *sdev, *pending, *prev, *forecast, *znorm;
+  long long* stat;
+  float *X, *mu_q, *mu_p, *ell, *logu;
+  float* x;
+  char *qbuf, *abuf, *hbuf;
+  int rows_max;
+  int* count_out;
+  long long* stats_out;
+  // forecast in flight
+  bool prefilled;
+  int B, N, T, H;
+  bool injected;  // next accept reads mu_q from its own buffer
+  float alpha_override;
+  std::vector<int> host_pt;
+  std::string err;
+};
+
+namespace {
+
+int fail(tsd_ctx* ctx, int code, const std::string& msg) {
+  if (ctx)
+    ctx->err = msg;
+  else
+    g_err = msg;
+  return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                        \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess) return fail(ctx, TSD_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+int check_model(const tsd_model_cfg& m, const char* name, std::string& why) {
+  auto bad = [&](const char* w) {
+    why = std::string(name) + ": " + w;
+    return TSD_E_INVALID_ARG;
+  };
+  if (m.n_layers < 1 || m.n_layers > 256) return bad("n_layers must be in 1..256");
+  if (m.d_model < 16 || m.d_model % 8) return bad("d_model must be a positive multiple of 8");
+  if (m.n_heads < 1 || m.d_model % m.n_heads) return bad("n_heads must divide d_model");
+  int hd = m.d_model / m.n_heads;
+  if (hd != 16 && hd != 32 && hd != 64) return bad("head_dim must be 16, 32 or 64");
+  if (m.d_ff < 8 || m.d_ff % 8) return bad("d_ff must be a positive multiple of 8");
+  if (m.n_experts != 0) return bad("routed FFN (n_experts > 0) is not supported by this build");
+  return TSD_OK;
+}
+
+int check_config(const tsd_config* c, std::string& why) {
+  if (!c) {
+    why = "cfg is NULL";
+    return TSD_E_INVALID_ARG;
+  }
+  auto bad = [&](const char* w) {
+    why = w;
+    return TSD_E_INVALID_ARG;
+  };
+  int rc;
+  if ((rc = check_model(c->target, "target", why))) return rc;
+  if ((rc = check_model(c->draft, "draft", why))) return rc;
+  if (c->patch < 8 || c->patch % 8 || c->patch > 1024) return bad("patch must be a multiple of 8 in 8..1024");
+  if (c->K < 1 || c->K > 16) return bad("K must be in 1..16");
+  if (c->max_batch < 1 || c->max_batch > (1 << 20)) return bad("max_batch out of range");
+  if (c->max_tokens < c->K + 3 || c->max_tokens > 1024) return bad("max_tokens must be in K+3..1024");
+  if (c->dtype != TSD_F32 && c->dtype != TSD_BF16) return bad("dtype must be TSD_F32 or TSD_BF16");
+  if (!is_pow2(c->page_tokens) || c->page_tokens > 64) return bad("page_tokens must be a power of two <= 64");
+  if (!(c->sigma_p > 0.f) || !(c->sigma_q > 0.f) || !std::isfinite(c->sigma_p) || !std::isfinite(c->sigma_q))
+    return bad("sigma_p and sigma_q must be positive and finite");
+  if (c->fallback_r != 0.f) return bad("fallback_r must be 0 (target-mean fallback)");
+  if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING)) return bad("unknown flag bits");
+  return TSD_OK;
+}
+
+struct Carver {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    off = (off + 255) & ~(size_t)255;
+    size_t r = off;
+    off += bytes;
+    return r;
+  }
+};
+
+// Lays out everything the handle needs inside the arena.  With ctx == nullptr only sizes it.
+size_t carve(const tsd_config& c, tsd_ctx* ctx) {
+  Carver cv;
+  char* base = ctx ? ctx->arena : nullptr;
+  const size_t es = c.dtype == TSD_BF16 ? 2 : 4;
+  const int P = c.patch, B = c.max_batch, K = c.K;
+  const int pps = (c.max_tokens + c.page_tokens - 1) / c.page_tokens;
+  const size_t n_pages = (size_t)B * pps;
+  auto at = [&](size_t off) { return base ? base + off : nullptr; };
+  for (int w = 0; w < 2; ++w) {
+    const tsd_model_cfg& m = w == 0 ? c.target : c.draft;
+    const size_t D = m.d_model, F = m.d_ff;
+    const int hd = m.d_model / m.n_heads;
+    ModelDev* md = ctx ? &ctx->model[w] : nullptr;
+    size_t o = cv.take(P * D * es);
+    if (md) {
+      md->c = m;
+      md->hd = hd;
+      md->W_e = at(o);
+      md->layers.resize(m.n_layers);
+      md->loaded = false;
+    }
+    for (int l = 0; l < m.n_layers; ++l) {
+      size_t oq = cv.take(3 * D * D * es), oo = cv.take(D * D * es), o1 = cv.take(D * F * es), o2 = cv.take(F * D * es);
+      if (md) md->layers[l] = Layer{at(oq), at(oo), at(o1), at(o2)};
+    }
+    o = cv.take(D * P * es);
+    if (md) md->W_h = at(o);
+    size_t oc = cv.take((size_t)c.max_tokens * (hd / 2) * 4), os = cv.take((size_t)c.max_tokens * (hd / 2) * 4);
+    if (md) {
+      md->rope_cos = (float*)at(oc);
+      md->rope_sin = (float*)at(os);
+    }
+    const size_t layer_pool = n_pages * 2 * c.page_tokens * D * es;
+    o = cv.take(layer_pool * m.n_layers);
+    if (md) {
+      md->kv_pool = at(o);
+      md->layer_pool_bytes = layer_pool;
+    }
+  }
+  size_t o_pt = cv.take(n_pages * 4);
+  size_t o_len = cv.take(B * 4), o_com = cv.take(B * 4), o_rnd = cv.take(B * 4), o_act = cv.take(B * 4), o_nacc = cv.take(B * 4);
+  size_t o_mean = cv.take(B * 4), o_sdev = cv.take(B * 4);
+  size_t o_pend = cv.take((size_t)B * P * 4), o_prev = cv.take((size_t)B * P * 4);
+  size_t o_fc = cv.take((size_t)B * c.max_tokens * P * 4), o_zn = cv.take((size_t)B * c.max_tokens * P * 4);
+  size_t o_stat = cv.take((size_t)B * 5 * 8);
+  size_t o_X = cv.take((size_t)B * K * P * 4), o_mq = cv.take((size_t)B * K * P * 4), o_mp = cv.take((size_t)B * (K + 1) * P * 4);
+  size_t o_ell = cv.take((size_t)B * K * 4), o_logu = cv.take((size_t)B * K * 4);
+  const size_t Dm = std::max(c.target.d_model, c.draft.d_model), Fm = std::max(c.target.d_ff, c.draft.d_ff);
+  const size_t rows = std::max((size_t)B * (K + 1), (size_t)c.max_tokens);
+  size_t o_x = cv.take(rows * Dm * 4), o_q = cv.take(rows * Dm * es), o_a = cv.take(rows * Dm * es), o_h = cv.take(rows * Fm * es);
+  size_t o_cnt = cv.take(256), o_so = cv.take(256);
+  if (ctx) {
+    ctx->es = (int)es;
+    ctx->pages_per_series = pps;
+    ctx->n_pages = (int)n_pages;
+    ctx->page_table = (int*)at(o_pt);
+    ctx->len = (int*)at(o_len);
+    ctx->committed = (int*)at(o_com);
+    ctx->round = (int*)at(o_rnd);
+    ctx->active = (int*)at(o_act);
+    ctx->n_acc = (int*)at(o_nacc);
+    ctx->mean = (float*)at(o_mean);
+    ctx->sdev = (float*)at(o_sdev);
+    ctx->pending = (float*)at(o_pend);
+    ctx->prev = (float*)at(o_prev);
+    ctx->forecast = (float*)at(o_fc);
+    ctx->znorm = (float*)at(o_zn);
+    ctx->stat = (long long*)at(o_stat);
+    ctx->X = (float*)at(o_X);
+    ctx->mu_q = (float*)at(o_mq);
+    ctx->mu_p = (float*)at(o_mp);
+    ctx->ell = (float*)at(o_ell);
+    ctx->logu = (float*)at(o_logu);
+    ctx->x = (float*)at(o_x);
+    ctx->qbuf = at(o_q);
+    ctx->abuf = at(o_a);
+    ctx->hbuf = at(o_h);
+    ctx->rows_max = (int)rows;
+    ctx->count_out = (int*)at(o_cnt);
+    ctx->stats_out = (long long*)at(o_so);
+  }
+  return (cv.off + 255) & ~(size_t)255;
+}
+
+size_t weights_count(const tsd_model_cfg& m, int P) {
+  size_t D = m.d_model, F = m.d_ff;
+  size_t per_layer = D + 4 * D * D + D + 2 * D * F;
+  return (size_t)P * D + per_layer * m.n_layers + D + D * P;
+}
+
+struct Pass {
+  int which;
+  int B, s0, nq;
+  const int* base_pos;
+  int pos_off;
+  const float *src0, *src1;
+  long stride0, stride1;
+  int n0;
+  float* out;  // NULL = skip the head
+  long out_stride_b;
+  int t_skip;
+};
+
+// One causal pass of `nq` new tokens per series through a model, against its paged KV cache.
+int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
+  const tsd_config& c = ctx->cfg;
+  ModelDev& md = ctx->model[ps.which];
+  const int D = md.c.d_model, F = md.c.d_ff, P = c.patch, M = ps.B * ps.nq;
+  if (M > ctx->rows_max) return fail(ctx, TSD_E_OUT_OF_RANGE, "pass exceeds the activation workspace");
+  GemmP g;
+  std::memset(&g, 0, sizeof(g));
+  g.M = M;
+  g.nq = ps.nq;
+  // patch embedding
+  g.N = D;
+  g.K = P;
+  g.src0 = ps.src0;
+  g.src1 = ps.src1;
+  g.stride0 = ps.stride0;
+  g.stride1 = ps.stride1;
+  g.n0 = ps.n0;
+  g.W = md.W_e;
+  g.Cf = ctx->x;
+  HIP_TRY(ctx, launch_gemm(c.dtype, A_TOK, EP_STORE, g, st));
+  for (int l = 0; l < md.c.n_layers; ++l) {
+    char* pool = md.kv_pool + (size_t)l * md.layer_pool_bytes;
+    GemmP q;
+    std::memset(&q, 0, sizeof(q));
+    q.M = M;
+    q.nq = ps.nq;
+    q.N = 3 * D;
+    q.K = D;
+    q.A = ctx->x;
+    q.W = md.layers[l].Wqkv;
+    q.q_out = ctx->qbuf;
+    q.kv_pool = pool;
+    q.page_table = ctx->page_table;
+    q.pt_stride = ctx->pages_per_series;
+    q.base_pos = ps.base_pos;
+    q.pos_off = ps.pos_off;
+    q.s0 = ps.s0;
+    q.rope_cos = md.rope_cos;
+    q.rope_sin = md.rope_sin;
+    q.D = D;
+    q.Hh = md.c.n_heads;
+    q.hd = md.hd;
+    q.PT = c.page_tokens;
+    HIP_TRY(ctx, launch_gemm(c.dtype, A_NORM, EP_QKV, q, st));
+    AttnP a;
+    std::memset(&a, 0, sizeof(a));
+    a.q = ctx->qbuf;
+    a.out = ctx->abuf;
+    a.kv_pool = pool;
+    a.page_table = ctx->page_table;
+    a.pt_stride = ctx->pages_per_series;
+    a.base_pos = ps.base_pos;
+    a.pos_off = ps.pos_off;
+    a.s0 = ps.s0;
+    a.nq = ps.nq;
+    a.B = ps.B;
+    a.Hh = md.c.n_heads;
+    a.hd = md.hd;
+    a.D = D;
+    a.PT = c.page_tokens;
+    a.scale = 1.0f / std::sqrt((float)md.hd);
+    HIP_TRY(ctx, launch_attention(c.dtype, a, c.max_tokens, st));
+    GemmP o;
+    std::memset(&o, 0, sizeof(o));
+    o.M = M;
+    o.nq = ps.nq;
+    o.N = D;
+    o.K = D;
+    o.A = ctx->abuf;
+    o.W = md.layers[l].Wo;
+    o.Cf = ctx->x;
+    HIP_TRY(ctx, launch_gemm(c.dtype, A_ACT, EP_RESID, o, st));
+    GemmP f1;
+    std::memset(&f1, 0, sizeof(f1));
+    f1.M = M;
+    f1.nq = ps.nq;
+    f1.N = F;
+    f1.K = D;
+    f1.A = ctx->x;
+    f1.W = md.layers[l].W1;
+    f1.Ct = ctx->hbuf;
+    HIP_TRY(ctx, launch_gemm(c.dtype, A_NORM, EP_GELU, f1, st));
+    GemmP f2;
+    std::memset(&f2, 0, sizeof(f2));
+    f2.M = M;
+    f2.nq = ps.nq;
+    f2.N = D;
+    f2.K = F;
+    f2.A = ctx->hbuf;
+    f2.W = md.layers[l].W2;
+    f2.Cf = ctx->x;
+    HIP_TRY(ctx, launch_gemm(c.dtype, A_ACT, EP_RESID, f2, st));
+  }
+  if (ps.out) {
+    GemmP h;
+    std::memset(&h, 0, sizeof(h));
+    h.M = M;
+    h.nq = ps.nq;
+    h.N = P;
+    h.K = D;
+    h.A = ctx->x;
+    h.W = md.W_h;
+    h.out = ps.out;
+    h.out_stride_b = ps.out_stride_b;
+    h.t_skip = ps.t_skip;
+    HIP_TRY(ctx, launch_gemm(c.dtype, A_NORM, EP_HEAD, h, st));
+  }
+  return TSD_OK;
+}
+
+int require_ready(tsd_ctx* ctx, bool need_prefill) {
+  if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
+  if (need_prefill) {
+    if (!ctx->model[0].loaded || !ctx->model[1].loaded) return fail(ctx, TSD_E_BAD_STATE, "weights of both models must be loaded first");
+    if (!ctx->prefilled) return fail(ctx, TSD_E_BAD_STATE, "tsd_prefill has not been called");
+  }
+  return TSD_OK;
+}
+
+int accept_commit_impl(tsd_ctx* ctx, const int32_t* forced, int K, hipStream_t st) {
+  const tsd_config& c = ctx->cfg;
+  AcceptP a;
+  std::memset(&a, 0, sizeof(a));
+  a.X = ctx->X;
+  a.mu_q = ctx->injected ? ctx->mu_q : ctx->X;  // mean-propagating scheme: x_i = mu_q^(i)
+  a.mu_p = ctx->mu_p;
+  a.forced = forced;
+  a.pending = ctx->pending;
+  a.prev = ctx->prev;
+  a.forecast = ctx->forecast;
+  a.len = ctx->len;
+  a.committed = ctx->committed;
+  a.round = ctx->round;
+  a.active = ctx->active;
+  a.n_acc = ctx->n_acc;
+  a.ell = ctx->ell;
+  a.logu = ctx->logu;
+  a.stat = ctx->stat;
+  a.B = ctx->B;
+  a.K = K;
+  a.P = c.patch;
+  a.T = ctx->T;
+  a.inv2sp2 = 1.0f / (2.0f * c.sigma_p * c.sigma_p);
+  a.inv2sq2 = 1.0f / (2.0f * c.sigma_q * c.sigma_q);
+  a.logdet = 0.5f * std::log((c.sigma_q * c.sigma_q) / (c.sigma_p * c.sigma_p));
+  a.temper = (c.flags & TSD_FLAG_NO_TEMPERING) ? (float)c.patch : 1.0f;
+  a.log_alpha_override = ctx->alpha_override > 0.f ? std::log(ctx->alpha_override) : 1.0f;
+  a.key0 = (unsigned)(c.seed & 0xFFFFFFFFull);
+  a.key1 = (unsigned)(c.seed >> 32);
+  HIP_TRY(ctx, launch_accept(a, st));
+  ctx->injected = false;
+  return TSD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tsd_abi_version(void) { return 1; }
+
+const char* tsd_last_error(tsd_ctx* ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+int tsd_workspace_bytes(const tsd_config* cfg, size_t* bytes_host) {
+  std::string why;
+  int rc = check_config(cfg, why);
+  if (rc) return fail(nullptr, rc, why);
+  if (!bytes_host) return fail(nullptr, TSD_E_INVALID_ARG, "bytes_host is NULL");
+  *bytes_host = carve(*cfg, nullptr);
+  return TSD_OK;
+}
+
+int tsd_weights_count(const tsd_config* cfg, int which, size_t* n_floats_host) {
+  std::string why;
+  int rc = check_config(cfg, why);
+  if (rc) return fail(nullptr, rc, why);
+  if (which != TSD_TARGET && which != TSD_DRAFT) return fail(nullptr, TSD_E_INVALID_ARG, "which must be TSD_TARGET or TSD_DRAFT");
+  if (!n_floats_host) return fail(nullptr, TSD_E_INVALID_ARG, "n_floats_host is NULL");
+  *n_floats_host = weights_count(which == TSD_TARGET ? cfg->target : cfg->draft, cfg->patch);
+  return TSD_OK;
+}
+
+int tsd_create(const tsd_config* cfg, void* arena_dev, size_t arena_bytes, tsd_ctx** out) {
+  std::string why;
+  int rc = check_config(cfg, why);
+  if (rc) return fail(nullptr, rc, why);
+  if (!out) return fail(nullptr, TSD_E_INVALID_ARG, "out is NULL");
+  *out = nullptr;
+  if (!arena_dev) return fail(nullptr, TSD_E_INVALID_ARG, "arena_dev is NULL");
+  if ((uintptr_t)arena_dev & 255) return fail(nullptr, TSD_E_INVALID_ARG, "arena_dev must be 256-byte aligned");
+  size_t need = carve(*cfg, nullptr);
+  if (arena_bytes < need) return fail(nullptr, TSD_E_INVALID_ARG, "arena smaller than tsd_workspace_bytes");
+  tsd_ctx* ctx = new (std::nothrow) tsd_ctx();
+  if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "out of host memory");
+  ctx->cfg = *cfg;
+  ctx->arena = (char*)arena_dev;
+  ctx->arena_bytes = arena_bytes;
+  ctx->prefilled = false;
+  ctx->injected = false;
+  ctx->alpha_override = -1.f;
+  ctx->B = ctx->N = ctx->T = ctx->H = 0;
+  carve(*cfg, ctx);
+  // rotary tables: angle(pos, i) = pos * base^(-2 i / hd), computed in double
+  for (int w = 0; w < 2; ++w) {
+    ModelDev& md = ctx->model[w];
+    const int half = md.hd / 2;
+    std::vector<float> cs((size_t)cfg->max_tokens * half), sn(cs.size());
+    for (int pos = 0; pos < cfg->max_tokens; ++pos)
+      for (int i = 0; i < half; ++i) {
+        double ang = (double)pos * std::pow(kRopeBase, -2.0 * i / md.hd);
+        cs[(size_t)pos * half + i] = (float)std::cos(ang);
+        sn[(size_t)pos * half + i] = (float)std::sin(ang);
+      }
+    hipError_t e = hipMemcpy(md.rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(md.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+      std::string msg = std::string("copying rotary tables: ") + hipGetErrorString(e);
+      delete ctx;
+      return fail(nullptr, TSD_E_HIP, msg);
+    }
+  }
+  *out = ctx;
+  return TSD_OK;
+}
+
+int tsd_destroy(tsd_ctx* ctx) {
+  if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
+  hipError_t e = hipDeviceSynchronize();
+  delete ctx;
+  if (e != hipSuccess) return fail(nullptr, TSD_E_HIP, std::string("hipDeviceSynchronize: ") + hipGetErrorString(e));
+  return TSD_OK;
+}
+
+int tsd_load_weights(tsd_ctx* ctx, int which, const float* blob_dev, size_t n_floats, void* stream) {
+  if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
+  if (which != TSD_TARGET && which != TSD_DRAFT) return fail(ctx, TSD_E_INVALID_ARG, "which must be TSD_TARGET or TSD_DRAFT");
+  if (!blob_dev) return fail(ctx, TSD_E_INVALID_ARG, "blob_dev is NULL");
+  ModelDev& md = ctx->model[which];
+  const tsd_config& c = ctx->cfg;
+  if (n_floats != weights_count(md.c, c.patch)) return fail(ctx, TSD_E_INVALID_ARG, "n_floats does not match tsd_weights_count");
+  hipStream_t st = (hipStream_t)stream;
+  const size_t D = md.c.d_model, F = md.c.d_ff, P = c.patch, es = ctx->es;
+  const float* w = blob_dev;
+  auto pack = [&](const float* W, const float* gain, void* out, int K, int N) {
+    PackP p{W, gain, out, K, N};
+    return launch_pack(c.dtype, p, st);
+  };
+  HIP_TRY(ctx, pack(w, nullptr, md.W_e, (int)P, (int)D));
+  w += P * D;
+  for (int l = 0; l < md.c.n_layers; ++l) {
+    const float* g1 = w;
+    w += D;
+    for (int j = 0; j < 3; ++j) {  // W_q, W_k, W_v stacked as rows of one [3D][D] matrix
+      HIP_TRY(ctx, pack(w, g1, md.layers[l].Wqkv + (size_t)j * D * D * es, (int)D, (int)D));
+      w += D * D;
+    }
+    HIP_TRY(ctx, pack(w, nullptr, md.layers[l].Wo, (int)D, (int)D));
+    w += D * D;
+    const float* g2 = w;
+    w += D;
+    HIP_TRY(ctx, pack(w, g2, md.layers[l].W1, (int)D, (int)F));
+    w += D * F;
+    HIP_TRY(ctx, pack(w, nullptr, md.layers[l].W2, (int)F, (int)D));
+    w += F * D;
+  }
+  const float* gf = w;
+  w += D;
+  HIP_TRY(ctx, pack(w, gf, md.W_h, (int)D, (int)P));
+  md.loaded = true;
+  return TSD_OK;
+}
+
+int tsd_prefill(tsd_ctx* ctx, const float* series_dev, int32_t B, int32_t n_ctx_patches, int32_t horizon_steps, void* stream) {
+  if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
+  if (!ctx->model[0].loaded || !ctx->model[1].loaded) return fail(ctx, TSD_E_BAD_STATE, "weights of both models must be loaded first");
+  if (!series_dev) return fail(ctx, TSD_E_INVALID_ARG, "series_dev is NULL");
+  const tsd_config& c = ctx->cfg;
+  if (B < 1 || n_ctx_patches < 2 || horizon_steps < 1) return fail(ctx, TSD_E_INVALID_ARG, "need B >= 1, n_ctx_patches >= 2, horizon_steps >= 1");
+  if (B > c.max_batch) return fail(ctx, TSD_E_OUT_OF_RANGE, "B exceeds max_batch");
+  const int P = c.patch, N = n_ctx_patches, T = (horizon_steps + P - 1) / P;
+  if ((long)N + T + c.K > c.max_tokens) return fail(ctx, TSD_E_OUT_OF_RANGE, "n_ctx_patches + ceil(horizon/P) + K exceeds max_tokens");
+  hipStream_t st = (hipStream_t)stream;
+  ctx->prefilled = false;
+  // page table: every series reserves the pages its whole forecast can touch
+  const int need = (N + T + c.K + c.page_tokens - 1) / c.page_tokens;
+  std::vector<int> perm;
+  if (c.flags & TSD_FLAG_SCRAMBLE_PAGES) {
+    perm.resize(ctx->n_pages);
+    for (int i = 0; i < ctx->n_pages; ++i) perm[i] = i;
+    std::mt19937_64 rng(c.seed ^ 0x5bd1e995u);
+    for (int i = ctx->n_pages - 1; i > 0; --i) std::swap(perm[i], perm[(size_t)(rng() % (uint64_t)(i + 1))]);
+  }
+  ctx->host_pt.assign((size_t)B * ctx->pages_per_series, 0);
+  for (int b = 0; b < B; ++b)
+    for (int j = 0; j < need; ++j) {
+      int phys = j * B + b;  // pages handed out position-major across the batch
+      ctx->host_pt[(size_t)b * ctx->pages_per_series + j] = perm.empty() ? phys : perm[phys];
+    }
+  HIP_TRY(ctx, hipMemcpyAsync(ctx->page_table, ctx->host_pt.data(), ctx->host_pt.size() * 4, hipMemcpyHostToDevice, st));
+  PrefillP pp{series_dev, ctx->znorm, ctx->mean, ctx->sdev, ctx->pending, ctx->prev, ctx->len, ctx->committed,
+              ctx->round, ctx->active, ctx->stat, B, N, P};
+  HIP_TRY(ctx, launch_prefill_stats(pp, st));
+  ctx->B = B;
+  ctx->N = N;
+  ctx->T = T;
+  ctx->H = horizon_steps;
+  // context patches 0..N-2 through both models, in chunks of series that fit the workspace
+  const int nq = N - 1;
+  const int chunk = std::max(1, ctx->rows_max / nq);
+  for (int which = 0; which < 2; ++which)
+    for (int s0 = 0; s0 < B; s0 += chunk) {
+      Pass ps;
+      std::memset(&ps, 0, sizeof(ps));
+      ps.which = which;
+      ps.B = std::min(chunk, B - s0);
+      ps.s0 = s0;
+      ps.nq = nq;
+      ps.base_pos = nullptr;
+      ps.pos_off = 0;
+      ps.src0 = ctx->znorm + (size_t)s0 * N * P;
+      ps.stride0 = (long)N * P;
+      ps.n0 = nq;
+      ps.out = nullptr;
+      int rc = run_pass(ctx, ps, st);
+      if (rc) return rc;
+    }
+  ctx->prefilled = true;
+  return TSD_OK;
+}
+
+int tsd_reset_decode(tsd_ctx* ctx, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  PrefillP pp{nullptr, ctx->znorm, ctx->mean, ctx->sdev, ctx->pending, ctx->prev, ctx->len, ctx->committed,
+              ctx->round, ctx->active, ctx->stat, ctx->B, ctx->N, ctx->cfg.patch};
+  HIP_TRY(ctx, launch_reset(pp, (hipStream_t)stream));
+  return TSD_OK;
+}
+
+int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  const tsd_config& c = ctx->cfg;
+  const int P = c.patch, K = c.K;
+  hipStream_t st = (hipStream_t)stream;
+  // Step 1 ingests two tokens per series: the token just before the pending one and the pending
+  // one.  After a fully accepted round the draft cache lacks the former (it proposed x_K but
+  // never consumed it); for the other series the rewrite stores identical values.
+  Pass ps;
+  std::memset(&ps, 0, sizeof(ps));
+  ps.which = TSD_DRAFT;
+  ps.B = ctx->B;
+  ps.nq = 2;
+  ps.base_pos = ctx->len;
+  ps.pos_off = -1;
+  ps.src0 = ctx->prev;
+  ps.stride0 = P;
+  ps.n0 = 1;
+  ps.src1 = ctx->pending;
+  ps.stride1 = P;
+  ps.out = ctx->X;
+  ps.out_stride_b = (long)K * P;
+  ps.t_skip = 1;
+  if ((rc = run_pass(ctx, ps, st))) return rc;
+  for (int i = 2; i <= K; ++i) {  // step i consumes x_{i-1} at position len + i - 1, emits x_i
+    std::memset(&ps, 0, sizeof(ps));
+    ps.which = TSD_DRAFT;
+    ps.B = ctx->B;
+    ps.nq = 1;
+    ps.base_pos = ctx->len;
+    ps.pos_off = i - 1;
+    ps.src0 = ctx->X + (size_t)(i - 2) * P;
+    ps.stride0 = (long)K * P;
+    ps.n0 = 1;
+    ps.out = ctx->X + (size_t)(i - 1) * P;
+    ps.out_stride_b = (long)K * P;
+    ps.t_skip = 0;
+    if ((rc = run_pass(ctx, ps, st))) return rc;
+  }
+  return TSD_OK;
+}
+
+int tsd_target_verify(tsd_ctx* ctx, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  const tsd_config& c = ctx->cfg;
+  const int P = c.patch, K = c.K;
+  Pass ps;
+  std::memset(&ps, 0, sizeof(ps));
+  ps.which = TSD_TARGET;
+  ps.B = ctx->B;
+  ps.nq = K + 1;
+  ps.base_pos = ctx->len;
+  ps.pos_off = 0;
+  ps.src0 = ctx->pending;
+  ps.stride0 = P;
+  ps.n0 = 1;
+  ps.src1 = ctx->X;
+  ps.stride1 = (long)K * P;
+  ps.out = ctx->mu_p;
+  ps.out_stride_b = (long)(K + 1) * P;
+  ps.t_skip = 0;
+  return run_pass(ctx, ps, (hipStream_t)stream);
+}
+
+int tsd_accept_commit(tsd_ctx* ctx, const int32_t* forced_len_dev, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  return accept_commit_impl(ctx, forced_len_dev, ctx->cfg.K, (hipStream_t)stream);
+}
+
+int tsd_round(tsd_ctx* ctx, void* stream) {
+  int rc;
+  if ((rc = tsd_draft_propose(ctx, stream))) return rc;
+  if ((rc = tsd_target_verify(ctx, stream))) return rc;
+  return tsd_accept_commit(ctx, nullptr, stream);
+}
+
+int tsd_target_step(tsd_ctx* ctx, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  const int P = ctx->cfg.patch;
+  Pass ps;
+  std::memset(&ps, 0, sizeof(ps));
+  ps.which = TSD_TARGET;
+  ps.B = ctx->B;
+  ps.nq = 1;
+  ps.base_pos = ctx->len;
+  ps.pos_off = 0;
+  ps.src0 = ctx->pending;
+  ps.stride0 = P;
+  ps.n0 = 1;
+  ps.out = ctx->mu_p;
+  ps.out_stride_b = P;
+  ps.t_skip = 0;
+  if ((rc = run_pass(ctx, ps, (hipStream_t)stream))) return rc;
+  return accept_commit_impl(ctx, nullptr, 0, (hipStream_t)stream);  // K = 0: commit the target's mean
+}
+
+int tsd_num_active(tsd_ctx* ctx, int32_t* out_host, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  if (!out_host) return fail(ctx, TSD_E_INVALID_ARG, "out_host is NULL");
+  hipStream_t st = (hipStream_t)stream;
+  HIP_TRY(ctx, launch_count_active(ctx->active, ctx->B, ctx->count_out, st));
+  HIP_TRY(ctx, hipMemcpyAsync(out_host, ctx->count_out, 4, hipMemcpyDeviceToHost, st));
+  HIP_TRY(ctx, hipStreamSynchronize(st));
+  return TSD_OK;
+}
+
+int tsd_get_forecast(tsd_ctx* ctx, float* out_dev, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  if (!out_dev) return fail(ctx, TSD_E_INVALID_ARG, "out_dev is NULL");
+  HIP_TRY(ctx, launch_forecast_out(ctx->forecast, ctx->mean, ctx->sdev, ctx->committed, out_dev, ctx->B, ctx->cfg.patch,
+                                   ctx->T, ctx->H, (hipStream_t)stream));
+  return TSD_OK;
+}
+
+int tsd_get_round_io(tsd_ctx* ctx, float* X_dev, float* mu_q_dev, float* mu_p_dev, int32_t* n_acc_dev, float* ell_dev,
+                     float* logu_dev, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const size_t B = ctx->B, K = ctx->cfg.K, P = ctx->cfg.patch;
+  auto cp = [&](void* dst, const void* src, size_t bytes) {
+    return dst ? hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, st) : hipSuccess;
+  };
+  HIP_TRY(ctx, cp(X_dev, ctx->X, B * K * P * 4));
+  HIP_TRY(ctx, cp(mu_q_dev, ctx->X, B * K * P * 4));  // proposals are the draft means
+  HIP_TRY(ctx, cp(mu_p_dev, ctx->mu_p, B * (K + 1) * P * 4));
+  HIP_TRY(ctx, cp(n_acc_dev, ctx->n_acc, B * 4));
+  HIP_TRY(ctx, cp(ell_dev, ctx->ell, B * K * 4));
+  HIP_TRY(ctx, cp(logu_dev, ctx->logu, B * K * 4));
+  return TSD_OK;
+}
+
+int tsd_set_round_io(tsd_ctx* ctx, const float* X_dev, const float* mu_q_dev, const float* mu_p_dev, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  if (!X_dev || !mu_q_dev || !mu_p_dev) return fail(ctx, TSD_E_INVALID_ARG, "X_dev, mu_q_dev and mu_p_dev are all required");
+  hipStream_t st = (hipStream_t)stream;
+  const size_t B = ctx->B, K = ctx->cfg.K, P = ctx->cfg.patch;
+  HIP_TRY(ctx, hipMemcpyAsync(ctx->X, X_dev, B * K * P * 4, hipMemcpyDeviceToDevice, st));
+  HIP_TRY(ctx, hipMemcpyAsync(ctx->mu_q, mu_q_dev, B * K * P * 4, hipMemcpyDeviceToDevice, st));
+  HIP_TRY(ctx, hipMemcpyAsync(ctx->mu_p, mu_p_dev, B * (K + 1) * P * 4, hipMemcpyDeviceToDevice, st));
+  ctx->injected = true;
+  return TSD_OK;
+}
+
+int tsd_get_state(tsd_ctx* ctx, int32_t* len_dev, int32_t* committed_dev, float* pending_dev, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const size_t B = ctx->B, P = ctx->cfg.patch;
+  if (len_dev) HIP_TRY(ctx, hipMemcpyAsync(len_dev, ctx->len, B * 4, hipMemcpyDeviceToDevice, st));
+  if (committed_dev) HIP_TRY(ctx, hipMemcpyAsync(committed_dev, ctx->committed, B * 4, hipMemcpyDeviceToDevice, st));
+  if (pending_dev) HIP_TRY(ctx, hipMemcpyAsync(pending_dev, ctx->pending, B * P * 4, hipMemcpyDeviceToDevice, st));
+  return TSD_OK;
+}
+
+int tsd_get_stats(tsd_ctx* ctx, tsd_stats* out_host, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  if (!out_host) return fail(ctx, TSD_E_INVALID_ARG, "out_host is NULL");
+  hipStream_t st = (hipStream_t)stream;
+  long long h[5];
+  HIP_TRY(ctx, launch_sum_stats(ctx->stat, ctx->B, ctx->stats_out, st));
+  HIP_TRY(ctx, hipMemcpyAsync(h, ctx->stats_out, sizeof(h), hipMemcpyDeviceToHost, st));
+  HIP_TRY(ctx, hipStreamSynchronize(st));
+  out_host->rounds = h[0];
+  out_host->tested = h[1];
+  out_host->accepted = h[2];
+  out_host->committed = h[3];
+  out_host->near_ties = h[4];
+  return TSD_OK;
+}
+
+int tsd_set_accept_override(tsd_ctx* ctx, float alpha) {
+  if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
+  if (alpha > 1.f || alpha == 0.f || std::isnan(alpha)) return fail(ctx, TSD_E_INVALID_ARG, "alpha must be in (0, 1], or negative to disable");
+  ctx->alpha_override = alpha < 0.f ? -1.f : alpha;
+  return TSD_OK;
+}
+
+int tsd_set_sigma(tsd_ctx* ctx, float sigma_p, float sigma_q) {
+  if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
+  if (!(sigma_p > 0.f) || !(sigma_q > 0.f) || !std::isfinite(sigma_p) || !std::isfinite(sigma_q))
+    return fail(ctx, TSD_E_INVALID_ARG, "sigma_p and sigma_q must be positive and finite");
+  ctx->cfg.sigma_p = sigma_p;
+  ctx->cfg.sigma_q = sigma_q;
+  return TSD_OK;
+}
+
+}  // extern "C"

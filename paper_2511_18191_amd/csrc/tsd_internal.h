@@ -1,0 +1,139 @@
+// Internal declarations shared by the libtsd translation units (not part of the public ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "tsd.h"
+
+namespace tsd {
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kRmsEps = 1e-6f;   // inside the root of RMSNorm
+constexpr float kNormEps = 1e-5f;  // inside the root of the instance normalisation
+constexpr double kRopeBase = 10000.0;
+
+// ---- A-operand sources and epilogues of the fused GEMM family ------------------------------
+enum AMode {
+  A_TOK = 0,   // fp32 patches gathered from two per-series segments (patch embedding)
+  A_NORM = 1,  // fp32 residual stream; RMSNorm applied as a per-row scale of the product
+  A_ACT = 2    // activations already in the compute dtype
+};
+enum Epi {
+  EP_STORE = 0,  // x = C                       (fp32)
+  EP_RESID = 1,  // x += C                      (fp32 residual stream)
+  EP_GELU = 2,   // h = GELU_tanh(C)            (compute dtype)
+  EP_QKV = 3,    // RoPE on q,k; q -> buffer, k,v -> paged KV cache
+  EP_HEAD = 4    // mu = C, fp32, scattered to [series][token - t_skip]
+};
+
+struct GemmP {
+  int M, N, K;
+  // A operand
+  const void* A;  // A_NORM: const float* [M][K]; A_ACT: const T* [M][K]
+  const float* src0;
+  const float* src1;  // A_TOK: token t of series b comes from src0 + b*stride0 + t*K (t < n0)
+  long stride0, stride1;  //        else from src1 + b*stride1 + (t - n0)*K
+  int n0;
+  int nq;        // tokens per series in this pass: row r = (series r / nq, token r % nq)
+  const void* W;  // T [N][K]: transposed weights
+  // outputs
+  float* Cf;      // EP_STORE / EP_RESID: [M][N]
+  void* Ct;       // EP_GELU: T [M][N]
+  // EP_QKV
+  void* q_out;    // T [M][D]
+  void* kv_pool;  // this layer's pool: T [n_pages][2][Hh][PT][hd]
+  const int* page_table;
+  int pt_stride;
+  const int* base_pos;  // per-series position of token 0 minus pos_off (NULL = 0)
+  int pos_off;
+  int s0;  // first series of this pass (chunked prefill)
+  const float* rope_cos;
+  const float* rope_sin;  // [max_tokens][hd/2]
+  int D, Hh, hd, PT;
+  // EP_HEAD
+  float* out;
+  long out_stride_b;
+  int t_skip;
+};
+
+struct AttnP {
+  const void* q;       // T [rows][D]
+  void* out;           // T [rows][D]
+  const void* kv_pool; // this layer's pool
+  const int* page_table;
+  int pt_stride;
+  const int* base_pos;
+  int pos_off;
+  int s0;
+  int nq, B, Hh, hd, D, PT;
+  float scale;
+};
+
+// ---- launchers (each returns the hipError_t of the launch) ---------------------------------
+hipError_t launch_gemm(int dtype, int amode, int epi, const GemmP& p, hipStream_t st);
+// s_max: upper bound on (position of the pass's last token) + 1 over all series; sizes the score buffer.
+hipError_t launch_attention(int dtype, const AttnP& p, int s_max, hipStream_t st);
+
+struct PackP {
+  const float* W;     // [K][N] row-major source (y = x W)
+  const float* gain;  // [K] or NULL: folded as W'[n][k] = gain[k] * W[k][n]
+  void* out;          // T [N][K]
+  int K, N;
+};
+hipError_t launch_pack(int dtype, const PackP& p, hipStream_t st);
+
+struct PrefillP {
+  const float* series;  // [B][N*P]
+  float* znorm;         // [B][N*P] normalised
+  float* mean;
+  float* sdev;          // [B]
+  float* pending;
+  float* prev;          // [B][P]
+  int* len;
+  int* committed;
+  int* round;
+  int* active;
+  long long* stat;      // [B][5]
+  int B, N, P;
+};
+hipError_t launch_prefill_stats(const PrefillP& p, hipStream_t st);
+hipError_t launch_reset(const PrefillP& p, hipStream_t st);
+
+struct AcceptP {
+  const float* X;
+  const float* mu_q;  // [B][K][P]
+  const float* mu_p;  // [B][K+1][P]
+  const int* forced;  // nullable
+  float* pending;
+  float* prev;
+  float* forecast;    // [B][T*P] normalised
+  int* len;
+  int* committed;
+  int* round;
+  int* active;
+  int* n_acc;         // [B]
+  float* ell;
+  float* logu;        // [B][max(K,1)]
+  long long* stat;    // [B][5]: rounds, tested, accepted, committed, near_ties
+  int B, K, P, T;
+  float inv2sp2, inv2sq2, logdet, temper;  // temper = 1 (Eq. 5) or P (ablation without 1/d)
+  float log_alpha_override;                // > 0 means "no override"
+  unsigned key0, key1;
+};
+hipError_t launch_accept(const AcceptP& p, hipStream_t st);
+
+hipError_t launch_forecast_out(const float* forecast, const float* mean, const float* sdev, const int* committed,
+                               float* out, int B, int P, int T, int H, hipStream_t st);
+hipError_t launch_count_active(const int* active, int B, int* out, hipStream_t st);
+hipError_t launch_sum_stats(const long long* stat, int B, long long* out5, hipStream_t st);
+hipError_t launch_fill_nan(float* p, long n, hipStream_t st);
+
+}  // namespace tsd

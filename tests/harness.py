@@ -1,0 +1,137 @@
+"""Shared helpers of the GPU parity tests: build a libtsd session and the oracle's view of the
+same seeded inputs, and run the two in lock-step."""
+import math
+
+import numpy as np
+
+import synth
+from oracle import tsd_oracle as orc
+
+
+def rel_err(a, b):
+    """||a - b||_2 / max(||b||_2, 1e-12) per patch (last axis)."""
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    return np.linalg.norm(a - b, axis=-1) / np.maximum(np.linalg.norm(b, axis=-1), 1e-12)
+
+
+TOL = {"fp32": 1e-4, "bf16": 2e-2}
+# one model pass evaluated by the oracle on exactly the tokens the GPU consumed (no drift from
+# earlier rounding): bf16 operand rounding gives ~3e-3 median on these models
+PASS_TOL = {"fp32": 2e-5, "bf16": 8e-3}
+
+
+class Case:
+    """Seeded inputs of one configuration, for both implementations."""
+
+    def __init__(self, name, B=None, sigma=None, K=None, horizon=None, random_gains=False, draft_is_target=False,
+                 seed=2021, **over):
+        cfg = synth.get_config(name, **over)
+        if K is not None or horizon is not None or sigma is not None or B is not None:
+            import dataclasses
+            cfg = dataclasses.replace(cfg, K=K or cfg.K, horizon=horizon or cfg.horizon,
+                                      sigma=sigma or cfg.sigma, batch=B or cfg.batch)
+        if draft_is_target:
+            import dataclasses
+            cfg = dataclasses.replace(cfg, draft=cfg.target)
+        self.cfg = cfg
+        self.seed = seed
+        rng = np.random.default_rng(cfg.weight_seed)
+        self.wt = synth.make_weights(cfg.target, cfg.patch, rng, cfg.dtype, random_gains=random_gains)
+        self.wd = self.wt if draft_is_target else synth.make_weights(cfg.draft, cfg.patch, rng, cfg.dtype,
+                                                                     random_gains=random_gains)
+        self.Wt, self.Wd = orc.as_f64(self.wt), orc.as_f64(self.wd)
+        self.series = synth.make_series(cfg.series_kind, cfg.batch, cfg.context + cfg.horizon, cfg.series_seed,
+                                        cfg.context)
+        self.context = np.ascontiguousarray(self.series[:, : cfg.context])
+
+    def session(self, flags=0, page_tokens=16, max_batch=None, sigma_q=None):
+        import paper_2511_18191_amd as tsd
+        c = self.cfg
+        tc = tsd.make_config(c.target, c.draft, c.patch, c.K, max_batch or c.batch, c.max_tokens, c.dtype, c.sigma,
+                             sigma_q, seed=self.seed, page_tokens=page_tokens, flags=flags)
+        s = tsd.Session(tc)
+        s.load_weights(tsd.TSD_TARGET, synth.flatten_weights(c.target, c.patch, self.wt))
+        s.load_weights(tsd.TSD_DRAFT, synth.flatten_weights(c.draft, c.patch, self.wd))
+        return s
+
+    def oracle_hist(self, b):
+        ctx = self.context[b].astype(np.float64)
+        m, s = orc.context_stats(ctx)
+        return ((ctx - m) / s).reshape(-1, self.cfg.patch), m, s
+
+
+def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=True, tol=None):
+    """Run GPU and oracle round by round on the same histories.  The GPU evaluates its own
+    acceptance test (recorded) but commits the oracle's accepted length, so the two histories
+    stay aligned and every round's tensors can be compared.  Returns a report dict."""
+    import torch
+    c = case.cfg
+    B, K, P, T = c.batch, c.K, c.patch, c.T
+    sq = sigma_q or c.sigma
+    sess.prefill(case.context, c.n_ctx, c.horizon)
+    hist = [case.oracle_hist(b)[0] for b in range(B)]
+    Y = [np.empty((0, P)) for _ in range(B)]
+    rnd = [0] * B
+    rep = dict(max_rel_X=0.0, max_rel_mu_p=0.0, near_ties=0, mismatched=0, tested=0, accepted=0, rounds=0,
+               max_abs_ell=0.0, lengths=[], pass_rel_q=0.0, pass_rel_p=0.0)
+    tol = tol or TOL[c.dtype]
+    Yg = [np.empty((0, P)) for _ in range(B)]     # what the GPU committed (its own tensors)
+    rounds = 0
+    while any(y.shape[0] < T for y in Y) and (max_rounds is None or rounds < max_rounds):
+        sess.draft_propose()
+        sess.target_verify()
+        forced = np.full(B, -1, np.int32)
+        recs = {}
+        for b in range(B):
+            if Y[b].shape[0] >= T:
+                continue
+            recs[b] = orc.spec_round(case.Wt, c.target, case.Wd, c.draft, np.vstack([hist[b], Y[b]]), K, c.sigma, sq,
+                                     (lambda i, b=b: orc.uniform(case.seed, b, rnd[b], i)))
+            forced[b] = recs[b]["n"]
+        sess.accept_commit(torch.from_numpy(forced))
+        io = {k: v.cpu().numpy() for k, v in sess.get_round_io().items()}
+        for b, rec in recs.items():
+            n = rec["n"]
+            # compare what both sides computed from (nearly) identical histories
+            rx = rel_err(io["X"][b], rec["X"]).max()
+            rp = rel_err(io["mu_p"][b], rec["mu_p"]).max()
+            rep["max_rel_X"] = max(rep["max_rel_X"], rx)
+            rep["max_rel_mu_p"] = max(rep["max_rel_mu_p"], rp)
+            if check:
+                assert rx <= tol, f"series {b} round {rnd[b]}: proposals differ, rel {rx:.3e}"
+                assert rp <= tol, f"series {b} round {rnd[b]}: target means differ, rel {rp:.3e}"
+            if per_pass:
+                hg = np.vstack([hist[b], Yg[b]])
+                Xg, n0 = io["X"][b].astype(np.float64), hg.shape[0]
+                for i in range(K):
+                    q_ref = orc.forward(case.Wd, c.draft, np.vstack([hg, Xg[:i]]))[-1]
+                    rep["pass_rel_q"] = max(rep["pass_rel_q"], rel_err(Xg[i], q_ref))
+                p_ref = orc.forward(case.Wt, c.target, np.vstack([hg, Xg]))[n0 - 1:]
+                rep["pass_rel_p"] = max(rep["pass_rel_p"], rel_err(io["mu_p"][b], p_ref).max())
+                if check:
+                    assert rep["pass_rel_q"] <= PASS_TOL[c.dtype] and rep["pass_rel_p"] <= PASS_TOL[c.dtype], \
+                        f"series {b} round {rnd[b]}: per-pass error {rep['pass_rel_q']:.3e} / {rep['pass_rel_p']:.3e}"
+                Yg[b] = np.vstack([Yg[b], Xg[:n], io["mu_p"][b][n][None, :].astype(np.float64)])[:T]
+            tested = n + (1 if n < K else 0)
+            gap = np.abs(np.minimum(0.0, rec["ell"][:tested]) - rec["logu"][:tested])
+            near = bool(np.any(gap < 1e-4))
+            rep["near_ties"] += int(near)
+            rep["tested"] += tested
+            rep["accepted"] += n
+            g_n = int(io["n_acc"][b])
+            # the uniforms are exact on both sides; log u and ell only to rounding
+            np.testing.assert_allclose(io["logu"][b][:min(tested, g_n + 1)], rec["logu"][:min(tested, g_n + 1)], rtol=2e-6, atol=2e-6)
+            if g_n != n:
+                rep["mismatched"] += 1
+                if check and c.dtype == "fp32":
+                    assert near, f"series {b} round {rnd[b]}: accepted {g_n} vs oracle {n} away from any tie"
+            else:
+                d_ell = np.abs(io["ell"][b][:tested] - rec["ell"][:tested]).max() if tested else 0.0
+                rep["max_abs_ell"] = max(rep["max_abs_ell"], float(d_ell))
+            Y[b] = np.vstack([Y[b], rec["commits"]])[:T]
+            rnd[b] += 1
+            rep["lengths"].append(n + 1)
+        rounds += 1
+    rep["rounds"] = rounds
+    rep["Y"] = Y
+    return rep
