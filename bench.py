@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the speculative-decoding hot path on one MI355X.
+
+A step is one whole speculative decode of the batch: reset to the post-prefill state, then
+rounds (draft proposal, single-pass verification, acceptance/commit/rollback) until every series
+has its horizon.  Inputs (weights, KV cache of the context) are resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2] [--sigma 1.0]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--sigma", type=float, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-series", type=int, default=4, help="series in the oracle's bounded sample")
+    return ap.parse_args()
+
+
+def decode_spec(sess):
+    sess.reset_decode()
+    rounds = 0
+    while True:
+        sess.round()
+        rounds += 1
+        if sess.num_active() == 0:
+            return rounds
+
+
+def decode_target_only(sess, T):
+    sess.reset_decode()
+    for _ in range(T):
+        sess.target_step()
+
+
+def timed(torch, fn, steps):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()       # waits for every stream of the device, the session's included
+    return (time.perf_counter() - t0) / steps
+
+
+def phase_times(torch, sess, reps=20):
+    """hipEvent time of one draft proposal, one verification, one acceptance, one target-only
+    step (each repeated from the post-prefill state)."""
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    out = {}
+    for name, fn in (("draft", sess.draft_propose), ("verify", sess.target_verify),
+                     ("accept", sess.accept_commit), ("target_step", sess.target_step)):
+        tot = 0.0
+        for _ in range(reps):
+            sess.reset_decode()
+            if name == "accept":
+                sess.draft_propose(); sess.target_verify()
+            a, b = ev(), ev()
+            a.record(sess.stream); fn(); b.record(sess.stream)   # events on the stream the kernels run on
+            torch.cuda.synchronize()
+            tot += a.elapsed_time(b)
+        out[name] = tot / reps
+    return out
+
+
+PEAK = {"bf16": 2500.0, "fp32": 157.3}   # dense MFMA bf16 / vector fp32, TFLOP/s
+HBM_PEAK = 8000.0                        # GB/s
+
+
+def kernel_rooflines(sess, dtype, steps):
+    """Per kernel family: HIP-event time of every launch during `steps` speculative decodes
+    (kernel-by-kernel launches on the session's stream), and the algorithmic work they did."""
+    from paper_2511_18191_amd.binding import KERNEL_CLASSES
+    out = {}
+    for cls, name in enumerate(KERNEL_CLASSES):
+        sess.profile_begin(cls)
+        for _ in range(steps):
+            decode_spec(sess)
+        n, ms, work = sess.profile_end()
+        if n == 0:
+            continue
+        hbm = name in ("attn", "accept")
+        achieved = work / (ms * 1e-3) / (1e9 if hbm else 1e12)
+        peak = HBM_PEAK if hbm else PEAK[dtype]
+        out[name] = dict(bound="hbm" if hbm else "mfma", achieved=achieved, peak=peak, unit="GB/s" if hbm else "TFLOP/s",
+                         frac=achieved / peak, launches=n, avg_us=ms * 1e3 / n, total_ms=ms, traffic=None)
+    return out
+
+
+def cpu_baseline(case, n_series):
+    """The oracle, as it stands, on a bounded sample: n_series series, whole horizon,
+    single-pass mode, one process (numpy's BLAS threads)."""
+    from oracle import tsd_oracle as orc
+    c = case.cfg
+    t0 = time.perf_counter()
+    for b in range(n_series):
+        orc.forecast_spec(case.Wt, c.target, case.Wd, c.draft, case.context[b], c.patch, c.horizon, c.K, c.sigma,
+                          c.sigma, case.seed, b)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    return dict(value=n_series * c.horizon / dt, unit="forecast steps/s", cores=cores, kind="oracle",
+                sample=f"{n_series} of {c.batch} series, whole horizon of {c.horizon} steps, single-pass oracle, "
+                       f"{dt:.1f} s")
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from harness import Case
+    from oracle import tsd_oracle as orc  # CPU-baseline leg and the throughput-law arithmetic only
+
+    case = Case(a.config, sigma=a.sigma)
+    c = case.cfg
+    sess = case.session()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    sess.prefill(case.context, c.n_ctx, c.horizon)
+    torch.cuda.synchronize()
+    prefill_ms = (time.perf_counter() - t0) * 1e3
+
+    for _ in range(a.warmup):
+        decode_spec(sess)
+    rounds = decode_spec(sess)
+    st = sess.get_stats()
+    t_spec = timed(torch, lambda: decode_spec(sess), a.steps)
+    for _ in range(max(1, a.warmup // 2)):
+        decode_target_only(sess, c.T)
+    t_base = timed(torch, lambda: decode_target_only(sess, c.T), a.steps)
+    ph = phase_times(torch, sess)
+
+    fam = kernel_rooflines(sess, c.dtype, max(2, a.steps // 4))
+    dominant = max(fam, key=lambda k: fam[k]["total_ms"])
+
+    alpha = st["accepted"] / max(1, st["tested"])
+    mean_L = st["committed"] / max(1, st["rounds"])
+    cc = ph["draft"] / c.K / ph["target_step"]
+    v = (ph["verify"] + ph["accept"]) / ph["target_step"]
+    out = {
+        "metric": "forecast steps/s (batched spec decode) + speedup vs target-only AR decode",
+        "value": c.batch * c.horizon / t_spec,
+        "unit": "forecast steps/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": t_spec * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": c.dtype, "data": "synthetic",
+        "config": {"workload": f"{c.name}: B={c.batch} P={c.patch} N={c.n_ctx} H={c.horizon} K={c.K} sigma={c.sigma} "
+                               f"target {c.target.n_layers}L/d{c.target.d_model} draft {c.draft.n_layers}L/d{c.draft.d_model}",
+                   "step": "reset to post-prefill state + speculative rounds until all series reach the horizon"},
+        "speedup_vs_target_only": t_base / t_spec,
+        "target_only_steps_per_s": c.batch * c.horizon / t_base,
+        "target_only_ms": t_base * 1e3,
+        "prefill_ms": prefill_ms,
+        "rounds_per_decode": rounds,
+        "acceptance": alpha, "mean_committed_per_round": mean_L,
+        "phase_ms": ph, "c": cc, "v": v,
+        "predicted_speedup_eq8": orc.predicted_speedup(alpha, c.K, cc, v),
+        "near_ties": st["near_ties"],
+        # committed patches per unit time against one patch per target step (what Eq. 8 predicts)
+        "patch_rate_speedup": mean_L * ph["target_step"] / (ph["draft"] + ph["verify"] + ph["accept"]),
+        "roofline": dict({k: v for k, v in fam[dominant].items() if k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},
+                         kernel=dominant, avg_us=fam[dominant]["avg_us"], launches=fam[dominant]["launches"]),
+        "kernel_families": fam,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(case, min(a.cpu_series, c.batch))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

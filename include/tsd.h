@@ -61,6 +61,7 @@ extern "C" {
 /* flags */
 #define TSD_FLAG_SCRAMBLE_PAGES 1u /* assign physical KV pages by a pseudo-random permutation */
 #define TSD_FLAG_NO_TEMPERING 2u   /* ablation: use d * ell (drop the 1/d scaling of Eq. 5)    */
+#define TSD_FLAG_NO_GRAPH 4u       /* launch kernels one by one instead of replaying HIP graphs */
 
 typedef struct tsd_ctx tsd_ctx; /* opaque */
 
@@ -153,7 +154,9 @@ int tsd_target_verify(tsd_ctx* ctx, void* stream);
  * has been evaluated and recorded (used to keep two implementations in lock-step); -1 = free. */
 int tsd_accept_commit(tsd_ctx* ctx, const int32_t* forced_len_dev, void* stream);
 
-/* tsd_draft_propose; tsd_target_verify; tsd_accept_commit(NULL). */
+/* tsd_draft_propose; tsd_target_verify; tsd_accept_commit(NULL).  On a non-NULL stream that is not
+ * being captured by the caller, the launch sequence is captured into a HIP graph on first use and
+ * replayed afterwards (same for tsd_target_step); TSD_FLAG_NO_GRAPH switches that off. */
 int tsd_round(tsd_ctx* ctx, void* stream);
 
 /* Target-only autoregressive baseline (Eq. 1) from the same kernels: one target pass over the
@@ -190,6 +193,25 @@ int tsd_set_accept_override(tsd_ctx* ctx, float alpha);
 
 /* Change the acceptance temperatures (temperature sweeps without re-creating the handle). */
 int tsd_set_sigma(tsd_ctx* ctx, float sigma_p, float sigma_q);
+
+/* Measurement tap (not part of the method): time every launch of one kernel family with HIP
+ * events recorded on the launching stream.  kernel_class: TSD_K_*; while a class is selected,
+ * tsd_round / tsd_target_step launch kernel by kernel (no graph replay).  tsd_profile_end waits
+ * for the stream, returns the number of launches, their summed duration in milliseconds and their
+ * summed algorithmic work (GEMM families: 2*M*N*K flops; TSD_K_ATTN: bytes of the K and V rows
+ * each (series, head) must read, counted with the shortest possible history N-1, plus q and
+ * output rows; TSD_K_ACCEPT: bytes of X, mu_p read and the committed patch written), and
+ * switches the tap off. */
+#define TSD_K_EMBED 0  /* patch embedding GEMM                          */
+#define TSD_K_QKV 1    /* RMSNorm + QKV GEMM + RoPE + KV-cache write    */
+#define TSD_K_ATTN 2   /* paged causal attention                        */
+#define TSD_K_RESID 3  /* attention-output and FFN-down GEMMs (+residual) */
+#define TSD_K_GELU 4   /* RMSNorm + FFN-up GEMM + GELU                  */
+#define TSD_K_HEAD 5   /* RMSNorm + output-head GEMM                    */
+#define TSD_K_ACCEPT 6 /* acceptance + commit + rollback                */
+#define TSD_K_COUNT 7
+int tsd_profile_begin(tsd_ctx* ctx, int kernel_class);
+int tsd_profile_end(tsd_ctx* ctx, int64_t* launches_host, double* ms_host, double* work_host, void* stream);
 
 const char* tsd_last_error(tsd_ctx* ctx);
 

@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 TSD_F32, TSD_BF16 = 0, 1
 TSD_TARGET, TSD_DRAFT = 0, 1
-TSD_FLAG_SCRAMBLE_PAGES, TSD_FLAG_NO_TEMPERING = 1, 2
+TSD_FLAG_SCRAMBLE_PAGES, TSD_FLAG_NO_TEMPERING, TSD_FLAG_NO_GRAPH = 1, 2, 4
+KERNEL_CLASSES = ["embed", "qkv", "attn", "resid", "gelu", "head", "accept"]   # TSD_K_* order
 
 
 class TsdModelCfg(C.Structure):
@@ -55,6 +56,8 @@ SYMBOLS = {
     "tsd_set_round_io": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_get_state": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_get_stats": ([C.c_void_p, C.POINTER(TsdStats), C.c_void_p], C.c_int),
+    "tsd_profile_begin": ([C.c_void_p, C.c_int], C.c_int),
+    "tsd_profile_end": ([C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p], C.c_int),
     "tsd_set_accept_override": ([C.c_void_p, C.c_float], C.c_int),
     "tsd_set_sigma": ([C.c_void_p, C.c_float, C.c_float], C.c_int),
 }
@@ -71,6 +74,9 @@ def lib():
     there is no fallback implementation."""
     global _lib
     if _lib is None:
+        # torch ships its own HIP runtime; load it first so that libtsd binds to the same one
+        # (two runtimes in one process do not share device pointers or streams)
+        import torch  # noqa: F401
         path = library_path()
         if not os.path.exists(path):
             from . import build as _build
@@ -118,9 +124,28 @@ class Session:
         self.h = h
         self.B = 0
         self.H = 0
+        # a stream of its own (default priority): HIP graphs cannot be captured on the NULL stream
+        self.stream = torch.cuda.Stream(self.device)
 
     def _stream(self):
-        return self.torch.cuda.current_stream(self.device).cuda_stream
+        return self.stream.cuda_stream
+
+    def sync(self):
+        self.stream.synchronize()
+
+    def _to_dev(self, t, dtype):
+        """Copy to the device on torch's current stream and wait, so the library's stream sees it."""
+        torch = self.torch
+        if not isinstance(t, torch.Tensor):
+            t = torch.from_numpy(t)
+        t = t.to(self.device, dtype).contiguous()
+        torch.cuda.current_stream(self.device).synchronize()
+        return t
+
+    def _new(self, *shape, dtype=None):
+        """Output buffer for the library to fill; allocated after the library's stream is idle."""
+        self.sync()
+        return self.torch.empty(*shape, dtype=dtype or self.torch.float32, device=self.device)
 
     def close(self):
         if self.h:
@@ -140,18 +165,12 @@ class Session:
 
     def load_weights(self, which, blob):
         """blob: float32 torch tensor on the device (or numpy array, copied over)."""
-        torch = self.torch
-        if not isinstance(blob, torch.Tensor):
-            blob = torch.from_numpy(blob)
-        blob = blob.to(self.device, torch.float32).contiguous()
+        blob = self._to_dev(blob, self.torch.float32)
         _check(lib().tsd_load_weights(self.h, which, blob.data_ptr(), blob.numel(), self._stream()), self.h)
-        torch.cuda.current_stream(self.device).synchronize()  # blob may be freed after this
+        self.sync()  # blob may be freed after this
 
     def prefill(self, series, n_ctx_patches, horizon_steps):
-        torch = self.torch
-        if not isinstance(series, torch.Tensor):
-            series = torch.from_numpy(series)
-        self.series = series.to(self.device, torch.float32).contiguous()
+        self.series = self._to_dev(series, self.torch.float32)
         self.B, self.H = self.series.shape[0], horizon_steps
         _check(lib().tsd_prefill(self.h, self.series.data_ptr(), self.B, n_ctx_patches, horizon_steps, self._stream()), self.h)
 
@@ -167,7 +186,7 @@ class Session:
     def accept_commit(self, forced_len=None):
         ptr = None
         if forced_len is not None:
-            self._forced = forced_len.to(self.device, self.torch.int32).contiguous()
+            self._forced = self._to_dev(forced_len, self.torch.int32)
             ptr = self._forced.data_ptr()
         _check(lib().tsd_accept_commit(self.h, ptr, self._stream()), self.h)
 
@@ -183,36 +202,45 @@ class Session:
         return n.value
 
     def get_forecast(self):
-        out = self.torch.empty(self.B, self.H, dtype=self.torch.float32, device=self.device)
+        out = self._new(self.B, self.H)
         _check(lib().tsd_get_forecast(self.h, out.data_ptr(), self._stream()), self.h)
+        self.sync()
         return out
 
     def get_round_io(self):
         torch, B, K, P = self.torch, self.B, self.cfg.K, self.cfg.patch
-        f = lambda *s: torch.empty(*s, dtype=torch.float32, device=self.device)
+        f = self._new
         X, mu_q, mu_p, ell, logu = f(B, K, P), f(B, K, P), f(B, K + 1, P), f(B, K), f(B, K)
-        n_acc = torch.empty(B, dtype=torch.int32, device=self.device)
+        n_acc = f(B, dtype=torch.int32)
         _check(lib().tsd_get_round_io(self.h, X.data_ptr(), mu_q.data_ptr(), mu_p.data_ptr(), n_acc.data_ptr(),
                                       ell.data_ptr(), logu.data_ptr(), self._stream()), self.h)
+        self.sync()
         return dict(X=X, mu_q=mu_q, mu_p=mu_p, n_acc=n_acc, ell=ell, logu=logu)
 
     def set_round_io(self, X, mu_q, mu_p):
         torch = self.torch
-        self._inj = [t.to(self.device, torch.float32).contiguous() for t in (X, mu_q, mu_p)]
+        self._inj = [self._to_dev(t, torch.float32) for t in (X, mu_q, mu_p)]
         _check(lib().tsd_set_round_io(self.h, *[t.data_ptr() for t in self._inj], self._stream()), self.h)
 
     def get_state(self):
         torch, B, P = self.torch, self.B, self.cfg.patch
-        ln = torch.empty(B, dtype=torch.int32, device=self.device)
-        cm = torch.empty(B, dtype=torch.int32, device=self.device)
-        pend = torch.empty(B, P, dtype=torch.float32, device=self.device)
+        ln, cm, pend = self._new(B, dtype=torch.int32), self._new(B, dtype=torch.int32), self._new(B, P)
         _check(lib().tsd_get_state(self.h, ln.data_ptr(), cm.data_ptr(), pend.data_ptr(), self._stream()), self.h)
+        self.sync()
         return dict(len=ln, committed=cm, pending=pend)
 
     def get_stats(self):
         s = TsdStats()
         _check(lib().tsd_get_stats(self.h, C.byref(s), self._stream()), self.h)
         return {k: getattr(s, k) for k, _ in TsdStats._fields_}
+
+    def profile_begin(self, kernel_class):
+        _check(lib().tsd_profile_begin(self.h, kernel_class), self.h)
+
+    def profile_end(self):
+        n, ms, work = C.c_int64(), C.c_double(), C.c_double()
+        _check(lib().tsd_profile_end(self.h, C.byref(n), C.byref(ms), C.byref(work), self._stream()), self.h)
+        return n.value, ms.value, work.value
 
     def set_accept_override(self, alpha):
         _check(lib().tsd_set_accept_override(self.h, alpha), self.h)

@@ -2,9 +2,11 @@
 //
 // The keys/values of the new tokens were written into the cache by the QKV epilogue, so query t
 // (absolute position base + t) simply attends to cache positions 0 .. base + t.
-// One wavefront per (series, head).  Queries are processed in chunks of QC; for a chunk the
-// keys are read once (one key per lane, dot products against the chunk's queries held in LDS),
-// the softmax runs across lanes in fp32, and P.V is accumulated with lanes over the head dim.
+//
+// One wavefront per (series, head).  The head's K and V rows (at most a few hundred tokens) are
+// staged into LDS once with 16-byte loads that are all in flight together (the pass is bound by
+// HBM latency/bandwidth, not arithmetic); queries are then processed in chunks of QC:
+// scores with one key per lane, fp32 softmax across lanes, P.V with lanes over the head dim.
 #include <type_traits>
 
 #include "tsd_internal.h"
@@ -12,26 +14,6 @@
 namespace tsd {
 
 constexpr int QC = 8;
-
-template <typename T>
-struct Vec;
-template <>
-struct Vec<float> {
-  static constexpr int N = 4;
-  __device__ static void load(const float* p, float* o) {
-    float4 v = *reinterpret_cast<const float4*>(p);
-    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
-  }
-};
-template <>
-struct Vec<bf16> {
-  static constexpr int N = 8;
-  __device__ static void load(const bf16* p, float* o) {
-    bf16x8 v = *reinterpret_cast<const bf16x8*>(p);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) o[i] = (float)v[i];
-  }
-};
 
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
@@ -44,51 +26,139 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+template <typename T>
+__device__ __forceinline__ void unpack16(const uint4& r, float* o);
+template <>
+__device__ __forceinline__ void unpack16<float>(const uint4& r, float* o) {
+  const float4 f = *reinterpret_cast<const float4*>(&r);
+  o[0] = f.x; o[1] = f.y; o[2] = f.z; o[3] = f.w;
+}
+template <>
+__device__ __forceinline__ void unpack16<bf16>(const uint4& r, float* o) {
+  const bf16x8 v = *reinterpret_cast<const bf16x8*>(&r);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = (float)v[i];
+}
+
+// LDS bytes of one staged K (or V) row: the head's HD elements plus 16 bytes of padding so that
+// consecutive rows start in different banks.
+__host__ __device__ constexpr int row_bytes(int hd, int es) { return hd * es + 16; }
+
 template <typename T, int HD>
 __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
-  extern __shared__ float dyn[];
-  float* qs = dyn;              // [QC][HD]
-  float* ps = dyn + QC * HD;    // [QC][s_pad]
+  constexpr int ES = (int)sizeof(T);
+  constexpr int RB = row_bytes(HD, ES);
+  constexpr int CPR = HD * ES / 16;   // 16-byte chunks per row
+  constexpr int EPC = 16 / ES;        // elements per chunk
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn[];
+  unsigned char* Ks = dyn;                                   // [s_pad][RB]
+  unsigned char* Vs = dyn + (size_t)s_pad * RB;              // [s_pad][RB]
+  float* qs = reinterpret_cast<float*>(Vs + (size_t)s_pad * RB);  // [QC][HD]
+  float* ps = qs + QC * HD;                                  // [QC][s_pad]
+
   const int lane = threadIdx.x;
   const int bl = blockIdx.x / p.Hh, h = blockIdx.x % p.Hh;
   const int b = p.s0 + bl;
-  const int base = (p.base_pos ? p.base_pos[b] : 0) + p.pos_off;
-  const T* pool = reinterpret_cast<const T*>(p.kv_pool);
-  const int* pt = p.page_table + (long)b * p.pt_stride;
-  const int PT = p.PT, Hh = p.Hh;
+  const int PT = p.PT, Hh = p.Hh, pts = p.pt_shift;
   const T* q = reinterpret_cast<const T*>(p.q);
   T* out = reinterpret_cast<T*>(p.out);
+
+  // Independent loads first, all in flight together: this lane's page-table entry, the series'
+  // base position, and the first chunk's queries.
+  const int my_page = p.page_table[(long)b * p.pt_stride + min(lane, p.pt_stride - 1)];
+  const int base = (p.base_pos ? p.base_pos[b] : 0) + p.pos_off;
+  constexpr int QR = QC * HD / 64;
+  float qreg[QR];
+  {
+    const int n_first = min(QC, p.nq) * HD;
+#pragma unroll
+    for (int r = 0; r < QR; ++r) {
+      const int i = min(lane + r * 64, n_first - 1);
+      qreg[r] = (float)q[((long)bl * p.nq + i / HD) * p.D + h * HD + i % HD];
+    }
+  }
+  const int total_keys = base + p.nq;
+
+  // ---- stage this head's K and V rows (page ids come from other lanes' registers) ----
+  {
+    const unsigned char* pool = reinterpret_cast<const unsigned char*>(p.kv_pool);
+    const int total = total_keys * CPR;
+    constexpr int U = 4;
+    // uniform trip count: every lane stays active, so the page-id shuffles see all lanes
+    for (int base_c = 0; base_c < total; base_c += 64 * U) {
+      const int c0 = base_c + lane;
+      uint4 rk[U], rv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int c = min(c0 + u * 64, total - 1);  // clamped: always a valid row, stored only if in range
+        const int s = c / CPR, kc = c % CPR;
+        const int page = __shfl(my_page, s >> pts);
+        const long rowk = ((((long)page * 2 + 0) * Hh + h) * PT + (s & (PT - 1))) * HD;
+        const long rowv = rowk + (long)Hh * PT * HD;
+        rk[u] = *reinterpret_cast<const uint4*>(pool + rowk * ES + kc * 16);
+        rv[u] = *reinterpret_cast<const uint4*>(pool + rowv * ES + kc * 16);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int c = c0 + u * 64;
+        if (c < total) {
+          const int s = c / CPR, kc = c % CPR;
+          *reinterpret_cast<uint4*>(Ks + (size_t)s * RB + kc * 16) = rk[u];
+          *reinterpret_cast<uint4*>(Vs + (size_t)s * RB + kc * 16) = rv[u];
+        }
+      }
+    }
+  }
+
   constexpr int G = 64 / HD;  // key groups in the P.V stage
   const int d = lane % HD, sg = lane / HD;
 
   for (int q0 = 0; q0 < p.nq; q0 += QC) {
     const int nqc = min(QC, p.nq - q0);
-    __syncthreads();
-    for (int i = lane; i < nqc * HD; i += 64) {
-      int j = i / HD, e = i % HD;
-      qs[j * HD + e] = (float)q[((long)bl * p.nq + q0 + j) * p.D + h * HD + e] * p.scale;
+    __syncthreads();  // staging done / previous chunk's ps and qs no longer read
+    if (q0 == 0) {
+#pragma unroll
+      for (int r = 0; r < QR; ++r) qs[lane + r * 64] = qreg[r] * p.scale;
+    } else {
+      for (int i = lane; i < nqc * HD; i += 64) {
+        const int j = i / HD, e = i % HD;
+        qs[j * HD + e] = (float)q[((long)bl * p.nq + q0 + j) * p.D + h * HD + e] * p.scale;
+      }
     }
     __syncthreads();
     const int nkeys = base + q0 + nqc;  // the chunk's last query sees keys 0 .. nkeys-1
     // ---- scores: one key per lane ----
     for (int s = lane; s < nkeys; s += 64) {
-      const int page = pt[s / PT];
-      const T* kp = pool + ((((long)page * 2 + 0) * Hh + h) * PT + (s % PT)) * HD;
       float sc[QC];
 #pragma unroll
       for (int j = 0; j < QC; ++j) sc[j] = 0.f;
 #pragma unroll
-      for (int v = 0; v < HD / Vec<T>::N; ++v) {
-        float kf[Vec<T>::N];
-        Vec<T>::load(kp + v * Vec<T>::N, kf);
+      for (int v = 0; v < CPR; ++v) {
+        float kf[EPC];
+        unpack16<T>(*reinterpret_cast<const uint4*>(Ks + (size_t)s * RB + v * 16), kf);
 #pragma unroll
-        for (int j = 0; j < QC; ++j)
+        for (int j = 0; j < QC; ++j) {
+          if (j < nqc) {
 #pragma unroll
-          for (int e = 0; e < Vec<T>::N; ++e) sc[j] = fmaf(kf[e], qs[j * HD + v * Vec<T>::N + e], sc[j]);
+            for (int e4 = 0; e4 < EPC; e4 += 4) {
+              const float4 qq = *reinterpret_cast<const float4*>(qs + j * HD + v * EPC + e4);
+              sc[j] = fmaf(kf[e4 + 0], qq.x, sc[j]);
+              sc[j] = fmaf(kf[e4 + 1], qq.y, sc[j]);
+              sc[j] = fmaf(kf[e4 + 2], qq.z, sc[j]);
+              sc[j] = fmaf(kf[e4 + 3], qq.w, sc[j]);
+            }
+          }
+        }
       }
 #pragma unroll
       for (int j = 0; j < QC; ++j)
         if (j < nqc) ps[j * s_pad + s] = (s <= base + q0 + j) ? sc[j] : -INFINITY;
+    }
+    // keys nkeys .. round-up-to-4 are read (as zeros) by the vectorised P.V loop
+    const int nk4 = (nkeys + 3) & ~3;
+    for (int i = lane; i < nqc * (nk4 - nkeys); i += 64) {
+      const int j = i / (nk4 - nkeys), s = nkeys + i % (nk4 - nkeys);
+      ps[j * s_pad + s] = -INFINITY;
     }
     __syncthreads();
     // ---- softmax over keys, per query ----
@@ -98,11 +168,11 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
       inv_sum[j] = 0.f;
       if (j < nqc) {
         float m = -INFINITY;
-        for (int s = lane; s < nkeys; s += 64) m = fmaxf(m, ps[j * s_pad + s]);
+        for (int s = lane; s < nk4; s += 64) m = fmaxf(m, ps[j * s_pad + s]);
         m = wave_max(m);
         float sum = 0.f;
-        for (int s = lane; s < nkeys; s += 64) {
-          float e = __expf(ps[j * s_pad + s] - m);
+        for (int s = lane; s < nk4; s += 64) {
+          const float e = __expf(ps[j * s_pad + s] - m);
           ps[j * s_pad + s] = e;
           sum += e;
         }
@@ -110,16 +180,25 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
       }
     }
     __syncthreads();
-    // ---- P.V: lanes over the head dim (G key groups when HD < 64) ----
+    // ---- P.V: lanes over the head dim (G key groups when HD < 64), four keys per step ----
     float acc[QC];
 #pragma unroll
     for (int j = 0; j < QC; ++j) acc[j] = 0.f;
-    for (int s = sg; s < nkeys; s += G) {
-      const int page = pt[s / PT];
-      const float vv = (float)pool[((((long)page * 2 + 1) * Hh + h) * PT + (s % PT)) * HD + d];
+    for (int s4 = sg * 4; s4 < nk4; s4 += 4 * G) {
+      float vv[4];
 #pragma unroll
-      for (int j = 0; j < QC; ++j)
-        if (j < nqc) acc[j] = fmaf(ps[j * s_pad + s], vv, acc[j]);
+      for (int u = 0; u < 4; ++u)
+        vv[u] = (s4 + u < nkeys) ? (float)*reinterpret_cast<const T*>(Vs + (size_t)(s4 + u) * RB + d * ES) : 0.f;
+#pragma unroll
+      for (int j = 0; j < QC; ++j) {
+        if (j < nqc) {
+          const float4 pp = *reinterpret_cast<const float4*>(ps + j * s_pad + s4);
+          acc[j] = fmaf(pp.x, vv[0], acc[j]);
+          acc[j] = fmaf(pp.y, vv[1], acc[j]);
+          acc[j] = fmaf(pp.z, vv[2], acc[j]);
+          acc[j] = fmaf(pp.w, vv[3], acc[j]);
+        }
+      }
     }
     if constexpr (G > 1) {
 #pragma unroll
@@ -135,23 +214,54 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
   }
 }
 
-template <typename T>
-static hipError_t launch_t(const AttnP& p, hipStream_t st, int s_pad) {
-  dim3 grid((unsigned)(p.B * p.Hh)), block(64);
-  size_t smem = (size_t)(QC * p.hd + QC * s_pad) * sizeof(float);
-  switch (p.hd) {
-    case 16: hipLaunchKernelGGL((attn_kernel<T, 16>), grid, block, smem, st, p, s_pad); break;
-    case 32: hipLaunchKernelGGL((attn_kernel<T, 32>), grid, block, smem, st, p, s_pad); break;
-    case 64: hipLaunchKernelGGL((attn_kernel<T, 64>), grid, block, smem, st, p, s_pad); break;
+size_t attention_lds_bytes(int dtype, int hd, int s_max, int page_tokens) {
+  const int es = dtype == TSD_BF16 ? 2 : 4;
+  const int s_pad = (s_max + 3) & ~3;
+  const int pages = (s_pad + page_tokens - 1) / page_tokens + 1;
+  return (size_t)2 * s_pad * row_bytes(hd, es) + (size_t)(QC * hd + QC * s_pad) * 4 + (size_t)pages * 4;
+}
+
+template <typename T, int HD>
+static hipError_t launch_hd(const AttnP& p, hipStream_t st, int s_pad, size_t smem) {
+  hipLaunchKernelGGL((attn_kernel<T, HD>), dim3((unsigned)(p.B * p.Hh)), dim3(64), smem, st, p, s_pad);
+  return hipGetLastError();
+}
+
+template <typename T, int HD>
+static hipError_t raise_lds() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<T, HD>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
+
+// More than 64 KB of dynamic LDS needs a one-time opt-in per kernel; done at handle creation so
+// that no such call happens while a stream is being captured.
+hipError_t prepare_attention(int dtype, int hd, int s_max, int page_tokens) {
+  if (attention_lds_bytes(dtype, hd, s_max, page_tokens) <= 64 * 1024) return hipSuccess;
+  const bool bf = dtype == TSD_BF16;
+  switch (hd) {
+    case 16: return bf ? raise_lds<bf16, 16>() : raise_lds<float, 16>();
+    case 32: return bf ? raise_lds<bf16, 32>() : raise_lds<float, 32>();
+    case 64: return bf ? raise_lds<bf16, 64>() : raise_lds<float, 64>();
     default: return hipErrorInvalidValue;
   }
-  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t launch_t(const AttnP& p, hipStream_t st, int s_pad, size_t smem) {
+  switch (p.hd) {
+    case 16: return launch_hd<T, 16>(p, st, s_pad, smem);
+    case 32: return launch_hd<T, 32>(p, st, s_pad, smem);
+    case 64: return launch_hd<T, 64>(p, st, s_pad, smem);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 hipError_t launch_attention(int dtype, const AttnP& p, int s_max, hipStream_t st) {
   if (p.B <= 0 || p.nq <= 0 || s_max <= 0) return hipErrorInvalidValue;
-  int s_pad = (s_max + 3) & ~3;
-  return dtype == TSD_BF16 ? launch_t<bf16>(p, st, s_pad) : launch_t<float>(p, st, s_pad);
+  const int s_pad = (s_max + 3) & ~3;
+  const size_t smem = attention_lds_bytes(dtype, p.hd, s_max, p.PT);
+  if (smem > 160 * 1024) return hipErrorInvalidValue;
+  return dtype == TSD_BF16 ? launch_t<bf16>(p, st, s_pad, smem) : launch_t<float>(p, st, s_pad, smem);
 }
 
 }  // namespace tsd

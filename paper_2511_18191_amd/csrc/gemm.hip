@@ -35,10 +35,9 @@ __device__ __forceinline__ void store4<bf16>(bf16* dst, float4 v) {
   *reinterpret_cast<bf16x4*>(dst) = o;
 }
 
-template <typename T, int AM, int EP, int BM, int BN>
+template <typename T, int AM, int EP, int BM, int BN, int BK>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   constexpr bool kBf = !std::is_same<T, float>::value;
-  constexpr int BK = kBf ? 32 : 16;
   constexpr int LDT = BK + (kBf ? 8 : 1);  // padded LDS row, in elements
   constexpr int LDC = BN + 4;
   constexpr int AB_BYTES = 2 * (BM + BN) * LDT * (int)sizeof(T);
@@ -102,22 +101,25 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
     brow[i] = gn < N ? reinterpret_cast<const char*>(reinterpret_cast<const T*>(p.W) + (long)gn * K) : nullptr;
   }
 
-  uint4 ra[NA], rb[NB];
-  auto load_global = [&](int kt) {
+  // Two tiles are kept in flight in two register sets that alternate (no copies between them:
+  // a copy would wait for the younger load), so the HBM latency of one tile overlaps the MFMA
+  // work and LDS traffic of two others.
+  uint4 ra0[NA], rb0[NB], ra1[NA], rb1[NB];
+  auto load_global = [&](int kt, uint4* xa, uint4* xb) {
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
       int k = kt * BK + a_kc[i] * CHA;
-      ra[i] = make_uint4(0, 0, 0, 0);
-      if (arow[i] && k < K) ra[i] = *reinterpret_cast<const uint4*>(arow[i] + (long)k * (kASrcF32 ? 4 : 2));
+      xa[i] = make_uint4(0, 0, 0, 0);
+      if (arow[i] && k < K) xa[i] = *reinterpret_cast<const uint4*>(arow[i] + (long)k * (kASrcF32 ? 4 : 2));
     }
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
       int k = kt * BK + b_kc[i] * CHB;
-      rb[i] = make_uint4(0, 0, 0, 0);
-      if (brow[i] && k < K) rb[i] = *reinterpret_cast<const uint4*>(brow[i] + (long)k * (int)sizeof(T));
+      xb[i] = make_uint4(0, 0, 0, 0);
+      if (brow[i] && k < K) xb[i] = *reinterpret_cast<const uint4*>(brow[i] + (long)k * (int)sizeof(T));
     }
   };
-  auto store_lds = [&](int buf) {
+  auto store_lds = [&](int buf, uint4* ra, uint4* rb) {
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
       T* dst = As + (buf * BM + a_r[i]) * LDT + a_kc[i] * CHA;
@@ -175,13 +177,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   const int ty = tid >> 4, tx = tid & 15;  // fp32 path: 4x4 micro-tile at (ty*4, tx*4)
 
   // ---- main loop ----------------------------------------------------------------------------
-  const int nk = (K + BK - 1) / BK;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-  int buf = 0;
-  for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) load_global(kt + 1);
+  auto compute = [&](int buf) {
     const T* at = As + buf * BM * LDT;
     const T* bt = Bs + buf * BN * LDT;
     if constexpr (kBf) {
@@ -215,9 +211,24 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
           for (int j = 0; j < 4; ++j) accf[i][j] = fmaf(a[i], b[j], accf[i][j]);
       }
     }
-    if (kt + 1 < nk) store_lds(buf ^ 1);
+  };
+  const int nk = (K + BK - 1) / BK;
+  load_global(0, ra0, rb0);
+  if (nk > 1) load_global(1, ra1, rb1);
+  store_lds(0, ra0, rb0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; kt += 2) {
+    // even tile: lives in LDS buffer 0; set 1 holds tile kt+1, set 0 is free for tile kt+2
+    if (kt + 2 < nk) load_global(kt + 2, ra0, rb0);
+    compute(0);
+    if (kt + 1 < nk) store_lds(1, ra1, rb1);
     __syncthreads();
-    buf ^= 1;
+    if (kt + 1 >= nk) break;
+    // odd tile: LDS buffer 1; set 0 holds tile kt+2, set 1 is free for tile kt+3
+    if (kt + 3 < nk) load_global(kt + 3, ra1, rb1);
+    compute(1);
+    if (kt + 2 < nk) store_lds(0, ra0, rb0);
+    __syncthreads();
   }
 
   // ---- RMSNorm row scale --------------------------------------------------------------------
@@ -314,8 +325,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
         if (which == 0) {
           store4<T>(reinterpret_cast<T*>(p.q_out) + (long)gm * D + c, v);
         } else {
-          const int page = p.page_table[(long)b * p.pt_stride + pos / p.PT];
-          const long off = ((((long)page * 2 + (which - 1)) * p.Hh + h) * p.PT + (pos % p.PT)) * hd + d;
+          const int page = p.page_table[(long)b * p.pt_stride + (pos >> p.pt_shift)];
+          const long off = ((((long)page * 2 + (which - 1)) * p.Hh + h) * p.PT + (pos & (p.PT - 1))) * hd + d;
           store4<T>(reinterpret_cast<T*>(p.kv_pool) + off, v);
         }
       }
@@ -329,12 +340,12 @@ static hipError_t launch_cfg(const GemmP& p, hipStream_t st) {
   if constexpr (kBf) {
     long t128 = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
     if (t128 >= 192) {
-      hipLaunchKernelGGL((gemm_kernel<T, AM, EP, 128, 128>), dim3((unsigned)t128), dim3(256), 0, st, p);
+      hipLaunchKernelGGL((gemm_kernel<T, AM, EP, 128, 128, 32>), dim3((unsigned)t128), dim3(256), 0, st, p);
       return hipGetLastError();
     }
   }
   long t64 = (long)((p.M + 63) / 64) * ((p.N + 63) / 64);
-  hipLaunchKernelGGL((gemm_kernel<T, AM, EP, 64, 64>), dim3((unsigned)t64), dim3(256), 0, st, p);
+  hipLaunchKernelGGL((gemm_kernel<T, AM, EP, 64, 64, (kBf ? 64 : 16)>), dim3((unsigned)t64), dim3(256), 0, st, p);
   return hipGetLastError();
 }
 

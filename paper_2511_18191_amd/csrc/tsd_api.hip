@@ -58,6 +58,13 @@ struct tsd_ctx {
   bool injected;  // next accept reads mu_q from its own buffer
   float alpha_override;
   std::vector<int> host_pt;
+  // captured launch sequences of tsd_round / tsd_target_step (rebuilt when anything they bake in changes)
+  hipGraphExec_t graph_round = nullptr, graph_step = nullptr;
+  // measurement tap: event pairs around every launch of one kernel family
+  int prof_class = -1;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
+  size_t prof_used = 0;
+  double prof_work = 0;
   std::string err;
 };
 
@@ -115,7 +122,12 @@ int check_config(const tsd_config* c, std::string& why) {
   if (!(c->sigma_p > 0.f) || !(c->sigma_q > 0.f) || !std::isfinite(c->sigma_p) || !std::isfinite(c->sigma_q))
     return bad("sigma_p and sigma_q must be positive and finite");
   if (c->fallback_r != 0.f) return bad("fallback_r must be 0 (target-mean fallback)");
-  if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING)) return bad("unknown flag bits");
+  if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING | TSD_FLAG_NO_GRAPH)) return bad("unknown flag bits");
+  if ((c->max_tokens + c->page_tokens - 1) / c->page_tokens > 64)
+    return bad("max_tokens / page_tokens must not exceed 64 pages per series");
+  for (const tsd_model_cfg* m : {&c->target, &c->draft})
+    if (attention_lds_bytes(c->dtype, m->d_model / m->n_heads, c->max_tokens, c->page_tokens) > 160 * 1024)
+      return bad("max_tokens too large: one head's K and V rows must fit the 160 KB of LDS");
   return TSD_OK;
 }
 
@@ -220,6 +232,27 @@ size_t weights_count(const tsd_model_cfg& m, int P) {
   return (size_t)P * D + per_layer * m.n_layers + D + D * P;
 }
 
+// Launches `fn` on `st`; if kernel family `cls` is being profiled, brackets it with two events.
+template <typename F>
+hipError_t timed_launch(tsd_ctx* ctx, int cls, double work, hipStream_t st, F fn) {
+  if (ctx->prof_class != cls) return fn();
+  if (ctx->prof_used == ctx->prof_events.size()) {
+    hipEvent_t a, b;
+    hipError_t e = hipEventCreate(&a);
+    if (e != hipSuccess) return e;
+    e = hipEventCreate(&b);
+    if (e != hipSuccess) return e;
+    ctx->prof_events.emplace_back(a, b);
+  }
+  auto& ev = ctx->prof_events[ctx->prof_used++];
+  hipError_t e = hipEventRecord(ev.first, st);
+  if (e != hipSuccess) return e;
+  e = fn();
+  if (e != hipSuccess) return e;
+  ctx->prof_work += work;
+  return hipEventRecord(ev.second, st);
+}
+
 struct Pass {
   int which;
   int B, s0, nq;
@@ -253,7 +286,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
   g.n0 = ps.n0;
   g.W = md.W_e;
   g.Cf = ctx->x;
-  HIP_TRY(ctx, launch_gemm(c.dtype, A_TOK, EP_STORE, g, st));
+  HIP_TRY(ctx, timed_launch(ctx, TSD_K_EMBED, 2.0 * M * D * P, st, [&] { return launch_gemm(c.dtype, A_TOK, EP_STORE, g, st); }));
   for (int l = 0; l < md.c.n_layers; ++l) {
     char* pool = md.kv_pool + (size_t)l * md.layer_pool_bytes;
     GemmP q;
@@ -277,7 +310,8 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     q.Hh = md.c.n_heads;
     q.hd = md.hd;
     q.PT = c.page_tokens;
-    HIP_TRY(ctx, launch_gemm(c.dtype, A_NORM, EP_QKV, q, st));
+    q.pt_shift = __builtin_ctz(c.page_tokens);
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_QKV, 6.0 * M * D * D, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_QKV, q, st); }));
     AttnP a;
     std::memset(&a, 0, sizeof(a));
     a.q = ctx->qbuf;
@@ -294,8 +328,11 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     a.hd = md.hd;
     a.D = D;
     a.PT = c.page_tokens;
+    a.pt_shift = __builtin_ctz(c.page_tokens);
     a.scale = 1.0f / std::sqrt((float)md.hd);
-    HIP_TRY(ctx, launch_attention(c.dtype, a, c.max_tokens, st));
+    // K and V rows of the shortest history this pass can see (N-1 cached tokens + the new ones), q and output rows
+    const double attn_bytes = (double)ps.B * D * ctx->es * (2.0 * (ctx->N - 1 + ps.nq + (ps.base_pos ? ps.pos_off : 1 - ctx->N)) + 2.0 * ps.nq);
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_ATTN, attn_bytes, st, [&] { return launch_attention(c.dtype, a, c.max_tokens, st); }));
     GemmP o;
     std::memset(&o, 0, sizeof(o));
     o.M = M;
@@ -305,7 +342,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     o.A = ctx->abuf;
     o.W = md.layers[l].Wo;
     o.Cf = ctx->x;
-    HIP_TRY(ctx, launch_gemm(c.dtype, A_ACT, EP_RESID, o, st));
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_RESID, 2.0 * M * D * D, st, [&] { return launch_gemm(c.dtype, A_ACT, EP_RESID, o, st); }));
     GemmP f1;
     std::memset(&f1, 0, sizeof(f1));
     f1.M = M;
@@ -315,7 +352,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     f1.A = ctx->x;
     f1.W = md.layers[l].W1;
     f1.Ct = ctx->hbuf;
-    HIP_TRY(ctx, launch_gemm(c.dtype, A_NORM, EP_GELU, f1, st));
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_GELU, 2.0 * M * D * F, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_GELU, f1, st); }));
     GemmP f2;
     std::memset(&f2, 0, sizeof(f2));
     f2.M = M;
@@ -325,7 +362,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     f2.A = ctx->hbuf;
     f2.W = md.layers[l].W2;
     f2.Cf = ctx->x;
-    HIP_TRY(ctx, launch_gemm(c.dtype, A_ACT, EP_RESID, f2, st));
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_RESID, 2.0 * M * D * F, st, [&] { return launch_gemm(c.dtype, A_ACT, EP_RESID, f2, st); }));
   }
   if (ps.out) {
     GemmP h;
@@ -339,8 +376,46 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     h.out = ps.out;
     h.out_stride_b = ps.out_stride_b;
     h.t_skip = ps.t_skip;
-    HIP_TRY(ctx, launch_gemm(c.dtype, A_NORM, EP_HEAD, h, st));
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_HEAD, 2.0 * M * D * P, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_HEAD, h, st); }));
   }
+  return TSD_OK;
+}
+
+void drop_graphs(tsd_ctx* ctx) {
+  for (hipGraphExec_t* g : {&ctx->graph_round, &ctx->graph_step})
+    if (*g) {
+      (void)hipGraphExecDestroy(*g);
+      *g = nullptr;
+    }
+}
+
+// Runs `body` (a sequence of kernel launches on `st`) through a HIP graph: captured on first use,
+// replayed afterwards.  Falls back to plain launches on the NULL stream, when the caller is
+// itself capturing `st`, or when graphs are switched off.
+template <typename F>
+int run_graphed(tsd_ctx* ctx, hipGraphExec_t* slot, hipStream_t st, F body) {
+  if ((ctx->cfg.flags & TSD_FLAG_NO_GRAPH) || st == nullptr || ctx->prof_class >= 0) return body();
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  HIP_TRY(ctx, hipStreamIsCapturing(st, &cs));
+  if (cs != hipStreamCaptureStatusNone) return body();
+  if (!*slot) {
+    HIP_TRY(ctx, hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+    int rc = body();
+    hipGraph_t graph = nullptr;
+    hipError_t e = hipStreamEndCapture(st, &graph);
+    if (rc) {
+      if (graph) (void)hipGraphDestroy(graph);
+      return rc;
+    }
+    if (e != hipSuccess) return fail(ctx, TSD_E_HIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+    e = hipGraphInstantiate(slot, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (e != hipSuccess) {
+      *slot = nullptr;
+      return fail(ctx, TSD_E_HIP, std::string("hipGraphInstantiate: ") + hipGetErrorString(e));
+    }
+  }
+  HIP_TRY(ctx, hipGraphLaunch(*slot, st));
   return TSD_OK;
 }
 
@@ -383,7 +458,7 @@ int accept_commit_impl(tsd_ctx* ctx, const int32_t* forced, int K, hipStream_t s
   a.log_alpha_override = ctx->alpha_override > 0.f ? std::log(ctx->alpha_override) : 1.0f;
   a.key0 = (unsigned)(c.seed & 0xFFFFFFFFull);
   a.key1 = (unsigned)(c.seed >> 32);
-  HIP_TRY(ctx, launch_accept(a, st));
+  HIP_TRY(ctx, timed_launch(ctx, TSD_K_ACCEPT, 4.0 * ctx->B * c.patch * (2.0 * K + 2), st, [&] { return launch_accept(a, st); }));
   ctx->injected = false;
   return TSD_OK;
 }
@@ -454,6 +529,14 @@ int tsd_create(const tsd_config* cfg, void* arena_dev, size_t arena_bytes, tsd_c
       return fail(nullptr, TSD_E_HIP, msg);
     }
   }
+  for (int w = 0; w < 2; ++w) {
+    hipError_t e = prepare_attention(cfg->dtype, ctx->model[w].hd, cfg->max_tokens, cfg->page_tokens);
+    if (e != hipSuccess) {
+      std::string msg = std::string("raising the attention kernel's LDS limit: ") + hipGetErrorString(e);
+      delete ctx;
+      return fail(nullptr, TSD_E_HIP, msg);
+    }
+  }
   *out = ctx;
   return TSD_OK;
 }
@@ -461,6 +544,11 @@ int tsd_create(const tsd_config* cfg, void* arena_dev, size_t arena_bytes, tsd_c
 int tsd_destroy(tsd_ctx* ctx) {
   if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
   hipError_t e = hipDeviceSynchronize();
+  drop_graphs(ctx);
+  for (auto& ev : ctx->prof_events) {
+    (void)hipEventDestroy(ev.first);
+    (void)hipEventDestroy(ev.second);
+  }
   delete ctx;
   if (e != hipSuccess) return fail(nullptr, TSD_E_HIP, std::string("hipDeviceSynchronize: ") + hipGetErrorString(e));
   return TSD_OK;
@@ -474,6 +562,7 @@ int tsd_load_weights(tsd_ctx* ctx, int which, const float* blob_dev, size_t n_fl
   const tsd_config& c = ctx->cfg;
   if (n_floats != weights_count(md.c, c.patch)) return fail(ctx, TSD_E_INVALID_ARG, "n_floats does not match tsd_weights_count");
   hipStream_t st = (hipStream_t)stream;
+  drop_graphs(ctx);
   const size_t D = md.c.d_model, F = md.c.d_ff, P = c.patch, es = ctx->es;
   const float* w = blob_dev;
   auto pack = [&](const float* W, const float* gain, void* out, int K, int N) {
@@ -516,6 +605,7 @@ int tsd_prefill(tsd_ctx* ctx, const float* series_dev, int32_t B, int32_t n_ctx_
   if ((long)N + T + c.K > c.max_tokens) return fail(ctx, TSD_E_OUT_OF_RANGE, "n_ctx_patches + ceil(horizon/P) + K exceeds max_tokens");
   hipStream_t st = (hipStream_t)stream;
   ctx->prefilled = false;
+  drop_graphs(ctx);  // batch size, context length and horizon are baked into the captured launches
   // page table: every series reserves the pages its whole forecast can touch
   const int need = (N + T + c.K + c.page_tokens - 1) / c.page_tokens;
   std::vector<int> perm;
@@ -578,6 +668,7 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
   const tsd_config& c = ctx->cfg;
   const int P = c.patch, K = c.K;
   hipStream_t st = (hipStream_t)stream;
+  ctx->injected = false;
   // Step 1 ingests two tokens per series: the token just before the pending one and the pending
   // one.  After a fully accepted round the draft cache lacks the former (it proposed x_K but
   // never consumed it); for the other series the rewrite stores identical values.
@@ -645,31 +736,38 @@ int tsd_accept_commit(tsd_ctx* ctx, const int32_t* forced_len_dev, void* stream)
 }
 
 int tsd_round(tsd_ctx* ctx, void* stream) {
-  int rc;
-  if ((rc = tsd_draft_propose(ctx, stream))) return rc;
-  if ((rc = tsd_target_verify(ctx, stream))) return rc;
-  return tsd_accept_commit(ctx, nullptr, stream);
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  return run_graphed(ctx, &ctx->graph_round, (hipStream_t)stream, [&]() {
+    int r;
+    if ((r = tsd_draft_propose(ctx, stream))) return r;
+    if ((r = tsd_target_verify(ctx, stream))) return r;
+    return tsd_accept_commit(ctx, nullptr, stream);
+  });
 }
 
 int tsd_target_step(tsd_ctx* ctx, void* stream) {
   int rc = require_ready(ctx, true);
   if (rc) return rc;
   const int P = ctx->cfg.patch;
-  Pass ps;
-  std::memset(&ps, 0, sizeof(ps));
-  ps.which = TSD_TARGET;
-  ps.B = ctx->B;
-  ps.nq = 1;
-  ps.base_pos = ctx->len;
-  ps.pos_off = 0;
-  ps.src0 = ctx->pending;
-  ps.stride0 = P;
-  ps.n0 = 1;
-  ps.out = ctx->mu_p;
-  ps.out_stride_b = P;
-  ps.t_skip = 0;
-  if ((rc = run_pass(ctx, ps, (hipStream_t)stream))) return rc;
-  return accept_commit_impl(ctx, nullptr, 0, (hipStream_t)stream);  // K = 0: commit the target's mean
+  return run_graphed(ctx, &ctx->graph_step, (hipStream_t)stream, [&]() {
+    Pass ps;
+    std::memset(&ps, 0, sizeof(ps));
+    ps.which = TSD_TARGET;
+    ps.B = ctx->B;
+    ps.nq = 1;
+    ps.base_pos = ctx->len;
+    ps.pos_off = 0;
+    ps.src0 = ctx->pending;
+    ps.stride0 = P;
+    ps.n0 = 1;
+    ps.out = ctx->mu_p;
+    ps.out_stride_b = P;
+    ps.t_skip = 0;
+    int r = run_pass(ctx, ps, (hipStream_t)stream);
+    if (r) return r;
+    return accept_commit_impl(ctx, nullptr, 0, (hipStream_t)stream);  // K = 0: commit the target's mean
+  });
 }
 
 int tsd_num_active(tsd_ctx* ctx, int32_t* out_host, void* stream) {
@@ -751,10 +849,39 @@ int tsd_get_stats(tsd_ctx* ctx, tsd_stats* out_host, void* stream) {
   return TSD_OK;
 }
 
+int tsd_profile_begin(tsd_ctx* ctx, int kernel_class) {
+  if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
+  if (kernel_class < -1 || kernel_class >= TSD_K_COUNT) return fail(ctx, TSD_E_INVALID_ARG, "kernel_class must be a TSD_K_* value or -1");
+  ctx->prof_class = kernel_class;
+  ctx->prof_used = 0;
+  ctx->prof_work = 0;
+  return TSD_OK;
+}
+
+int tsd_profile_end(tsd_ctx* ctx, int64_t* launches_host, double* ms_host, double* work_host, void* stream) {
+  if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
+  if (!launches_host || !ms_host || !work_host) return fail(ctx, TSD_E_INVALID_ARG, "output pointers must not be NULL");
+  if (ctx->prof_class < 0) return fail(ctx, TSD_E_BAD_STATE, "tsd_profile_begin has not selected a kernel class");
+  ctx->prof_class = -1;
+  HIP_TRY(ctx, hipStreamSynchronize((hipStream_t)stream));
+  double ms = 0;
+  for (size_t i = 0; i < ctx->prof_used; ++i) {
+    float t = 0;
+    HIP_TRY(ctx, hipEventElapsedTime(&t, ctx->prof_events[i].first, ctx->prof_events[i].second));
+    ms += t;
+  }
+  *launches_host = (int64_t)ctx->prof_used;
+  *ms_host = ms;
+  *work_host = ctx->prof_work;
+  ctx->prof_used = 0;
+  return TSD_OK;
+}
+
 int tsd_set_accept_override(tsd_ctx* ctx, float alpha) {
   if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
   if (alpha > 1.f || alpha == 0.f || std::isnan(alpha)) return fail(ctx, TSD_E_INVALID_ARG, "alpha must be in (0, 1], or negative to disable");
   ctx->alpha_override = alpha < 0.f ? -1.f : alpha;
+  drop_graphs(ctx);
   return TSD_OK;
 }
 
@@ -764,6 +891,7 @@ int tsd_set_sigma(tsd_ctx* ctx, float sigma_p, float sigma_q) {
     return fail(ctx, TSD_E_INVALID_ARG, "sigma_p and sigma_q must be positive and finite");
   ctx->cfg.sigma_p = sigma_p;
   ctx->cfg.sigma_q = sigma_q;
+  drop_graphs(ctx);
   return TSD_OK;
 }
 

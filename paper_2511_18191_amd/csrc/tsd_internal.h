@@ -58,6 +58,7 @@ struct GemmP {
   const float* rope_cos;
   const float* rope_sin;  // [max_tokens][hd/2]
   int D, Hh, hd, PT;
+  int pt_shift;  // log2(PT)
   // EP_HEAD
   float* out;
   long out_stride_b;
@@ -74,6 +75,7 @@ struct AttnP {
   int pos_off;
   int s0;
   int nq, B, Hh, hd, D, PT;
+  int pt_shift;  // log2(PT)
   float scale;
 };
 
@@ -81,6 +83,9 @@ struct AttnP {
 hipError_t launch_gemm(int dtype, int amode, int epi, const GemmP& p, hipStream_t st);
 // s_max: upper bound on (position of the pass's last token) + 1 over all series; sizes the score buffer.
 hipError_t launch_attention(int dtype, const AttnP& p, int s_max, hipStream_t st);
+// dynamic LDS the attention kernel needs for up to s_max cached tokens (must stay <= 160 KB)
+size_t attention_lds_bytes(int dtype, int hd, int s_max, int page_tokens);
+hipError_t prepare_attention(int dtype, int hd, int s_max, int page_tokens);
 
 struct PackP {
   const float* W;     // [K][N] row-major source (y = x W)
