@@ -326,8 +326,18 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
           store4<T>(reinterpret_cast<T*>(p.q_out) + (long)gm * D + c, v);
         } else {
           const int page = p.page_table[(long)b * p.pt_stride + (pos >> p.pt_shift)];
-          const long off = ((((long)page * 2 + (which - 1)) * p.Hh + h) * p.PT + (pos & (p.PT - 1))) * hd + d;
-          store4<T>(reinterpret_cast<T*>(p.kv_pool) + off, v);
+          const int tok = pos & (p.PT - 1);
+          if (which == 2 && p.v_transposed) {
+            // V block stored [head][dim][token]: four strided element stores
+            T* vp = reinterpret_cast<T*>(p.kv_pool) + (((long)page * 2 + 1) * p.Hh + h) * p.PT * hd + (long)d * p.PT + tok;
+            vp[0] = (T)v.x;
+            vp[p.PT] = (T)v.y;
+            vp[2 * p.PT] = (T)v.z;
+            vp[3 * p.PT] = (T)v.w;
+          } else {
+            const long off = ((((long)page * 2 + (which - 1)) * p.Hh + h) * p.PT + tok) * hd + d;
+            store4<T>(reinterpret_cast<T*>(p.kv_pool) + off, v);
+          }
         }
       }
     }

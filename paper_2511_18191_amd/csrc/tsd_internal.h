@@ -59,6 +59,7 @@ struct GemmP {
   const float* rope_sin;  // [max_tokens][hd/2]
   int D, Hh, hd, PT;
   int pt_shift;  // log2(PT)
+  int v_transposed;  // V block of a page is [head][dim][token]
   // EP_HEAD
   float* out;
   long out_stride_b;
@@ -76,6 +77,7 @@ struct AttnP {
   int s0;
   int nq, B, Hh, hd, D, PT;
   int pt_shift;  // log2(PT)
+  int v_transposed;  // V block of a page is [head][dim][token] (bf16 head_dim-64 MFMA attention)
   float scale;
 };
 
