@@ -43,20 +43,31 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   constexpr int AB_BYTES = 2 * (BM + BN) * LDT * (int)sizeof(T);
   constexpr int C_BYTES = 64 * LDC * 4;
   constexpr int SMEM = AB_BYTES > C_BYTES ? AB_BYTES : C_BYTES;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
-  __shared__ float row_scale[BM];
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // SMEM + BM * 4 bytes
   T* As = reinterpret_cast<T*>(smem);  // [2][BM][LDT]
   T* Bs = As + 2 * BM * LDT;           // [2][BN][LDT]
   float* Cs = reinterpret_cast<float*>(smem);  // [64][LDC], reuses the tile buffers
+  float* row_scale = reinterpret_cast<float*>(smem + SMEM);  // [BM]
 
   const int tid = threadIdx.x;
-  const int tiles_n = (p.N + BN - 1) / BN;
-  const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
-  const int m0 = tm * BM, n0 = tn * BN;
   const int M = p.M, N = p.N, K = p.K;
+  // Tile order.  Workgroups go round-robin to the 8 XCDs (each with its own L2), so workgroup
+  // w lands on XCD w % 8.  Give every XCD one contiguous run of the tile list, and order the
+  // list in groups of 8 tile columns walked row by row: the ~32 tiles an XCD runs at a time then
+  // form a 4 x 8 rectangle that shares 4 row panels and 8 column panels through that L2.
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const int n_tiles = tiles_m * tiles_n;
+  const int per_xcd = (n_tiles + 7) >> 3;
+  const int lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (lin >= n_tiles) return;
+  constexpr int GW = 8;
+  const int gc = lin / (GW * tiles_m), rem = lin - gc * (GW * tiles_m);
+  const int gw = min(GW, tiles_n - gc * GW);
+  const int tm = rem / gw, tn = gc * GW + rem - tm * gw;
+  const int m0 = tm * BM, n0 = tn * BN;
 
   // ---- A loader set-up ----------------------------------------------------------------------
-  constexpr bool kASrcF32 = (AM != A_ACT) || !kBf;   // source rows are fp32
+  constexpr bool kASrcF32 = (AM == A_TOK) || !kBf;   // source rows are fp32 (bf16 mode reads the bf16 shadow of the residual)
   constexpr int CHA = kASrcF32 ? 4 : 8;              // elements per 16-byte chunk
   constexpr int CPRA = BK / CHA;                     // chunks per tile row
   constexpr int NA = BM * CPRA / 256;
@@ -70,9 +81,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
     a_r[i] = id / CPRA;
     a_kc[i] = id % CPRA;
     ss[i] = 0.f;
-    int gm = m0 + a_r[i];
+    // rows past M are clamped to the last row: their products land in rows that are never stored
+    int gm = min(m0 + a_r[i], M - 1);
     arow[i] = nullptr;
-    if (gm < M) {
+    {
       if constexpr (AM == A_TOK) {
         int b = gm / p.nq, t = gm % p.nq;
         const float* src = (t < p.n0) ? p.src0 + (long)b * p.stride0 + (long)t * K
@@ -97,32 +109,34 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
     int id = tid + i * 256;
     b_r[i] = id / CPRB;
     b_kc[i] = id % CPRB;
-    int gn = n0 + b_r[i];
-    brow[i] = gn < N ? reinterpret_cast<const char*>(reinterpret_cast<const T*>(p.W) + (long)gn * K) : nullptr;
+    int gn = min(n0 + b_r[i], N - 1);  // clamped like the rows of A
+    brow[i] = reinterpret_cast<const char*>(reinterpret_cast<const T*>(p.W) + (long)gn * K);
   }
 
   // Two tiles are kept in flight in two register sets that alternate (no copies between them:
   // a copy would wait for the younger load), so the HBM latency of one tile overlaps the MFMA
   // work and LDS traffic of two others.
   uint4 ra0[NA], rb0[NB], ra1[NA], rb1[NB];
+  // Loads are unconditional (addresses clamped into range) so that the number of loads in flight
+  // is the same on every path and the compiler can wait for exactly the older tile; the K tail
+  // is zeroed when the registers are written to LDS.
   auto load_global = [&](int kt, uint4* xa, uint4* xb) {
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
-      int k = kt * BK + a_kc[i] * CHA;
-      xa[i] = make_uint4(0, 0, 0, 0);
-      if (arow[i] && k < K) xa[i] = *reinterpret_cast<const uint4*>(arow[i] + (long)k * (kASrcF32 ? 4 : 2));
+      const int k = min(kt * BK + a_kc[i] * CHA, K - CHA);
+      xa[i] = *reinterpret_cast<const uint4*>(arow[i] + (long)k * (kASrcF32 ? 4 : 2));
     }
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-      int k = kt * BK + b_kc[i] * CHB;
-      xb[i] = make_uint4(0, 0, 0, 0);
-      if (brow[i] && k < K) xb[i] = *reinterpret_cast<const uint4*>(brow[i] + (long)k * (int)sizeof(T));
+      const int k = min(kt * BK + b_kc[i] * CHB, K - CHB);
+      xb[i] = *reinterpret_cast<const uint4*>(brow[i] + (long)k * (int)sizeof(T));
     }
   };
-  auto store_lds = [&](int buf, uint4* ra, uint4* rb) {
+  auto store_lds = [&](int kt, int buf, uint4* ra, uint4* rb) {
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
       T* dst = As + (buf * BM + a_r[i]) * LDT + a_kc[i] * CHA;
+      if (kt * BK + a_kc[i] * CHA >= K) ra[i] = make_uint4(0, 0, 0, 0);
       if constexpr (kASrcF32) {
         float4 f = *reinterpret_cast<float4*>(&ra[i]);
         if constexpr (AM == A_NORM) ss[i] += f.x * f.x + f.y * f.y + f.z * f.z + f.w * f.w;
@@ -135,12 +149,21 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
           dst[3] = f.w;
         }
       } else {
+        if constexpr (AM == A_NORM) {
+          const bf16x8 v = *reinterpret_cast<const bf16x8*>(&ra[i]);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float f = (float)v[e];
+            ss[i] = fmaf(f, f, ss[i]);
+          }
+        }
         *reinterpret_cast<uint4*>(dst) = ra[i];
       }
     }
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
       T* dst = Bs + (buf * BN + b_r[i]) * LDT + b_kc[i] * CHB;
+      if (kt * BK + b_kc[i] * CHB >= K) rb[i] = make_uint4(0, 0, 0, 0);
       if constexpr (kBf) {
         *reinterpret_cast<uint4*>(dst) = rb[i];
       } else {
@@ -214,21 +237,30 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   };
   const int nk = (K + BK - 1) / BK;
   load_global(0, ra0, rb0);
-  if (nk > 1) load_global(1, ra1, rb1);
-  store_lds(0, ra0, rb0);
+  load_global(min(1, nk - 1), ra1, rb1);
+  store_lds(0, 0, ra0, rb0);
   __syncthreads();
-  for (int kt = 0; kt < nk; kt += 2) {
-    // even tile: lives in LDS buffer 0; set 1 holds tile kt+1, set 0 is free for tile kt+2
-    if (kt + 2 < nk) load_global(kt + 2, ra0, rb0);
+  int kt = 0;
+  // Steady state, two tiles per trip and no branches inside: tile kt sits in LDS buffer 0, register
+  // set 1 holds tile kt+1 (in flight), set 0 is free.  The scheduling barriers keep each prefetch
+  // ahead of the MFMA work it is meant to overlap.
+  for (; kt + 2 < nk; kt += 2) {
+    load_global(kt + 2, ra0, rb0);
+    __builtin_amdgcn_sched_barrier(0);
     compute(0);
-    if (kt + 1 < nk) store_lds(1, ra1, rb1);
+    store_lds(kt + 1, 1, ra1, rb1);
     __syncthreads();
-    if (kt + 1 >= nk) break;
-    // odd tile: LDS buffer 1; set 0 holds tile kt+2, set 1 is free for tile kt+3
-    if (kt + 3 < nk) load_global(kt + 3, ra1, rb1);
+    load_global(min(kt + 3, nk - 1), ra1, rb1);
+    __builtin_amdgcn_sched_barrier(0);
     compute(1);
-    if (kt + 2 < nk) store_lds(0, ra0, rb0);
+    store_lds(kt + 2, 0, ra0, rb0);
     __syncthreads();
+  }
+  compute(0);
+  if (kt + 1 < nk) {
+    store_lds(kt + 1, 1, ra1, rb1);
+    __syncthreads();
+    compute(1);
   }
 
   // ---- RMSNorm row scale --------------------------------------------------------------------
@@ -285,6 +317,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
       }
       if constexpr (EP == EP_STORE) {
         *reinterpret_cast<float4*>(p.Cf + (long)gm * N + gn) = v;
+        if (kBf && p.Cb) store4<T>(reinterpret_cast<T*>(p.Cb) + (long)gm * N + gn, v);
       } else if constexpr (EP == EP_RESID) {
         float4* dst = reinterpret_cast<float4*>(p.Cf + (long)gm * N + gn);
         float4 o = *dst;
@@ -293,6 +326,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
         o.z += v.z;
         o.w += v.w;
         *dst = o;
+        if (kBf && p.Cb) store4<T>(reinterpret_cast<T*>(p.Cb) + (long)gm * N + gn, o);
       } else if constexpr (EP == EP_GELU) {
         v.x = gelu_tanh(v.x);
         v.y = gelu_tanh(v.y);
@@ -344,19 +378,54 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   }
 }
 
+template <typename T, int BM, int BN, int BK>
+constexpr size_t gemm_smem_bytes() {
+  constexpr bool kBf = !std::is_same<T, float>::value;
+  constexpr int LDT = BK + (kBf ? 8 : 1);
+  constexpr size_t ab = 2 * (BM + BN) * LDT * sizeof(T), c = 64 * (BN + 4) * 4;
+  return (ab > c ? ab : c) + BM * 4;
+}
+
+template <typename T, int AM, int EP, int BM, int BN, int BK>
+static hipError_t launch_tile(const GemmP& p, hipStream_t st) {
+  constexpr size_t smem = gemm_smem_bytes<T, BM, BN, BK>();
+  const long tiles = (long)((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+  const unsigned grid = (unsigned)(((tiles + 7) / 8) * 8);  // padded so that every XCD gets a full run
+  hipLaunchKernelGGL((gemm_kernel<T, AM, EP, BM, BN, BK>), dim3(grid), dim3(256), smem, st, p);
+  return hipGetLastError();
+}
+
 template <typename T, int AM, int EP>
 static hipError_t launch_cfg(const GemmP& p, hipStream_t st) {
   constexpr bool kBf = !std::is_same<T, float>::value;
   if constexpr (kBf) {
-    long t128 = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
-    if (t128 >= 192) {
-      hipLaunchKernelGGL((gemm_kernel<T, AM, EP, 128, 128, 32>), dim3((unsigned)t128), dim3(256), 0, st, p);
-      return hipGetLastError();
-    }
+    const long t128 = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
+    if (t128 >= 192) return launch_tile<T, AM, EP, 128, 128, 64>(p, st);
+    return launch_tile<T, AM, EP, 64, 64, 64>(p, st);
+  } else {
+    return launch_tile<T, AM, EP, 64, 64, 16>(p, st);
   }
-  long t64 = (long)((p.M + 63) / 64) * ((p.N + 63) / 64);
-  hipLaunchKernelGGL((gemm_kernel<T, AM, EP, 64, 64, (kBf ? 64 : 16)>), dim3((unsigned)t64), dim3(256), 0, st, p);
-  return hipGetLastError();
+}
+
+template <typename T, int AM, int EP>
+static hipError_t raise_cfg() {
+  if constexpr (!std::is_same<T, float>::value) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, AM, EP, 128, 128, 64>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_smem_bytes<T, 128, 128, 64>());
+  }
+  return hipSuccess;
+}
+
+// The 128x128x64 tiles use more than 64 KB of dynamic LDS: opt in once, outside any stream capture.
+hipError_t prepare_gemm(int dtype) {
+  if (dtype != TSD_BF16) return hipSuccess;
+  hipError_t e;
+  if ((e = raise_cfg<bf16, A_TOK, EP_STORE>()) != hipSuccess) return e;
+  if ((e = raise_cfg<bf16, A_NORM, EP_QKV>()) != hipSuccess) return e;
+  if ((e = raise_cfg<bf16, A_ACT, EP_RESID>()) != hipSuccess) return e;
+  if ((e = raise_cfg<bf16, A_NORM, EP_GELU>()) != hipSuccess) return e;
+  if ((e = raise_cfg<bf16, A_NORM, EP_HEAD>()) != hipSuccess) return e;
+  return raise_cfg<bf16, A_NORM, EP_STORE>();
 }
 
 template <typename T>

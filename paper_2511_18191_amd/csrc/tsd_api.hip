@@ -48,7 +48,8 @@ struct tsd_ctx {
   float *mean, *sdev, *pending, *prev, *forecast, *znorm;
   long long* stat;
   float *X, *mu_q, *mu_p, *ell, *logu;
-  float* x;
+  float* x;   // residual stream, fp32
+  char* xb;   // its bf16 shadow (GEMM A operand in bf16 mode)
   char *qbuf, *abuf, *hbuf;
   int rows_max;
   int* count_out;
@@ -193,6 +194,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
   size_t o_ell = cv.take((size_t)B * K * 4), o_logu = cv.take((size_t)B * K * 4);
   const size_t Dm = std::max(c.target.d_model, c.draft.d_model), Fm = std::max(c.target.d_ff, c.draft.d_ff);
   const size_t rows = std::max((size_t)B * (K + 1), (size_t)c.max_tokens);
+  size_t o_xb = cv.take(rows * Dm * es);
   size_t o_x = cv.take(rows * Dm * 4), o_q = cv.take(rows * Dm * es), o_a = cv.take(rows * Dm * es), o_h = cv.take(rows * Fm * es);
   size_t o_cnt = cv.take(256), o_so = cv.take(256);
   if (ctx) {
@@ -218,6 +220,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
     ctx->ell = (float*)at(o_ell);
     ctx->logu = (float*)at(o_logu);
     ctx->x = (float*)at(o_x);
+    ctx->xb = at(o_xb);
     ctx->qbuf = at(o_q);
     ctx->abuf = at(o_a);
     ctx->hbuf = at(o_h);
@@ -288,6 +291,8 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
   g.n0 = ps.n0;
   g.W = md.W_e;
   g.Cf = ctx->x;
+  g.Cb = ctx->xb;
+  const void* xin = c.dtype == TSD_BF16 ? (const void*)ctx->xb : (const void*)ctx->x;  // A operand of the norm-fused GEMMs
   HIP_TRY(ctx, timed_launch(ctx, TSD_K_EMBED, 2.0 * M * D * P, st, [&] { return launch_gemm(c.dtype, A_TOK, EP_STORE, g, st); }));
   for (int l = 0; l < md.c.n_layers; ++l) {
     char* pool = md.kv_pool + (size_t)l * md.layer_pool_bytes;
@@ -297,7 +302,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     q.nq = ps.nq;
     q.N = 3 * D;
     q.K = D;
-    q.A = ctx->x;
+    q.A = xin;
     q.W = md.layers[l].Wqkv;
     q.q_out = ctx->qbuf;
     q.kv_pool = pool;
@@ -346,6 +351,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     o.A = ctx->abuf;
     o.W = md.layers[l].Wo;
     o.Cf = ctx->x;
+    o.Cb = ctx->xb;
     HIP_TRY(ctx, timed_launch(ctx, TSD_K_RESID, 2.0 * M * D * D, st, [&] { return launch_gemm(c.dtype, A_ACT, EP_RESID, o, st); }));
     GemmP f1;
     std::memset(&f1, 0, sizeof(f1));
@@ -353,7 +359,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     f1.nq = ps.nq;
     f1.N = F;
     f1.K = D;
-    f1.A = ctx->x;
+    f1.A = xin;
     f1.W = md.layers[l].W1;
     f1.Ct = ctx->hbuf;
     HIP_TRY(ctx, timed_launch(ctx, TSD_K_GELU, 2.0 * M * D * F, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_GELU, f1, st); }));
@@ -366,6 +372,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     f2.A = ctx->hbuf;
     f2.W = md.layers[l].W2;
     f2.Cf = ctx->x;
+    f2.Cb = ctx->xb;
     HIP_TRY(ctx, timed_launch(ctx, TSD_K_RESID, 2.0 * M * D * F, st, [&] { return launch_gemm(c.dtype, A_ACT, EP_RESID, f2, st); }));
   }
   if (ps.out) {
@@ -375,7 +382,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     h.nq = ps.nq;
     h.N = P;
     h.K = D;
-    h.A = ctx->x;
+    h.A = xin;
     h.W = md.W_h;
     h.out = ps.out;
     h.out_stride_b = ps.out_stride_b;
@@ -529,6 +536,14 @@ int tsd_create(const tsd_config* cfg, void* arena_dev, size_t arena_bytes, tsd_c
     if (e == hipSuccess) e = hipMemcpy(md.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
       std::string msg = std::string("copying rotary tables: ") + hipGetErrorString(e);
+      delete ctx;
+      return fail(nullptr, TSD_E_HIP, msg);
+    }
+  }
+  {
+    hipError_t e = prepare_gemm(cfg->dtype);
+    if (e != hipSuccess) {
+      std::string msg = std::string("raising the GEMM kernels' LDS limit: ") + hipGetErrorString(e);
       delete ctx;
       return fail(nullptr, TSD_E_HIP, msg);
     }

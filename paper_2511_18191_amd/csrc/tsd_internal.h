@@ -46,6 +46,7 @@ struct GemmP {
   const void* W;  // T [N][K]: transposed weights
   // outputs
   float* Cf;      // EP_STORE / EP_RESID: [M][N]
+  void* Cb;       // EP_STORE / EP_RESID, bf16 mode: shadow copy of the result in bf16 (nullable)
   void* Ct;       // EP_GELU: T [M][N]
   // EP_QKV
   void* q_out;    // T [M][D]
@@ -83,6 +84,7 @@ struct AttnP {
 
 // ---- launchers (each returns the hipError_t of the launch) ---------------------------------
 hipError_t launch_gemm(int dtype, int amode, int epi, const GemmP& p, hipStream_t st);
+hipError_t prepare_gemm(int dtype);
 // s_max: upper bound on (position of the pass's last token) + 1 over all series; sizes the score buffer.
 hipError_t launch_attention(int dtype, const AttnP& p, int s_max, hipStream_t st);
 // dynamic LDS the attention kernel needs for up to s_max cached tokens (must stay <= 160 KB)
