@@ -91,7 +91,7 @@ def kernel_rooflines(sess, dtype, steps):
         n, ms, work = sess.profile_end()
         if n == 0:
             continue
-        hbm = name in ("attn", "accept")
+        hbm = name in ("attn", "accept", "route")
         achieved = work / (ms * 1e-3) / (1e9 if hbm else 1e12)
         peak = HBM_PEAK if hbm else PEAK[dtype]
         out[name] = dict(bound="hbm" if hbm else "mfma", achieved=achieved, peak=peak, unit="GB/s" if hbm else "TFLOP/s",

@@ -67,8 +67,8 @@ typedef struct tsd_ctx tsd_ctx; /* opaque */
 
 typedef struct {
   int32_t n_layers, d_model, n_heads, d_ff;
-  int32_t n_experts; /* 0 = dense FFN */
-  int32_t top_k;     /* used when n_experts > 0 */
+  int32_t n_experts; /* 0 = dense FFN, else 2..16 routed experts          */
+  int32_t top_k;     /* experts per token when n_experts > 0, 1..min(4, E) */
 } tsd_model_cfg;
 
 typedef struct {
@@ -200,8 +200,9 @@ int tsd_set_sigma(tsd_ctx* ctx, float sigma_p, float sigma_q);
  * for the stream, returns the number of launches, their summed duration in milliseconds and their
  * summed algorithmic work (GEMM families: 2*M*N*K flops; TSD_K_ATTN: bytes of the K and V rows
  * each (series, head) must read, counted with the shortest possible history N-1, plus q and
- * output rows; TSD_K_ACCEPT: bytes of X, mu_p read and the committed patch written), and
- * switches the tap off. */
+ * output rows; TSD_K_ACCEPT: bytes of X, mu_p read and the committed patch written; TSD_K_ROUTE:
+ * bytes of the rows read and written; the grouped expert GEMMs count under TSD_K_GELU and
+ * TSD_K_RESID), and switches the tap off. */
 #define TSD_K_EMBED 0  /* patch embedding GEMM                          */
 #define TSD_K_QKV 1    /* RMSNorm + QKV GEMM + RoPE + KV-cache write    */
 #define TSD_K_ATTN 2   /* paged causal attention                        */
@@ -209,7 +210,8 @@ int tsd_set_sigma(tsd_ctx* ctx, float sigma_p, float sigma_q);
 #define TSD_K_GELU 4   /* RMSNorm + FFN-up GEMM + GELU                  */
 #define TSD_K_HEAD 5   /* RMSNorm + output-head GEMM                    */
 #define TSD_K_ACCEPT 6 /* acceptance + commit + rollback                */
-#define TSD_K_COUNT 7
+#define TSD_K_ROUTE 7  /* routed FFN: router, expert sort, gated combine (bytes) */
+#define TSD_K_COUNT 8
 int tsd_profile_begin(tsd_ctx* ctx, int kernel_class);
 int tsd_profile_end(tsd_ctx* ctx, int64_t* launches_host, double* ms_host, double* work_host, void* stream);
 

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 TSD_F32, TSD_BF16 = 0, 1
 TSD_TARGET, TSD_DRAFT = 0, 1
 TSD_FLAG_SCRAMBLE_PAGES, TSD_FLAG_NO_TEMPERING, TSD_FLAG_NO_GRAPH = 1, 2, 4
-KERNEL_CLASSES = ["embed", "qkv", "attn", "resid", "gelu", "head", "accept"]   # TSD_K_* order
+KERNEL_CLASSES = ["embed", "qkv", "attn", "resid", "gelu", "head", "accept", "route"]   # TSD_K_* order
 
 
 class TsdModelCfg(C.Structure):

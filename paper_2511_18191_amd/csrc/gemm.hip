@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   // w lands on XCD w % 8.  Give every XCD one contiguous run of the tile list, and order the
   // list in groups of 8 tile columns walked row by row: the ~32 tiles an XCD runs at a time then
   // form a 4 x 8 rectangle that shares 4 row panels and 8 column panels through that L2.
-  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const int tiles_m = p.tile_map ? p.n_mtiles : (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const int n_tiles = tiles_m * tiles_n;
   const int per_xcd = (n_tiles + 7) >> 3;
   const int lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -64,7 +64,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   const int gc = lin / (GW * tiles_m), rem = lin - gc * (GW * tiles_m);
   const int gw = min(GW, tiles_n - gc * GW);
   const int tm = rem / gw, tn = gc * GW + rem - tm * gw;
-  const int m0 = tm * BM, n0 = tn * BN;
+  int m0 = tm * BM, m_lim = M;
+  const int n0 = tn * BN;
+  const T* Wbase = reinterpret_cast<const T*>(p.W);
+  if (p.tile_map) {  // routed FFN: this row tile belongs to one expert's run of slots
+    const int4 tmap = reinterpret_cast<const int4*>(p.tile_map)[tm];
+    if (tmap.x < 0) return;
+    m0 = tmap.y;
+    m_lim = tmap.z;
+    Wbase += (long)tmap.x * p.w_stride;
+  }
 
   // ---- A loader set-up ----------------------------------------------------------------------
   constexpr bool kASrcF32 = (AM == A_TOK) || !kBf;   // source rows are fp32 (bf16 mode reads the bf16 shadow of the residual)
@@ -82,7 +91,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
     a_kc[i] = id % CPRA;
     ss[i] = 0.f;
     // rows past M are clamped to the last row: their products land in rows that are never stored
-    int gm = min(m0 + a_r[i], M - 1);
+    int gm = min(m0 + a_r[i], m_lim - 1);
+    if (p.src_row) gm = p.src_row[gm];
     arow[i] = nullptr;
     {
       if constexpr (AM == A_TOK) {
@@ -110,7 +120,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
     b_r[i] = id / CPRB;
     b_kc[i] = id % CPRB;
     int gn = min(n0 + b_r[i], N - 1);  // clamped like the rows of A
-    brow[i] = reinterpret_cast<const char*>(reinterpret_cast<const T*>(p.W) + (long)gn * K);
+    brow[i] = reinterpret_cast<const char*>(Wbase + (long)gn * K);
   }
 
   // Two tiles are kept in flight in two register sets that alternate (no copies between them:
@@ -305,7 +315,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
       const int g = tid + it * 256;
       const int row = g / GPR, col = (g % GPR) * 4;
       const int gm = m0 + pass * 64 + row, gn = n0 + col;
-      if (gm >= M || gn >= N) continue;
+      if (gm >= m_lim || gn >= N) continue;
       float4 v = *reinterpret_cast<const float4*>(Cs + row * LDC + col);
       float rs = 1.f;
       if constexpr (AM == A_NORM) {
@@ -389,18 +399,25 @@ constexpr size_t gemm_smem_bytes() {
 template <typename T, int AM, int EP, int BM, int BN, int BK>
 static hipError_t launch_tile(const GemmP& p, hipStream_t st) {
   constexpr size_t smem = gemm_smem_bytes<T, BM, BN, BK>();
-  const long tiles = (long)((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+  const long tiles = (long)(p.tile_map ? p.n_mtiles : (p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
   const unsigned grid = (unsigned)(((tiles + 7) / 8) * 8);  // padded so that every XCD gets a full run
   hipLaunchKernelGGL((gemm_kernel<T, AM, EP, BM, BN, BK>), dim3(grid), dim3(256), smem, st, p);
   return hipGetLastError();
+}
+
+// Row-tile size the launcher will use for an M x N product (the routed FFN builds its tile map for it).
+int gemm_row_tile(int dtype, int M, int N, int force_bm) {
+  if (dtype != TSD_BF16) return 64;
+  if (force_bm) return force_bm;
+  const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+  return t128 >= 192 ? 128 : 64;
 }
 
 template <typename T, int AM, int EP>
 static hipError_t launch_cfg(const GemmP& p, hipStream_t st) {
   constexpr bool kBf = !std::is_same<T, float>::value;
   if constexpr (kBf) {
-    const long t128 = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
-    if (t128 >= 192) return launch_tile<T, AM, EP, 128, 128, 64>(p, st);
+    if (gemm_row_tile(TSD_BF16, p.M, p.N, p.force_bm) == 128) return launch_tile<T, AM, EP, 128, 128, 64>(p, st);
     return launch_tile<T, AM, EP, 64, 64, 64>(p, st);
   } else {
     return launch_tile<T, AM, EP, 64, 64, 16>(p, st);
@@ -425,6 +442,7 @@ hipError_t prepare_gemm(int dtype) {
   if ((e = raise_cfg<bf16, A_ACT, EP_RESID>()) != hipSuccess) return e;
   if ((e = raise_cfg<bf16, A_NORM, EP_GELU>()) != hipSuccess) return e;
   if ((e = raise_cfg<bf16, A_NORM, EP_HEAD>()) != hipSuccess) return e;
+  if ((e = raise_cfg<bf16, A_ACT, EP_STORE>()) != hipSuccess) return e;
   return raise_cfg<bf16, A_NORM, EP_STORE>();
 }
 
@@ -436,6 +454,7 @@ static hipError_t launch_t(int amode, int epi, const GemmP& p, hipStream_t st) {
   if (amode == A_NORM && epi == EP_GELU) return launch_cfg<T, A_NORM, EP_GELU>(p, st);
   if (amode == A_NORM && epi == EP_HEAD) return launch_cfg<T, A_NORM, EP_HEAD>(p, st);
   if (amode == A_NORM && epi == EP_STORE) return launch_cfg<T, A_NORM, EP_STORE>(p, st);
+  if (amode == A_ACT && epi == EP_STORE) return launch_cfg<T, A_ACT, EP_STORE>(p, st);
   return hipErrorInvalidValue;
 }
 

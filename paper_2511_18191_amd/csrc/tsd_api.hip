@@ -15,7 +15,8 @@ namespace {
 thread_local std::string g_err;  // errors of calls that have no handle
 
 struct Layer {
-  char *Wqkv, *Wo, *W1, *W2;
+  char *Wqkv, *Wo, *W1, *W2;  // routed FFN: W1 = [E][F][D], W2 = [E][D][F]
+  float* Wr;                  // routed FFN: router [E][D], fp32 (NULL for a dense FFN)
 };
 struct ModelDev {
   tsd_model_cfg c;
@@ -52,6 +53,12 @@ struct tsd_ctx {
   char* xb;   // its bf16 shadow (GEMM A operand in bf16 mode)
   char *qbuf, *abuf, *hbuf;
   int rows_max;
+  int* moe_ids;
+  float* moe_gates;
+  int *moe_src, *moe_slot;
+  char* moe_tmap;
+  float* moe_Y;
+  char* moe_h;
   int* count_out;
   long long* stats_out;
   // forecast in flight
@@ -99,7 +106,11 @@ int check_model(const tsd_model_cfg& m, const char* name, std::string& why) {
   int hd = m.d_model / m.n_heads;
   if (hd != 16 && hd != 32 && hd != 64) return bad("head_dim must be 16, 32 or 64");
   if (m.d_ff < 8 || m.d_ff % 8) return bad("d_ff must be a positive multiple of 8");
-  if (m.n_experts != 0) return bad("routed FFN (n_experts > 0) is not supported by this build");
+  if (m.n_experts != 0) {
+    if (m.n_experts < 2 || m.n_experts > 16) return bad("n_experts must be 0 (dense) or in 2..16");
+    if (m.top_k < 1 || m.top_k > 4 || m.top_k > m.n_experts) return bad("top_k must be in 1..min(4, n_experts)");
+    if (m.d_model % 4) return bad("d_model must be a multiple of 4");
+  }
   return TSD_OK;
 }
 
@@ -166,9 +177,11 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
       md->layers.resize(m.n_layers);
       md->loaded = false;
     }
+    const size_t nE = m.n_experts > 0 ? m.n_experts : 1;
     for (int l = 0; l < m.n_layers; ++l) {
-      size_t oq = cv.take(3 * D * D * es), oo = cv.take(D * D * es), o1 = cv.take(D * F * es), o2 = cv.take(F * D * es);
-      if (md) md->layers[l] = Layer{at(oq), at(oo), at(o1), at(o2)};
+      size_t oq = cv.take(3 * D * D * es), oo = cv.take(D * D * es), o1 = cv.take(nE * D * F * es), o2 = cv.take(nE * F * D * es);
+      size_t orr = m.n_experts > 0 ? cv.take(nE * D * 4) : 0;
+      if (md) md->layers[l] = Layer{at(oq), at(oo), at(o1), at(o2), m.n_experts > 0 ? (float*)at(orr) : nullptr};
     }
     o = cv.take(D * P * es);
     if (md) md->W_h = at(o);
@@ -197,6 +210,19 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
   size_t o_xb = cv.take(rows * Dm * es);
   size_t o_x = cv.take(rows * Dm * 4), o_q = cv.take(rows * Dm * es), o_a = cv.take(rows * Dm * es), o_h = cv.take(rows * Fm * es);
   size_t o_cnt = cv.take(256), o_so = cv.take(256);
+  // routed FFN scratch: one slot per (token, chosen expert)
+  const size_t topk = std::max(c.target.n_experts > 0 ? c.target.top_k : 0, c.draft.n_experts > 0 ? c.draft.top_k : 0);
+  const size_t slots = rows * topk, nEmax = std::max(c.target.n_experts, c.draft.n_experts);
+  size_t o_ids = 0, o_gates = 0, o_src = 0, o_slot = 0, o_tmap = 0, o_Y = 0, o_hx = 0;
+  if (topk) {
+    o_ids = cv.take(slots * 4);
+    o_gates = cv.take(slots * 4);
+    o_src = cv.take(slots * 4);
+    o_slot = cv.take(slots * 4);
+    o_tmap = cv.take((slots / 64 + nEmax + 2) * 16);
+    o_Y = cv.take(slots * Dm * 4);
+    o_hx = cv.take(slots * Fm * es);
+  }
   if (ctx) {
     ctx->es = (int)es;
     ctx->pages_per_series = pps;
@@ -226,14 +252,21 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
     ctx->hbuf = at(o_h);
     ctx->rows_max = (int)rows;
     ctx->count_out = (int*)at(o_cnt);
+    ctx->moe_ids = topk ? (int*)at(o_ids) : nullptr;
+    ctx->moe_gates = (float*)at(o_gates);
+    ctx->moe_src = (int*)at(o_src);
+    ctx->moe_slot = (int*)at(o_slot);
+    ctx->moe_tmap = at(o_tmap);
+    ctx->moe_Y = (float*)at(o_Y);
+    ctx->moe_h = at(o_hx);
     ctx->stats_out = (long long*)at(o_so);
   }
   return (cv.off + 255) & ~(size_t)255;
 }
 
 size_t weights_count(const tsd_model_cfg& m, int P) {
-  size_t D = m.d_model, F = m.d_ff;
-  size_t per_layer = D + 4 * D * D + D + 2 * D * F;
+  size_t D = m.d_model, F = m.d_ff, E = m.n_experts;
+  size_t per_layer = D + 4 * D * D + D + (E > 0 ? D * E + E * 2 * D * F : 2 * D * F);
   return (size_t)P * D + per_layer * m.n_layers + D + D * P;
 }
 
@@ -353,6 +386,51 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     o.Cf = ctx->x;
     o.Cb = ctx->xb;
     HIP_TRY(ctx, timed_launch(ctx, TSD_K_RESID, 2.0 * M * D * D, st, [&] { return launch_gemm(c.dtype, A_ACT, EP_RESID, o, st); }));
+    if (md.c.n_experts > 0) {
+      // routed FFN: router -> stable sort of (token, choice) by expert -> grouped up/down GEMMs -> gated combine
+      const int E = md.c.n_experts, topk = md.c.top_k, slots = M * topk;
+      const int bm = gemm_row_tile(c.dtype, slots, F, 0);
+      const int n_mtiles = (slots + bm - 1) / bm + E;
+      HIP_TRY(ctx, timed_launch(ctx, TSD_K_ROUTE, 4.0 * M * D, st, [&] {
+        return launch_router(ctx->x, md.layers[l].Wr, M, D, E, topk, ctx->moe_ids, ctx->moe_gates, st);
+      }));
+      HIP_TRY(ctx, timed_launch(ctx, TSD_K_ROUTE, 12.0 * slots, st, [&] {
+        return launch_permute(ctx->moe_ids, slots, topk, E, bm, n_mtiles, ctx->moe_src, ctx->moe_slot, ctx->moe_tmap, st);
+      }));
+      GemmP f1;
+      std::memset(&f1, 0, sizeof(f1));
+      f1.M = slots;
+      f1.nq = ps.nq;
+      f1.N = F;
+      f1.K = D;
+      f1.A = xin;
+      f1.W = md.layers[l].W1;
+      f1.Ct = ctx->moe_h;
+      f1.tile_map = ctx->moe_tmap;
+      f1.src_row = ctx->moe_src;
+      f1.w_stride = (long)F * D;
+      f1.n_mtiles = n_mtiles;
+      f1.force_bm = bm;
+      HIP_TRY(ctx, timed_launch(ctx, TSD_K_GELU, 2.0 * slots * D * F, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_GELU, f1, st); }));
+      GemmP f2;
+      std::memset(&f2, 0, sizeof(f2));
+      f2.M = slots;
+      f2.nq = ps.nq;
+      f2.N = D;
+      f2.K = F;
+      f2.A = ctx->moe_h;
+      f2.W = md.layers[l].W2;
+      f2.Cf = ctx->moe_Y;
+      f2.tile_map = ctx->moe_tmap;
+      f2.w_stride = (long)D * F;
+      f2.n_mtiles = n_mtiles;
+      f2.force_bm = bm;
+      HIP_TRY(ctx, timed_launch(ctx, TSD_K_RESID, 2.0 * slots * D * F, st, [&] { return launch_gemm(c.dtype, A_ACT, EP_STORE, f2, st); }));
+      HIP_TRY(ctx, timed_launch(ctx, TSD_K_ROUTE, 4.0 * D * (2.0 * M + slots), st, [&] {
+        return launch_combine(c.dtype, ctx->moe_Y, ctx->moe_slot, ctx->moe_gates, ctx->x, c.dtype == TSD_BF16 ? ctx->xb : nullptr, M, D, topk, st);
+      }));
+      continue;
+    }
     GemmP f1;
     std::memset(&f1, 0, sizeof(f1));
     f1.M = M;
@@ -601,10 +679,23 @@ int tsd_load_weights(tsd_ctx* ctx, int which, const float* blob_dev, size_t n_fl
     w += D * D;
     const float* g2 = w;
     w += D;
-    HIP_TRY(ctx, pack(w, g2, md.layers[l].W1, (int)D, (int)F));
-    w += D * F;
-    HIP_TRY(ctx, pack(w, nullptr, md.layers[l].W2, (int)F, (int)D));
-    w += F * D;
+    if (md.c.n_experts > 0) {
+      const size_t E = md.c.n_experts;
+      PackP pr{w, g2, md.layers[l].Wr, (int)D, (int)E};  // router stays fp32
+      HIP_TRY(ctx, launch_pack(TSD_F32, pr, st));
+      w += D * E;
+      for (size_t e = 0; e < E; ++e) {
+        HIP_TRY(ctx, pack(w, g2, md.layers[l].W1 + e * F * D * es, (int)D, (int)F));
+        w += D * F;
+        HIP_TRY(ctx, pack(w, nullptr, md.layers[l].W2 + e * D * F * es, (int)F, (int)D));
+        w += F * D;
+      }
+    } else {
+      HIP_TRY(ctx, pack(w, g2, md.layers[l].W1, (int)D, (int)F));
+      w += D * F;
+      HIP_TRY(ctx, pack(w, nullptr, md.layers[l].W2, (int)F, (int)D));
+      w += F * D;
+    }
   }
   const float* gf = w;
   w += D;

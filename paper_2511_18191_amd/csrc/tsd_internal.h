@@ -61,6 +61,12 @@ struct GemmP {
   int D, Hh, hd, PT;
   int pt_shift;  // log2(PT)
   int v_transposed;  // V block of a page is [head][dim][token]
+  // grouped (routed-FFN) mode: the row tiles come from a device-side map, one expert per tile
+  const void* tile_map;  // int4 per row tile: (expert or -1, first slot, end slot of the expert, 0); NULL = dense
+  const int* src_row;    // A row of slot s is src_row[s] (NULL: the slot itself)
+  long w_stride;         // elements between consecutive experts' matrices in W
+  int n_mtiles;          // entries of tile_map
+  int force_bm;          // row-tile size the map was built for (0 = pick by problem size)
   // EP_HEAD
   float* out;
   long out_stride_b;
@@ -85,6 +91,7 @@ struct AttnP {
 // ---- launchers (each returns the hipError_t of the launch) ---------------------------------
 hipError_t launch_gemm(int dtype, int amode, int epi, const GemmP& p, hipStream_t st);
 hipError_t prepare_gemm(int dtype);
+int gemm_row_tile(int dtype, int M, int N, int force_bm);
 // s_max: upper bound on (position of the pass's last token) + 1 over all series; sizes the score buffer.
 hipError_t launch_attention(int dtype, const AttnP& p, int s_max, hipStream_t st);
 // dynamic LDS the attention kernel needs for up to s_max cached tokens (must stay <= 160 KB)
@@ -138,6 +145,13 @@ struct AcceptP {
   unsigned key0, key1;
 };
 hipError_t launch_accept(const AcceptP& p, hipStream_t st);
+
+hipError_t launch_router(const float* x, const float* Wr, int M, int D, int E, int topk, int* ids, float* gates,
+                         hipStream_t st);
+hipError_t launch_permute(const int* ids, int n_assign, int topk, int E, int BM, int n_mtiles, int* src_row,
+                          int* slot_of, void* tile_map, hipStream_t st);
+hipError_t launch_combine(int dtype, const float* Y, const int* slot_of, const float* gates, float* x, void* xb, int M,
+                          int D, int topk, hipStream_t st);
 
 hipError_t launch_forecast_out(const float* forecast, const float* mean, const float* sdev, const int* committed,
                                float* out, int B, int P, int T, int H, hipStream_t st);

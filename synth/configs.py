@@ -75,6 +75,9 @@ CONFIGS.update({
     # bf16 MoE target like cfg5
     "mini5": RunCfg("mini5", ModelCfg(2, 128, 2, 256, 8, 2), ModelCfg(1, 64, 1, 256), 32, 6, 32 * 12, 32 * 9, 8,
                     0.6, "bf16", "smooth_noisy_mix", 2005),
+    # fp32 MoE (tight tolerance on routing, grouped GEMMs and the combine)
+    "mini5_fp32": RunCfg("mini5_fp32", ModelCfg(2, 128, 2, 256, 8, 2), ModelCfg(1, 64, 1, 256), 32, 6, 32 * 12, 32 * 9,
+                         8, 0.6, "fp32", "smooth_noisy_mix", 2005),
     # fp32 variant of mini2 (tight tolerance on the head_dim-64 kernels)
     "mini2_fp32": RunCfg("mini2_fp32", ModelCfg(2, 128, 2, 512), ModelCfg(1, 64, 1, 256), 96, 5, 96 * 6,
                          96 * 3 + 48, 4, 0.5, "fp32", "seasonal_walk_t", 2002),
