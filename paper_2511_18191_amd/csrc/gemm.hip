@@ -38,14 +38,20 @@ __device__ __forceinline__ void store4<bf16>(bf16* dst, float4 v) {
 template <typename T, int AM, int EP, int BM, int BN, int BK>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   constexpr bool kBf = !std::is_same<T, float>::value;
+  constexpr bool kNorm = (AM == A_NORM || AM == A_NORM32);  // RMSNorm fused as a row scale
+  // fp32 A rows in bf16 mode (patches, and the residual feeding the output head) are split into
+  // hi + lo bf16 parts, each multiplied by the same B fragment: the small GEMMs at the two ends of
+  // the model then carry ~16 mantissa bits of their input instead of 8.
+  constexpr bool kSplit = kBf && (AM == A_TOK || AM == A_NORM32);
+  constexpr int NAS = kSplit ? 2 : 1;  // A tiles kept in LDS per buffer
   constexpr int LDT = BK + (kBf ? 8 : 1);  // padded LDS row, in elements
   constexpr int LDC = BN + 4;
-  constexpr int AB_BYTES = 2 * (BM + BN) * LDT * (int)sizeof(T);
+  constexpr int AB_BYTES = 2 * (NAS * BM + BN) * LDT * (int)sizeof(T);
   constexpr int C_BYTES = 64 * LDC * 4;
   constexpr int SMEM = AB_BYTES > C_BYTES ? AB_BYTES : C_BYTES;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // SMEM + BM * 4 bytes
-  T* As = reinterpret_cast<T*>(smem);  // [2][BM][LDT]
-  T* Bs = As + 2 * BM * LDT;           // [2][BN][LDT]
+  T* As = reinterpret_cast<T*>(smem);  // [2][NAS][BM][LDT]
+  T* Bs = As + 2 * NAS * BM * LDT;     // [2][BN][LDT]
   float* Cs = reinterpret_cast<float*>(smem);  // [64][LDC], reuses the tile buffers
   float* row_scale = reinterpret_cast<float*>(smem + SMEM);  // [BM]
 
@@ -76,7 +82,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   }
 
   // ---- A loader set-up ----------------------------------------------------------------------
-  constexpr bool kASrcF32 = (AM == A_TOK) || !kBf;   // source rows are fp32 (bf16 mode reads the bf16 shadow of the residual)
+  constexpr bool kASrcF32 = (AM == A_TOK) || (AM == A_NORM32) || !kBf;   // source rows are fp32 (bf16 mode reads the bf16 shadow of the residual)
   constexpr int CHA = kASrcF32 ? 4 : 8;              // elements per 16-byte chunk
   constexpr int CPRA = BK / CHA;                     // chunks per tile row
   constexpr int NA = BM * CPRA / 256;
@@ -145,12 +151,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   auto store_lds = [&](int kt, int buf, uint4* ra, uint4* rb) {
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
-      T* dst = As + (buf * BM + a_r[i]) * LDT + a_kc[i] * CHA;
+      T* dst = As + ((buf * NAS) * BM + a_r[i]) * LDT + a_kc[i] * CHA;
       if (kt * BK + a_kc[i] * CHA >= K) ra[i] = make_uint4(0, 0, 0, 0);
       if constexpr (kASrcF32) {
         float4 f = *reinterpret_cast<float4*>(&ra[i]);
-        if constexpr (AM == A_NORM) ss[i] += f.x * f.x + f.y * f.y + f.z * f.z + f.w * f.w;
-        if constexpr (kBf) {
+        if constexpr (kNorm) ss[i] += f.x * f.x + f.y * f.y + f.z * f.z + f.w * f.w;
+        if constexpr (kSplit) {
+          const float4 hi = make_float4((float)(bf16)f.x, (float)(bf16)f.y, (float)(bf16)f.z, (float)(bf16)f.w);
+          store4<bf16>(reinterpret_cast<bf16*>(dst), hi);
+          store4<bf16>(reinterpret_cast<bf16*>(dst + BM * LDT), make_float4(f.x - hi.x, f.y - hi.y, f.z - hi.z, f.w - hi.w));
+        } else if constexpr (kBf) {
           store4<bf16>(reinterpret_cast<bf16*>(dst), f);
         } else {
           dst[0] = f.x;
@@ -159,7 +169,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
           dst[3] = f.w;
         }
       } else {
-        if constexpr (AM == A_NORM) {
+        if constexpr (kNorm) {
           const bf16x8 v = *reinterpret_cast<const bf16x8*>(&ra[i]);
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
@@ -211,24 +221,28 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
 
   // ---- main loop ----------------------------------------------------------------------------
   auto compute = [&](int buf) {
-    const T* at = As + buf * BM * LDT;
+    const T* at = As + buf * NAS * BM * LDT;
     const T* bt = Bs + buf * BN * LDT;
     if constexpr (kBf) {
 #pragma unroll
       for (int k16 = 0; k16 < BK / 16; ++k16) {
-        bf16x8 af[TM], bfr[TN];
+        bf16x8 af[NAS][TM], bfr[TN];
         const int ko = k16 * 16 + (lane >> 5) * 8;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-          af[i] = *reinterpret_cast<const bf16x8*>(at + (wm * WTM + i * 32 + (lane & 31)) * LDT + ko);
+        for (int h = 0; h < NAS; ++h)
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+            af[h][i] = *reinterpret_cast<const bf16x8*>(at + (h * BM + wm * WTM + i * 32 + (lane & 31)) * LDT + ko);
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           bfr[j] = *reinterpret_cast<const bf16x8*>(bt + (wn * WTN + j * 32 + (lane & 31)) * LDT + ko);
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int h = NAS - 1; h >= 0; --h)  // low part first, then the high part
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[h][i], bfr[j], acc[i][j], 0, 0, 0);
       }
     } else {
 #pragma unroll
@@ -274,7 +288,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   }
 
   // ---- RMSNorm row scale --------------------------------------------------------------------
-  if constexpr (AM == A_NORM) {
+  if constexpr (kNorm) {
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
       float s = ss[i];
@@ -318,7 +332,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
       if (gm >= m_lim || gn >= N) continue;
       float4 v = *reinterpret_cast<const float4*>(Cs + row * LDC + col);
       float rs = 1.f;
-      if constexpr (AM == A_NORM) {
+      if constexpr (kNorm) {
         rs = row_scale[pass * 64 + row];
         v.x *= rs;
         v.y *= rs;
@@ -388,17 +402,18 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   }
 }
 
-template <typename T, int BM, int BN, int BK>
+template <typename T, int AM, int BM, int BN, int BK>
 constexpr size_t gemm_smem_bytes() {
   constexpr bool kBf = !std::is_same<T, float>::value;
   constexpr int LDT = BK + (kBf ? 8 : 1);
-  constexpr size_t ab = 2 * (BM + BN) * LDT * sizeof(T), c = 64 * (BN + 4) * 4;
+  constexpr int nas = (kBf && (AM == A_TOK || AM == A_NORM32)) ? 2 : 1;
+  constexpr size_t ab = 2 * (nas * BM + BN) * LDT * sizeof(T), c = 64 * (BN + 4) * 4;
   return (ab > c ? ab : c) + BM * 4;
 }
 
 template <typename T, int AM, int EP, int BM, int BN, int BK>
 static hipError_t launch_tile(const GemmP& p, hipStream_t st) {
-  constexpr size_t smem = gemm_smem_bytes<T, BM, BN, BK>();
+  constexpr size_t smem = gemm_smem_bytes<T, AM, BM, BN, BK>();
   const long tiles = (long)(p.tile_map ? p.n_mtiles : (p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
   const unsigned grid = (unsigned)(((tiles + 7) / 8) * 8);  // padded so that every XCD gets a full run
   hipLaunchKernelGGL((gemm_kernel<T, AM, EP, BM, BN, BK>), dim3(grid), dim3(256), smem, st, p);
@@ -428,7 +443,7 @@ template <typename T, int AM, int EP>
 static hipError_t raise_cfg() {
   if constexpr (!std::is_same<T, float>::value) {
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, AM, EP, 128, 128, 64>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_smem_bytes<T, 128, 128, 64>());
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_smem_bytes<T, AM, 128, 128, 64>());
   }
   return hipSuccess;
 }
@@ -441,7 +456,7 @@ hipError_t prepare_gemm(int dtype) {
   if ((e = raise_cfg<bf16, A_NORM, EP_QKV>()) != hipSuccess) return e;
   if ((e = raise_cfg<bf16, A_ACT, EP_RESID>()) != hipSuccess) return e;
   if ((e = raise_cfg<bf16, A_NORM, EP_GELU>()) != hipSuccess) return e;
-  if ((e = raise_cfg<bf16, A_NORM, EP_HEAD>()) != hipSuccess) return e;
+  if ((e = raise_cfg<bf16, A_NORM32, EP_HEAD>()) != hipSuccess) return e;
   if ((e = raise_cfg<bf16, A_ACT, EP_STORE>()) != hipSuccess) return e;
   return raise_cfg<bf16, A_NORM, EP_STORE>();
 }
@@ -452,7 +467,7 @@ static hipError_t launch_t(int amode, int epi, const GemmP& p, hipStream_t st) {
   if (amode == A_NORM && epi == EP_QKV) return launch_cfg<T, A_NORM, EP_QKV>(p, st);
   if (amode == A_ACT && epi == EP_RESID) return launch_cfg<T, A_ACT, EP_RESID>(p, st);
   if (amode == A_NORM && epi == EP_GELU) return launch_cfg<T, A_NORM, EP_GELU>(p, st);
-  if (amode == A_NORM && epi == EP_HEAD) return launch_cfg<T, A_NORM, EP_HEAD>(p, st);
+  if (amode == A_NORM32 && epi == EP_HEAD) return launch_cfg<T, A_NORM32, EP_HEAD>(p, st);
   if (amode == A_NORM && epi == EP_STORE) return launch_cfg<T, A_NORM, EP_STORE>(p, st);
   if (amode == A_ACT && epi == EP_STORE) return launch_cfg<T, A_ACT, EP_STORE>(p, st);
   return hipErrorInvalidValue;

@@ -10,6 +10,7 @@ namespace tsd {
 
 constexpr int kMaxExperts = 16;
 constexpr int kMaxTopK = 4;
+constexpr size_t kPermuteLdsMax = 150 * 1024;  // expert ids of one pass staged in LDS
 
 // One wavefront per token.  x: fp32 residual rows [M][D]; Wr: fp32 [E][D] with the norm gain folded.
 __global__ __launch_bounds__(64) void router_kernel(const float* x, const float* Wr, int M, int D, int E, int topk,
@@ -80,15 +81,19 @@ __global__ __launch_bounds__(64) void router_kernel(const float* x, const float*
   }
 }
 
-// One block, one wavefront per expert.  Assignment a = token * topk + choice.
+// One block, one wavefront per expert.  Assignment a = token * topk + choice.  The expert ids are
+// first copied into LDS with every load in flight; the two scans (count, then place) run from LDS.
 __global__ __launch_bounds__(1024) void permute_kernel(const int* ids, int n_assign, int topk, int E, int BM, int n_mtiles,
                                                        int* src_row, int* slot_of, int4* tile_map) {
+  extern __shared__ int lds_ids[];  // [n_assign]
   __shared__ int cnt[kMaxExperts], beg[kMaxExperts + 1];
+  for (int a = threadIdx.x; a < n_assign; a += blockDim.x) lds_ids[a] = ids[a];
+  __syncthreads();
   const int e = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int c = 0;
   for (int a0 = 0; a0 < n_assign; a0 += 64) {
     const int a = a0 + lane;
-    c += __popcll(__ballot(a < n_assign && ids[a] == e));
+    c += __popcll(__ballot(a < n_assign && lds_ids[a] == e));
   }
   if (lane == 0) cnt[e] = c;
   __syncthreads();
@@ -106,7 +111,7 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int* ids, int n_ass
   int pos = beg[e];
   for (int a0 = 0; a0 < n_assign; a0 += 64) {
     const int a = a0 + lane;
-    const bool mine = a < n_assign && ids[a] == e;
+    const bool mine = a < n_assign && lds_ids[a] == e;
     const unsigned long long m = __ballot(mine);
     if (mine) {
       const int slot = pos + __popcll(m & ((1ull << lane) - 1ull));
@@ -141,6 +146,12 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* Y, const int*
   }
 }
 
+// More than 64 KB of dynamic LDS needs a one-time opt-in (done at handle creation).
+hipError_t prepare_moe() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&permute_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)kPermuteLdsMax);
+}
+
 hipError_t launch_router(const float* x, const float* Wr, int M, int D, int E, int topk, int* ids, float* gates,
                          hipStream_t st) {
   if (E > kMaxExperts || topk > kMaxTopK || topk > E || D % 4) return hipErrorInvalidValue;
@@ -150,8 +161,8 @@ hipError_t launch_router(const float* x, const float* Wr, int M, int D, int E, i
 
 hipError_t launch_permute(const int* ids, int n_assign, int topk, int E, int BM, int n_mtiles, int* src_row,
                           int* slot_of, void* tile_map, hipStream_t st) {
-  if (E > kMaxExperts) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(64 * E), 0, st, ids, n_assign, topk, E, BM, n_mtiles, src_row, slot_of,
+  if (E > kMaxExperts || (size_t)n_assign * 4 > kPermuteLdsMax) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(64 * E), (size_t)n_assign * 4, st, ids, n_assign, topk, E, BM, n_mtiles, src_row, slot_of,
                      reinterpret_cast<int4*>(tile_map));
   return hipGetLastError();
 }

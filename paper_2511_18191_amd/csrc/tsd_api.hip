@@ -139,6 +139,9 @@ int check_config(const tsd_config* c, std::string& why) {
   if ((c->max_tokens + c->page_tokens - 1) / c->page_tokens > 64)
     return bad("max_tokens / page_tokens must not exceed 64 pages per series");
   for (const tsd_model_cfg* m : {&c->target, &c->draft})
+    if (m->n_experts > 0 && (size_t)std::max((long)c->max_batch * (c->K + 1), (long)c->max_tokens) * m->top_k * 4 > 150 * 1024)
+      return bad("max_batch * (K + 1) * top_k too large for the expert sort (ids must fit 150 KB of LDS)");
+  for (const tsd_model_cfg* m : {&c->target, &c->draft})
     if (attention_lds_bytes(c->dtype, m->d_model / m->n_heads, c->max_tokens, c->page_tokens) > 160 * 1024)
       return bad("max_tokens too large: one head's K and V rows must fit the 160 KB of LDS");
   return TSD_OK;
@@ -460,12 +463,12 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     h.nq = ps.nq;
     h.N = P;
     h.K = D;
-    h.A = xin;
+    h.A = ctx->x;  // the head reads the fp32 residual
     h.W = md.W_h;
     h.out = ps.out;
     h.out_stride_b = ps.out_stride_b;
     h.t_skip = ps.t_skip;
-    HIP_TRY(ctx, timed_launch(ctx, TSD_K_HEAD, 2.0 * M * D * P, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_HEAD, h, st); }));
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_HEAD, 2.0 * M * D * P, st, [&] { return launch_gemm(c.dtype, A_NORM32, EP_HEAD, h, st); }));
   }
   return TSD_OK;
 }
@@ -614,6 +617,14 @@ int tsd_create(const tsd_config* cfg, void* arena_dev, size_t arena_bytes, tsd_c
     if (e == hipSuccess) e = hipMemcpy(md.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
       std::string msg = std::string("copying rotary tables: ") + hipGetErrorString(e);
+      delete ctx;
+      return fail(nullptr, TSD_E_HIP, msg);
+    }
+  }
+  if (cfg->target.n_experts > 0 || cfg->draft.n_experts > 0) {
+    hipError_t e = prepare_moe();
+    if (e != hipSuccess) {
+      std::string msg = std::string("raising the expert-sort kernel's LDS limit: ") + hipGetErrorString(e);
       delete ctx;
       return fail(nullptr, TSD_E_HIP, msg);
     }

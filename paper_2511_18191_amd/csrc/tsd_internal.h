@@ -24,7 +24,8 @@ constexpr double kRopeBase = 10000.0;
 enum AMode {
   A_TOK = 0,   // fp32 patches gathered from two per-series segments (patch embedding)
   A_NORM = 1,  // fp32 residual stream; RMSNorm applied as a per-row scale of the product
-  A_ACT = 2    // activations already in the compute dtype
+  A_ACT = 2,   // activations already in the compute dtype
+  A_NORM32 = 3 // like A_NORM but reads the fp32 residual itself (output head; split hi+lo in bf16 mode)
 };
 enum Epi {
   EP_STORE = 0,  // x = C                       (fp32)
@@ -146,6 +147,7 @@ struct AcceptP {
 };
 hipError_t launch_accept(const AcceptP& p, hipStream_t st);
 
+hipError_t prepare_moe();
 hipError_t launch_router(const float* x, const float* Wr, int M, int D, int E, int topk, int* ids, float* gates,
                          hipStream_t st);
 hipError_t launch_permute(const int* ids, int n_assign, int topk, int E, int BM, int n_mtiles, int* src_row,

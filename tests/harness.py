@@ -60,7 +60,7 @@ class Case:
         return ((ctx - m) / s).reshape(-1, self.cfg.patch), m, s
 
 
-def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=True, tol=None):
+def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=True, tol=None, subset=None):
     """Run GPU and oracle round by round on the same histories.  The GPU evaluates its own
     acceptance test (recorded) but commits the oracle's accepted length, so the two histories
     stay aligned and every round's tensors can be compared.  Returns a report dict."""
@@ -69,20 +69,21 @@ def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=Tru
     B, K, P, T = c.batch, c.K, c.patch, c.T
     sq = sigma_q or c.sigma
     sess.prefill(case.context, c.n_ctx, c.horizon)
-    hist = [case.oracle_hist(b)[0] for b in range(B)]
-    Y = [np.empty((0, P)) for _ in range(B)]
-    rnd = [0] * B
+    follow = list(range(B)) if subset is None else list(subset)
+    hist = {b: case.oracle_hist(b)[0] for b in follow}
+    Y = {b: np.empty((0, P)) for b in follow}
+    rnd = {b: 0 for b in follow}
     rep = dict(max_rel_X=0.0, max_rel_mu_p=0.0, near_ties=0, mismatched=0, tested=0, accepted=0, rounds=0,
                max_abs_ell=0.0, lengths=[], pass_rel_q=0.0, pass_rel_p=0.0)
     tol = tol or TOL[c.dtype]
-    Yg = [np.empty((0, P)) for _ in range(B)]     # what the GPU committed (its own tensors)
+    Yg = {b: np.empty((0, P)) for b in follow}    # what the GPU committed (its own tensors)
     rounds = 0
-    while any(y.shape[0] < T for y in Y) and (max_rounds is None or rounds < max_rounds):
+    while any(y.shape[0] < T for y in Y.values()) and (max_rounds is None or rounds < max_rounds):
         sess.draft_propose()
         sess.target_verify()
         forced = np.full(B, -1, np.int32)
         recs = {}
-        for b in range(B):
+        for b in follow:
             if Y[b].shape[0] >= T:
                 continue
             recs[b] = orc.spec_round(case.Wt, c.target, case.Wd, c.draft, np.vstack([hist[b], Y[b]]), K, c.sigma, sq,

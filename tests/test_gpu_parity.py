@@ -281,3 +281,35 @@ def test_edge_shapes(name, K, horizon, n_ctx):
     rep = lockstep(case, sess, tol=0.06 if (K == 16 and c.dtype == "bf16") else None)
     assert all(1 <= L <= K + 1 for L in rep["lengths"])
     assert sess.num_active() == 0 and sess.get_stats()["committed"] == c.batch * c.T
+
+
+@pytest.mark.parametrize("name,dtype,subset,rounds", [("cfg2", "bf16", [0, 101, 255], 3), ("cfg3", "bf16", [7, 1023], 2),
+                                                     ("cfg5", "fp32", [3, 500], 1), ("cfg5", "bf16", [3, 500], 1)])
+def test_full_size_sampled_series(name, dtype, subset, rounds):
+    # The benchmark configurations at their full sizes and in the launch configuration bench.py
+    # times (graph replay included via tsd_round in the free-running tail); the oracle follows a
+    # few sampled series (series are independent) for the first rounds.
+    # Routed FFN: the fp32 run pins the implementation at 1e-4.  In bf16 the discrete top-k choice
+    # flips for some tokens under operand rounding (about 2000 routing decisions feed one pass of
+    # one series, and with random-init weights an expert's output is as large as the residual
+    # stream), so there the comparison is reported, not asserted.
+    case = Case(name, dtype=dtype)
+    c = case.cfg
+    sess = case.session()
+    routed_bf16 = c.target.n_experts > 0 and dtype == "bf16"
+    rep = lockstep(case, sess, max_rounds=rounds, subset=subset, tol=float("inf"), check=not routed_bf16)
+    print(f"\n{name} {dtype} full size: per-pass q {rep['pass_rel_q']:.2e} p {rep['pass_rel_p']:.2e}; chained X {rep['max_rel_X']:.2e} "
+          f"mu_p {rep['max_rel_mu_p']:.2e}; lengths {rep['lengths']} mismatched {rep['mismatched']}")
+    if not routed_bf16:
+        assert rep["max_rel_X"] <= TOL[c.dtype] and rep["max_rel_mu_p"] <= TOL[c.dtype]
+    else:
+        assert rep["pass_rel_q"] <= 8e-3          # the dense draft is unaffected by routing
+    # properties that hold at any size: finish the decode free-running and check the books
+    while sess.num_active() > 0:
+        sess.round()
+    st = sess.get_stats()
+    state = sess.get_state()
+    assert st["committed"] == c.batch * c.T
+    assert int(state["committed"].min()) == c.T and int(state["len"].max()) == c.n_ctx - 1 + c.T
+    assert st["tested"] - st["accepted"] <= st["rounds"] and st["accepted"] <= st["tested"]
+    assert torch.isfinite(sess.get_forecast()).all()
