@@ -215,6 +215,11 @@ int tsd_set_sigma(tsd_ctx* ctx, float sigma_p, float sigma_q);
 int tsd_profile_begin(tsd_ctx* ctx, int kernel_class);
 int tsd_profile_end(tsd_ctx* ctx, int64_t* launches_host, double* ms_host, double* work_host, void* stream);
 
+/* Measurement tap: one plain product C[M,N] = A[M,K] * Wt[N,K]^T (fp32 result) through the same
+ * tiled kernel, tile selection and tile order the transformer passes use.  dtype TSD_BF16: A and
+ * Wt are bf16; TSD_F32: fp32.  K must be a multiple of 8, N of 4.  No handle needed. */
+int tsd_bench_gemm(int dtype, int M, int N, int K, const void* A_dev, const void* Wt_dev, float* C_dev, void* stream);
+
 const char* tsd_last_error(tsd_ctx* ctx);
 
 /* ABI version of this header (bumped on incompatible change). */

@@ -998,6 +998,28 @@ int tsd_profile_end(tsd_ctx* ctx, int64_t* launches_host, double* ms_host, doubl
   return TSD_OK;
 }
 
+int tsd_bench_gemm(int dtype, int M, int N, int K, const void* A_dev, const void* Wt_dev, float* C_dev, void* stream) {
+  if (dtype != TSD_F32 && dtype != TSD_BF16) return fail(nullptr, TSD_E_INVALID_ARG, "dtype must be TSD_F32 or TSD_BF16");
+  if (M < 1 || N < 4 || K < 8 || (K % 8) || (N % 4)) return fail(nullptr, TSD_E_INVALID_ARG, "need M >= 1, N a multiple of 4, K a multiple of 8");
+  if (!A_dev || !Wt_dev || !C_dev) return fail(nullptr, TSD_E_INVALID_ARG, "device pointers must not be NULL");
+  static bool prepared = false;
+  if (!prepared) {
+    HIP_TRY(nullptr, prepare_gemm(TSD_BF16));
+    prepared = true;
+  }
+  GemmP g;
+  std::memset(&g, 0, sizeof(g));
+  g.M = M;
+  g.N = N;
+  g.K = K;
+  g.nq = 1;
+  g.A = A_dev;
+  g.W = Wt_dev;
+  g.Cf = C_dev;
+  HIP_TRY(nullptr, launch_gemm(dtype, A_ACT, EP_STORE, g, (hipStream_t)stream));
+  return TSD_OK;
+}
+
 int tsd_set_accept_override(tsd_ctx* ctx, float alpha) {
   if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
   if (alpha > 1.f || alpha == 0.f || std::isnan(alpha)) return fail(ctx, TSD_E_INVALID_ARG, "alpha must be in (0, 1], or negative to disable");

@@ -313,3 +313,18 @@ def test_full_size_sampled_series(name, dtype, subset, rounds):
     assert int(state["committed"].min()) == c.T and int(state["len"].max()) == c.n_ctx - 1 + c.T
     assert st["tested"] - st["accepted"] <= st["rounds"] and st["accepted"] <= st["tested"]
     assert torch.isfinite(sess.get_forecast()).all()
+
+
+@pytest.mark.parametrize("M,N,K", [(40, 96, 16), (77, 200, 264), (1280, 1536, 512), (300, 512, 2048), (2304, 1024, 1024)])
+def test_gemm_tap_matches_fp64_product(M, N, K):
+    # the tiled GEMM alone (ragged M/N/K tails, both tile sizes, XCD tile order) against a float64 product
+    import paper_2511_18191_amd as tsd
+    g = torch.Generator().manual_seed(M * 7 + N)
+    A = torch.randn(M, K, generator=g)
+    W = torch.randn(N, K, generator=g)
+    for dt, tol in ((torch.float32, 2e-6), (torch.bfloat16, 2e-6)):
+        a, w = A.to(dt), W.to(dt)                       # bf16 inputs are exact for both sides
+        ref = a.double() @ w.double().T
+        out = tsd.bench_gemm(a.cuda(), w.cuda()).cpu().double()
+        err = (out - ref).abs().max() / ref.abs().max()
+        assert err < tol * (K ** 0.5), f"{dt}: {err:.3e}"
