@@ -49,11 +49,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   constexpr int AB_BYTES = 2 * (NAS * BM + BN) * LDT * (int)sizeof(T);
   constexpr int C_BYTES = 64 * LDC * 4;
   constexpr int SMEM = AB_BYTES > C_BYTES ? AB_BYTES : C_BYTES;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // SMEM + BM * 4 bytes
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // SMEM + BM * 12 bytes
   T* As = reinterpret_cast<T*>(smem);  // [2][NAS][BM][LDT]
   T* Bs = As + 2 * NAS * BM * LDT;     // [2][BN][LDT]
   float* Cs = reinterpret_cast<float*>(smem);  // [64][LDC], reuses the tile buffers
   float* row_scale = reinterpret_cast<float*>(smem + SMEM);  // [BM]
+  int* row_pos = reinterpret_cast<int*>(smem + SMEM + BM * 4);   // [BM] EP_QKV: absolute position of the row's token
+  int* row_page = row_pos + BM;                                   // [BM] EP_QKV: its physical KV page
 
   const int tid = threadIdx.x;
   const int M = p.M, N = p.N, K = p.K;
@@ -262,6 +264,28 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   const int nk = (K + BK - 1) / BK;
   load_global(0, ra0, rb0);
   load_global(min(1, nk - 1), ra1, rb1);
+  // Epilogue inputs that do not depend on the product are requested now, so their latency hides
+  // behind the main loop: the KV position/page of each row (QKV), the old residual values (RESID).
+  int my_pos = 0, my_page = 0;
+  if constexpr (EP == EP_QKV) {
+    if (tid < BM) {
+      const int gm = min(m0 + tid, m_lim - 1);
+      const int bl = gm / p.nq, t = gm - bl * p.nq, b = p.s0 + bl;
+      my_pos = (p.base_pos ? p.base_pos[b] : 0) + p.pos_off + t;
+      my_page = p.page_table[(long)b * p.pt_stride + (my_pos >> p.pt_shift)];
+    }
+  }
+  constexpr bool kPrefetchC = (EP == EP_RESID) && BM == 64;
+  constexpr int NPRE = kPrefetchC ? 64 * (BN / 4) / 256 : 1;
+  float4 oldc[NPRE];
+  if constexpr (kPrefetchC) {
+#pragma unroll
+    for (int it = 0; it < NPRE; ++it) {
+      const int g = tid + it * 256;
+      const int gm = min(m0 + g / (BN / 4), m_lim - 1), gn = min(n0 + (g % (BN / 4)) * 4, N - 4);
+      oldc[it] = *reinterpret_cast<const float4*>(p.Cf + (long)gm * N + gn);
+    }
+  }
   store_lds(0, 0, ra0, rb0);
   __syncthreads();
   int kt = 0;
@@ -287,6 +311,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
     compute(1);
   }
 
+  if constexpr (EP == EP_QKV) {
+    if (tid < BM) {
+      row_pos[tid] = my_pos;
+      row_page[tid] = my_page;
+    }
+  }
   // ---- RMSNorm row scale --------------------------------------------------------------------
   if constexpr (kNorm) {
 #pragma unroll
@@ -344,7 +374,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
         if (kBf && p.Cb) store4<T>(reinterpret_cast<T*>(p.Cb) + (long)gm * N + gn, v);
       } else if constexpr (EP == EP_RESID) {
         float4* dst = reinterpret_cast<float4*>(p.Cf + (long)gm * N + gn);
-        float4 o = *dst;
+        float4 o;
+        if constexpr (kPrefetchC) o = oldc[it]; else o = *dst;
         o.x += v.x;
         o.y += v.y;
         o.z += v.z;
@@ -364,9 +395,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
         const int D = p.D, hd = p.hd, half = hd >> 1;
         const int which = gn / D, c = gn - which * D;
         const int h = c / hd, d = c - h * hd;
-        const int bl = gm / p.nq, t = gm - bl * p.nq;
-        const int b = p.s0 + bl;
-        const int pos = (p.base_pos ? p.base_pos[b] : 0) + p.pos_off + t;
+        const int pos = row_pos[pass * 64 + row];
         if (which < 2) {
           const bool lo = d < half;
           const int pcol = lo ? col + half : col - half;
@@ -383,7 +412,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
         if (which == 0) {
           store4<T>(reinterpret_cast<T*>(p.q_out) + (long)gm * D + c, v);
         } else {
-          const int page = p.page_table[(long)b * p.pt_stride + (pos >> p.pt_shift)];
+          const int page = row_page[pass * 64 + row];
           const int tok = pos & (p.PT - 1);
           if (which == 2 && p.v_transposed) {
             // V block stored [head][dim][token]: four strided element stores
@@ -408,7 +437,7 @@ constexpr size_t gemm_smem_bytes() {
   constexpr int LDT = BK + (kBf ? 8 : 1);
   constexpr int nas = (kBf && (AM == A_TOK || AM == A_NORM32)) ? 2 : 1;
   constexpr size_t ab = 2 * (nas * BM + BN) * LDT * sizeof(T), c = 64 * (BN + 4) * 4;
-  return (ab > c ? ab : c) + BM * 4;
+  return (ab > c ? ab : c) + BM * 12;
 }
 
 template <typename T, int AM, int EP, int BM, int BN, int BK>
