@@ -62,6 +62,7 @@ extern "C" {
 #define TSD_FLAG_SCRAMBLE_PAGES 1u /* assign physical KV pages by a pseudo-random permutation */
 #define TSD_FLAG_NO_TEMPERING 2u   /* ablation: use d * ell (drop the 1/d scaling of Eq. 5)    */
 #define TSD_FLAG_NO_GRAPH 4u       /* launch kernels one by one instead of replaying HIP graphs */
+#define TSD_FLAG_NO_COMPACT 8u     /* always run passes over the whole batch (see tsd_num_active) */
 
 typedef struct tsd_ctx tsd_ctx; /* opaque */
 
@@ -163,7 +164,10 @@ int tsd_round(tsd_ctx* ctx, void* stream);
  * pending token, whose output is committed for every active series. */
 int tsd_target_step(tsd_ctx* ctx, void* stream);
 
-/* Number of series that still need patches.  Synchronises `stream`. */
+/* Number of series that still need patches.  Synchronises `stream`.  Also rebuilds the list of
+ * active series; until the next prefill/reset, passes then cover only the listed series (those
+ * that finish later stay listed and are masked, so the list stays valid without further calls).
+ * Results are identical with or without it; finished series simply stop costing work. */
 int tsd_num_active(tsd_ctx* ctx, int32_t* out_host, void* stream);
 
 /* De-normalised forecast, out_dev: [B, horizon_steps] (first H steps of the committed patches;
@@ -172,7 +176,7 @@ int tsd_get_forecast(tsd_ctx* ctx, float* out_dev, void* stream);
 
 /* Parity taps: copies of the last round's tensors.  Any pointer may be NULL.
  * X, mu_q: [B,K,P]; mu_p: [B,K+1,P]; n_acc: int32 [B] accepted count found by the test (-1 for
- * inactive series); ell, logu: [B,K] (NaN where a position was not tested). */
+ * series that were inactive when the round ran; rows of series no longer listed keep old values); ell, logu: [B,K] (NaN where a position was not tested). */
 int tsd_get_round_io(tsd_ctx* ctx, float* X_dev, float* mu_q_dev, float* mu_p_dev, int32_t* n_acc_dev,
                      float* ell_dev, float* logu_dev, void* stream);
 
@@ -215,10 +219,13 @@ int tsd_set_sigma(tsd_ctx* ctx, float sigma_p, float sigma_q);
 int tsd_profile_begin(tsd_ctx* ctx, int kernel_class);
 int tsd_profile_end(tsd_ctx* ctx, int64_t* launches_host, double* ms_host, double* work_host, void* stream);
 
-/* Measurement tap: one plain product C[M,N] = A[M,K] * Wt[N,K]^T (fp32 result) through the same
- * tiled kernel, tile selection and tile order the transformer passes use.  dtype TSD_BF16: A and
- * Wt are bf16; TSD_F32: fp32.  K must be a multiple of 8, N of 4.  No handle needed. */
-int tsd_bench_gemm(int dtype, int M, int N, int K, const void* A_dev, const void* Wt_dev, float* C_dev, void* stream);
+/* Measurement tap: one product through the same tiled kernel, tile selection and tile order the
+ * transformer passes use.  dtype TSD_BF16: A and Wt are bf16; TSD_F32: fp32.  variant 0:
+ * C[M,N] = A[M,K] * Wt[N,K]^T (fp32 result); variant 1: the same with each row of the product
+ * scaled by rsqrt(mean(A_row^2) + 1e-6) (the fused RMSNorm); variant 2: C += A * Wt^T (the
+ * residual epilogue).  K must be a multiple of 8, N of 4.  No handle needed. */
+int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_dev, const void* Wt_dev, float* C_dev,
+                   void* stream);
 
 const char* tsd_last_error(tsd_ctx* ctx);
 

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 TSD_F32, TSD_BF16 = 0, 1
 TSD_TARGET, TSD_DRAFT = 0, 1
-TSD_FLAG_SCRAMBLE_PAGES, TSD_FLAG_NO_TEMPERING, TSD_FLAG_NO_GRAPH = 1, 2, 4
+TSD_FLAG_SCRAMBLE_PAGES, TSD_FLAG_NO_TEMPERING, TSD_FLAG_NO_GRAPH, TSD_FLAG_NO_COMPACT = 1, 2, 4, 8
 KERNEL_CLASSES = ["embed", "qkv", "attn", "resid", "gelu", "head", "accept", "route"]   # TSD_K_* order
 
 
@@ -58,7 +58,7 @@ SYMBOLS = {
     "tsd_get_stats": ([C.c_void_p, C.POINTER(TsdStats), C.c_void_p], C.c_int),
     "tsd_profile_begin": ([C.c_void_p, C.c_int], C.c_int),
     "tsd_profile_end": ([C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p], C.c_int),
-    "tsd_bench_gemm": ([C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_bench_gemm": ([C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_set_accept_override": ([C.c_void_p, C.c_float], C.c_int),
     "tsd_set_sigma": ([C.c_void_p, C.c_float, C.c_float], C.c_int),
 }
@@ -105,16 +105,17 @@ def _check(rc, ctx=None):
         raise TsdError(rc, msg.decode() if msg else "")
 
 
-def bench_gemm(A, Wt, out=None):
+def bench_gemm(A, Wt, out=None, variant=0):
     """C = A @ Wt.T through libtsd's tiled GEMM on torch's current stream.  A: [M,K], Wt: [N,K]
-    (both bf16 or both fp32, on the GPU); returns fp32 [M,N]."""
+    (both bf16 or both fp32, on the GPU); returns fp32 [M,N].  variant 1 fuses the RMSNorm row
+    scale, variant 2 accumulates into `out`."""
     import torch
     M, K = A.shape
     N = Wt.shape[0]
     dt = TSD_BF16 if A.dtype == torch.bfloat16 else TSD_F32
     if out is None:
         out = torch.empty(M, N, dtype=torch.float32, device=A.device)
-    _check(lib().tsd_bench_gemm(dt, M, N, K, A.data_ptr(), Wt.data_ptr(), out.data_ptr(),
+    _check(lib().tsd_bench_gemm(dt, variant, M, N, K, A.data_ptr(), Wt.data_ptr(), out.data_ptr(),
                                 torch.cuda.current_stream(A.device).cuda_stream))
     return out
 

@@ -18,6 +18,9 @@ SOURCES = ["tsd_api.hip", "gemm.hip", "attn.hip", "misc.hip", "moe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
          # packed-fp32 instruction selection is switched off on purpose for the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # no implicit FMA contraction: a*b + c is fused only where the source says fmaf(), so the
+         # rounding of a row's arithmetic cannot depend on which unrolled copy of a loop body it met
+         "-ffp-contract=off",
          "-Wno-unused-command-line-argument"]
 
 

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
 
   const int lane = threadIdx.x;
   const int bl = blockIdx.x / p.Hh, h = blockIdx.x % p.Hh;
-  const int b = p.s0 + bl;
+  const int b = p.act ? p.act[bl] : p.s0 + bl;
   const int PT = p.PT, Hh = p.Hh, pts = p.pt_shift;
   const T* q = reinterpret_cast<const T*>(p.q);
   T* out = reinterpret_cast<T*>(p.out);
@@ -227,7 +227,7 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
 __global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnP p) {
   const int lane = threadIdx.x;
   const int bl = blockIdx.x / p.Hh, h = blockIdx.x % p.Hh;
-  const int b = p.s0 + bl;
+  const int b = p.act ? p.act[bl] : p.s0 + bl;
   const int PT = p.PT, Hh = p.Hh, pts = p.pt_shift;
   const bf16* q = reinterpret_cast<const bf16*>(p.q);
   bf16* out = reinterpret_cast<bf16*>(p.out);

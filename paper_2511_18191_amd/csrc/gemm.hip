@@ -105,6 +105,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
     {
       if constexpr (AM == A_TOK) {
         int b = gm / p.nq, t = gm % p.nq;
+        if (p.act) b = p.act[b];
         const float* src = (t < p.n0) ? p.src0 + (long)b * p.stride0 + (long)t * K
                                       : p.src1 + (long)b * p.stride1 + (long)(t - p.n0) * K;
         arow[i] = reinterpret_cast<const char*>(src);
@@ -270,7 +271,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   if constexpr (EP == EP_QKV) {
     if (tid < BM) {
       const int gm = min(m0 + tid, m_lim - 1);
-      const int bl = gm / p.nq, t = gm - bl * p.nq, b = p.s0 + bl;
+      const int bl = gm / p.nq, t = gm - bl * p.nq, b = p.act ? p.act[bl] : p.s0 + bl;
       my_pos = (p.base_pos ? p.base_pos[b] : 0) + p.pos_off + t;
       my_page = p.page_table[(long)b * p.pt_stride + (my_pos >> p.pt_shift)];
     }
@@ -389,7 +390,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
         v.w = gelu_tanh(v.w);
         store4<T>(reinterpret_cast<T*>(p.Ct) + (long)gm * N + gn, v);
       } else if constexpr (EP == EP_HEAD) {
-        const int b = gm / p.nq, t = gm % p.nq;
+        const int bl = gm / p.nq, t = gm % p.nq;
+        const int b = p.act ? p.act[bl] : bl;
         if (t >= p.t_skip) *reinterpret_cast<float4*>(p.out + (long)b * p.out_stride_b + (long)(t - p.t_skip) * N + gn) = v;
       } else {  // EP_QKV
         const int D = p.D, hd = p.hd, half = hd >> 1;

@@ -128,7 +128,7 @@ __device__ __forceinline__ unsigned philox_word0(unsigned c0, unsigned c1, unsig
 // tokens and the cache lengths (rollback is metadata only: speculative KV entries past the
 // accepted length are simply overwritten by the next round).
 __global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
-  const int b = blockIdx.x, lane = threadIdx.x;
+  const int b = p.act ? p.act[blockIdx.x] : (int)blockIdx.x, lane = threadIdx.x;
   const int K = p.K, P = p.P;
   const int KE = K > 0 ? K : 1;
   if (!p.active[b]) {
@@ -234,15 +234,34 @@ hipError_t launch_forecast_out(const float* forecast, const float* mean, const f
   return hipGetLastError();
 }
 
-__global__ void count_active_kernel(const int* active, int B, int* out) {
-  int c = 0;
-  for (int i = threadIdx.x; i < B; i += 64) c += active[i] ? 1 : 0;
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) c += __shfl_xor(c, o);
-  if (threadIdx.x == 0) *out = c;
+// One block: stable compaction of the active series (ascending series index) and their count.
+__global__ __launch_bounds__(1024) void compact_active_kernel(const int* active, int B, int* list, int* count) {
+  __shared__ int wave_cnt[16];
+  __shared__ int base_s;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  if (threadIdx.x == 0) base_s = 0;
+  __syncthreads();
+  for (int b0 = 0; b0 < B; b0 += 1024) {
+    const int b = b0 + threadIdx.x;
+    const bool on = b < B && active[b] != 0;
+    const unsigned long long m = __ballot(on);
+    if (lane == 0) wave_cnt[w] = __popcll(m);
+    __syncthreads();
+    int off = base_s;
+    for (int i = 0; i < w; ++i) off += wave_cnt[i];
+    if (on) list[off + __popcll(m & ((1ull << lane) - 1ull))] = b;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int t = 0;
+      for (int i = 0; i < 16; ++i) t += wave_cnt[i];
+      base_s += t;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *count = base_s;
 }
-hipError_t launch_count_active(const int* active, int B, int* out, hipStream_t st) {
-  hipLaunchKernelGGL(count_active_kernel, dim3(1), dim3(64), 0, st, active, B, out);
+hipError_t launch_compact_active(const int* active, int B, int* list, int* count, hipStream_t st) {
+  hipLaunchKernelGGL(compact_active_kernel, dim3(1), dim3(1024), 0, st, active, B, list, count);
   return hipGetLastError();
 }
 

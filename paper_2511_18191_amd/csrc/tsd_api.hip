@@ -60,6 +60,8 @@ struct tsd_ctx {
   float* moe_Y;
   char* moe_h;
   int* count_out;
+  int* act_list;   // series still decoding, ascending (device)
+  int n_act;       // host copy of its length; -1 = unknown (use the full batch)
   long long* stats_out;
   // forecast in flight
   bool prefilled;
@@ -135,7 +137,7 @@ int check_config(const tsd_config* c, std::string& why) {
   if (!(c->sigma_p > 0.f) || !(c->sigma_q > 0.f) || !std::isfinite(c->sigma_p) || !std::isfinite(c->sigma_q))
     return bad("sigma_p and sigma_q must be positive and finite");
   if (c->fallback_r != 0.f) return bad("fallback_r must be 0 (target-mean fallback)");
-  if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING | TSD_FLAG_NO_GRAPH)) return bad("unknown flag bits");
+  if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING | TSD_FLAG_NO_GRAPH | TSD_FLAG_NO_COMPACT)) return bad("unknown flag bits");
   if ((c->max_tokens + c->page_tokens - 1) / c->page_tokens > 64)
     return bad("max_tokens / page_tokens must not exceed 64 pages per series");
   for (const tsd_model_cfg* m : {&c->target, &c->draft})
@@ -212,7 +214,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
   const size_t rows = std::max((size_t)B * (K + 1), (size_t)c.max_tokens);
   size_t o_xb = cv.take(rows * Dm * es);
   size_t o_x = cv.take(rows * Dm * 4), o_q = cv.take(rows * Dm * es), o_a = cv.take(rows * Dm * es), o_h = cv.take(rows * Fm * es);
-  size_t o_cnt = cv.take(256), o_so = cv.take(256);
+  size_t o_cnt = cv.take(256), o_so = cv.take(256), o_alist = cv.take((size_t)B * 4);
   // routed FFN scratch: one slot per (token, chosen expert)
   const size_t topk = std::max(c.target.n_experts > 0 ? c.target.top_k : 0, c.draft.n_experts > 0 ? c.draft.top_k : 0);
   const size_t slots = rows * topk, nEmax = std::max(c.target.n_experts, c.draft.n_experts);
@@ -255,6 +257,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
     ctx->hbuf = at(o_h);
     ctx->rows_max = (int)rows;
     ctx->count_out = (int*)at(o_cnt);
+    ctx->act_list = (int*)at(o_alist);
     ctx->moe_ids = topk ? (int*)at(o_ids) : nullptr;
     ctx->moe_gates = (float*)at(o_gates);
     ctx->moe_src = (int*)at(o_src);
@@ -297,6 +300,7 @@ hipError_t timed_launch(tsd_ctx* ctx, int cls, double work, hipStream_t st, F fn
 struct Pass {
   int which;
   int B, s0, nq;
+  const int* act;  // compacted pass over B listed series (NULL: series s0 .. s0+B-1)
   const int* base_pos;
   int pos_off;
   const float *src0, *src1;
@@ -325,6 +329,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
   g.stride0 = ps.stride0;
   g.stride1 = ps.stride1;
   g.n0 = ps.n0;
+  g.act = ps.act;
   g.W = md.W_e;
   g.Cf = ctx->x;
   g.Cb = ctx->xb;
@@ -347,6 +352,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     q.base_pos = ps.base_pos;
     q.pos_off = ps.pos_off;
     q.s0 = ps.s0;
+    q.act = ps.act;
     q.rope_cos = md.rope_cos;
     q.rope_sin = md.rope_sin;
     q.D = D;
@@ -366,6 +372,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     a.base_pos = ps.base_pos;
     a.pos_off = ps.pos_off;
     a.s0 = ps.s0;
+    a.act = ps.act;
     a.nq = ps.nq;
     a.B = ps.B;
     a.Hh = md.c.n_heads;
@@ -468,9 +475,21 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     h.out = ps.out;
     h.out_stride_b = ps.out_stride_b;
     h.t_skip = ps.t_skip;
+    h.act = ps.act;
     HIP_TRY(ctx, timed_launch(ctx, TSD_K_HEAD, 2.0 * M * D * P, st, [&] { return launch_gemm(c.dtype, A_NORM32, EP_HEAD, h, st); }));
   }
   return TSD_OK;
+}
+
+// Series a pass has to cover: the compacted active list when tsd_num_active has built one since
+// the last prefill/reset (it stays a superset of the active set as series finish), else everyone.
+struct Cover {
+  const int* act;
+  int n;
+};
+Cover cover(const tsd_ctx* ctx) {
+  if (ctx->n_act >= 0 && ctx->n_act < ctx->B) return Cover{ctx->act_list, ctx->n_act};
+  return Cover{nullptr, ctx->B};
 }
 
 void drop_graphs(tsd_ctx* ctx) {
@@ -486,7 +505,7 @@ void drop_graphs(tsd_ctx* ctx) {
 // itself capturing `st`, or when graphs are switched off.
 template <typename F>
 int run_graphed(tsd_ctx* ctx, hipGraphExec_t* slot, hipStream_t st, F body) {
-  if ((ctx->cfg.flags & TSD_FLAG_NO_GRAPH) || st == nullptr || ctx->prof_class >= 0) return body();
+  if ((ctx->cfg.flags & TSD_FLAG_NO_GRAPH) || st == nullptr || ctx->prof_class >= 0 || cover(ctx).act) return body();
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
   HIP_TRY(ctx, hipStreamIsCapturing(st, &cs));
   if (cs != hipStreamCaptureStatusNone) return body();
@@ -539,7 +558,10 @@ int accept_commit_impl(tsd_ctx* ctx, const int32_t* forced, int K, hipStream_t s
   a.ell = ctx->ell;
   a.logu = ctx->logu;
   a.stat = ctx->stat;
-  a.B = ctx->B;
+  const Cover cv = cover(ctx);
+  if (cv.n == 0) return TSD_OK;
+  a.B = cv.n;
+  a.act = cv.act;
   a.K = K;
   a.P = c.patch;
   a.T = ctx->T;
@@ -600,6 +622,7 @@ int tsd_create(const tsd_config* cfg, void* arena_dev, size_t arena_bytes, tsd_c
   ctx->prefilled = false;
   ctx->injected = false;
   ctx->alpha_override = -1.f;
+  ctx->n_act = -1;
   ctx->B = ctx->N = ctx->T = ctx->H = 0;
   carve(*cfg, ctx);
   // rotary tables: angle(pos, i) = pos * base^(-2 i / hd), computed in double
@@ -726,6 +749,7 @@ int tsd_prefill(tsd_ctx* ctx, const float* series_dev, int32_t B, int32_t n_ctx_
   if ((long)N + T + c.K > c.max_tokens) return fail(ctx, TSD_E_OUT_OF_RANGE, "n_ctx_patches + ceil(horizon/P) + K exceeds max_tokens");
   hipStream_t st = (hipStream_t)stream;
   ctx->prefilled = false;
+  ctx->n_act = -1;
   drop_graphs(ctx);  // batch size, context length and horizon are baked into the captured launches
   // page table: every series reserves the pages its whole forecast can touch
   const int need = (N + T + c.K + c.page_tokens - 1) / c.page_tokens;
@@ -780,6 +804,7 @@ int tsd_reset_decode(tsd_ctx* ctx, void* stream) {
   PrefillP pp{nullptr, ctx->znorm, ctx->mean, ctx->sdev, ctx->pending, ctx->prev, ctx->len, ctx->committed,
               ctx->round, ctx->active, ctx->stat, ctx->B, ctx->N, ctx->cfg.patch};
   HIP_TRY(ctx, launch_reset(pp, (hipStream_t)stream));
+  ctx->n_act = -1;  // every series is active again
   return TSD_OK;
 }
 
@@ -793,10 +818,13 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
   // Step 1 ingests two tokens per series: the token just before the pending one and the pending
   // one.  After a fully accepted round the draft cache lacks the former (it proposed x_K but
   // never consumed it); for the other series the rewrite stores identical values.
+  const Cover cv = cover(ctx);
+  if (cv.n == 0) return TSD_OK;
   Pass ps;
   std::memset(&ps, 0, sizeof(ps));
   ps.which = TSD_DRAFT;
-  ps.B = ctx->B;
+  ps.B = cv.n;
+  ps.act = cv.act;
   ps.nq = 2;
   ps.base_pos = ctx->len;
   ps.pos_off = -1;
@@ -812,7 +840,8 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
   for (int i = 2; i <= K; ++i) {  // step i consumes x_{i-1} at position len + i - 1, emits x_i
     std::memset(&ps, 0, sizeof(ps));
     ps.which = TSD_DRAFT;
-    ps.B = ctx->B;
+    ps.B = cv.n;
+    ps.act = cv.act;
     ps.nq = 1;
     ps.base_pos = ctx->len;
     ps.pos_off = i - 1;
@@ -832,10 +861,13 @@ int tsd_target_verify(tsd_ctx* ctx, void* stream) {
   if (rc) return rc;
   const tsd_config& c = ctx->cfg;
   const int P = c.patch, K = c.K;
+  const Cover cv = cover(ctx);
+  if (cv.n == 0) return TSD_OK;
   Pass ps;
   std::memset(&ps, 0, sizeof(ps));
   ps.which = TSD_TARGET;
-  ps.B = ctx->B;
+  ps.B = cv.n;
+  ps.act = cv.act;
   ps.nq = K + 1;
   ps.base_pos = ctx->len;
   ps.pos_off = 0;
@@ -874,8 +906,11 @@ int tsd_target_step(tsd_ctx* ctx, void* stream) {
   return run_graphed(ctx, &ctx->graph_step, (hipStream_t)stream, [&]() {
     Pass ps;
     std::memset(&ps, 0, sizeof(ps));
+    const Cover cv = cover(ctx);
+    if (cv.n == 0) return TSD_OK;
     ps.which = TSD_TARGET;
-    ps.B = ctx->B;
+    ps.B = cv.n;
+    ps.act = cv.act;
     ps.nq = 1;
     ps.base_pos = ctx->len;
     ps.pos_off = 0;
@@ -896,9 +931,10 @@ int tsd_num_active(tsd_ctx* ctx, int32_t* out_host, void* stream) {
   if (rc) return rc;
   if (!out_host) return fail(ctx, TSD_E_INVALID_ARG, "out_host is NULL");
   hipStream_t st = (hipStream_t)stream;
-  HIP_TRY(ctx, launch_count_active(ctx->active, ctx->B, ctx->count_out, st));
+  HIP_TRY(ctx, launch_compact_active(ctx->active, ctx->B, ctx->act_list, ctx->count_out, st));
   HIP_TRY(ctx, hipMemcpyAsync(out_host, ctx->count_out, 4, hipMemcpyDeviceToHost, st));
   HIP_TRY(ctx, hipStreamSynchronize(st));
+  if (!(ctx->cfg.flags & TSD_FLAG_NO_COMPACT)) ctx->n_act = *out_host;  // later passes cover only these series
   return TSD_OK;
 }
 
@@ -998,7 +1034,9 @@ int tsd_profile_end(tsd_ctx* ctx, int64_t* launches_host, double* ms_host, doubl
   return TSD_OK;
 }
 
-int tsd_bench_gemm(int dtype, int M, int N, int K, const void* A_dev, const void* Wt_dev, float* C_dev, void* stream) {
+int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_dev, const void* Wt_dev, float* C_dev,
+                   void* stream) {
+  if (variant < 0 || variant > 2) return fail(nullptr, TSD_E_INVALID_ARG, "variant must be 0, 1 or 2");
   if (dtype != TSD_F32 && dtype != TSD_BF16) return fail(nullptr, TSD_E_INVALID_ARG, "dtype must be TSD_F32 or TSD_BF16");
   if (M < 1 || N < 4 || K < 8 || (K % 8) || (N % 4)) return fail(nullptr, TSD_E_INVALID_ARG, "need M >= 1, N a multiple of 4, K a multiple of 8");
   if (!A_dev || !Wt_dev || !C_dev) return fail(nullptr, TSD_E_INVALID_ARG, "device pointers must not be NULL");
@@ -1016,7 +1054,7 @@ int tsd_bench_gemm(int dtype, int M, int N, int K, const void* A_dev, const void
   g.A = A_dev;
   g.W = Wt_dev;
   g.Cf = C_dev;
-  HIP_TRY(nullptr, launch_gemm(dtype, A_ACT, EP_STORE, g, (hipStream_t)stream));
+  HIP_TRY(nullptr, launch_gemm(dtype, variant == 1 ? A_NORM : A_ACT, variant == 2 ? EP_RESID : EP_STORE, g, (hipStream_t)stream));
   return TSD_OK;
 }
 

@@ -57,6 +57,7 @@ struct GemmP {
   const int* base_pos;  // per-series position of token 0 minus pos_off (NULL = 0)
   int pos_off;
   int s0;  // first series of this pass (chunked prefill)
+  const int* act;  // compacted pass: row block i belongs to series act[i] (NULL: series s0 + i)
   const float* rope_cos;
   const float* rope_sin;  // [max_tokens][hd/2]
   int D, Hh, hd, PT;
@@ -83,6 +84,7 @@ struct AttnP {
   const int* base_pos;
   int pos_off;
   int s0;
+  const int* act;  // compacted pass: block i handles series act[i] (NULL: series s0 + i)
   int nq, B, Hh, hd, D, PT;
   int pt_shift;  // log2(PT)
   int v_transposed;  // V block of a page is [head][dim][token] (bf16 head_dim-64 MFMA attention)
@@ -129,6 +131,7 @@ struct AcceptP {
   const float* mu_q;  // [B][K][P]
   const float* mu_p;  // [B][K+1][P]
   const int* forced;  // nullable
+  const int* act;     // compacted round: block i handles series act[i] (NULL: series i)
   float* pending;
   float* prev;
   float* forecast;    // [B][T*P] normalised
@@ -157,7 +160,8 @@ hipError_t launch_combine(int dtype, const float* Y, const int* slot_of, const f
 
 hipError_t launch_forecast_out(const float* forecast, const float* mean, const float* sdev, const int* committed,
                                float* out, int B, int P, int T, int H, hipStream_t st);
-hipError_t launch_count_active(const int* active, int B, int* out, hipStream_t st);
+// stable list of the series with active != 0 and their count
+hipError_t launch_compact_active(const int* active, int B, int* list, int* count, hipStream_t st);
 hipError_t launch_sum_stats(const long long* stat, int B, long long* out5, hipStream_t st);
 hipError_t launch_fill_nan(float* p, long n, hipStream_t st);
 

@@ -328,3 +328,50 @@ def test_gemm_tap_matches_fp64_product(M, N, K):
         out = tsd.bench_gemm(a.cuda(), w.cuda()).cpu().double()
         err = (out - ref).abs().max() / ref.abs().max()
         assert err < tol * (K ** 0.5), f"{dt}: {err:.3e}"
+
+
+@pytest.mark.parametrize("name", ["mini3", "mini5"])
+def test_active_list_compaction_changes_nothing(name):
+    # after tsd_num_active the passes cover only the listed series; finished series stop costing
+    # work but every bit of the result stays the same
+    import paper_2511_18191_amd as tsd
+    case = Case(name, B=23)
+    c = case.cfg
+    outs = []
+    for flags, poll in ((tsd.TSD_FLAG_NO_COMPACT, True), (0, True), (0, False)):
+        sess = case.session(flags=flags)
+        sess.prefill(case.context, c.n_ctx, c.horizon)
+        rounds, counts = 0, []
+        while True:
+            sess.round()
+            rounds += 1
+            if poll:
+                counts.append(sess.num_active())
+                if counts[-1] == 0:
+                    break
+            elif rounds == c.T:          # every round commits at least one patch
+                break
+        assert sess.num_active() == 0
+        outs.append((sess.get_forecast().cpu(), sess.get_stats(), counts))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][0], outs[2][0])
+    assert outs[0][1] == outs[1][1]
+    assert outs[0][2] == outs[1][2] and sorted(outs[1][2], reverse=True) == outs[1][2] and outs[1][2][0] < c.batch
+
+
+def test_batch_position_invariance():
+    # a series' proposals and target means do not depend, to the bit, on where it sits in the
+    # batch (which tile row, which prefill chunk, which physical pages)
+    case = Case("mini3", B=23)
+    c = case.cfg
+    ref = None
+    for perm in (np.arange(23), np.arange(23)[::-1].copy(), np.random.default_rng(3).permutation(23)):
+        sess = case.session()
+        sess.prefill(np.ascontiguousarray(case.context[perm]), c.n_ctx, c.horizon)
+        sess.draft_propose()
+        sess.target_verify()
+        io = sess.get_round_io()
+        X, mu_p = io["X"].cpu(), io["mu_p"].cpu()
+        if ref is None:
+            ref = (X, mu_p)
+        else:
+            assert torch.equal(X, ref[0][perm]) and torch.equal(mu_p, ref[1][perm])
