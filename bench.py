@@ -27,6 +27,8 @@ def parse():
     ap.add_argument("--sigma", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-series", type=int, default=4, help="series in the oracle's bounded sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB copy kernel 5 times (known traffic, to scale profiler memory counters)")
     return ap.parse_args()
 
 
@@ -75,11 +77,15 @@ def phase_times(torch, sess, reps=20):
     return out
 
 
+# HBM bytes per launch of each kernel family from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by the
+# copy-kernel calibration (profiles/traffic_cfg2_bench.md has the commands, raw values and factors)
+TRAFFIC = {"cfg2": {"resid": 7927537, "qkv": 8140259, "gelu": 6174597, "attn": 11248708, "head": 1098586,
+                    "embed": 1238448, "accept": 813759}}
 PEAK = {"bf16": 2500.0, "fp32": 157.3}   # dense MFMA bf16 / vector fp32, TFLOP/s
 HBM_PEAK = 8000.0                        # GB/s
 
 
-def kernel_rooflines(sess, dtype, steps):
+def kernel_rooflines(sess, dtype, steps, workload):
     """Per kernel family: HIP-event time of every launch during `steps` speculative decodes
     (kernel-by-kernel launches on the session's stream), and the algorithmic work they did."""
     from paper_2511_18191_amd.binding import KERNEL_CLASSES
@@ -95,7 +101,8 @@ def kernel_rooflines(sess, dtype, steps):
         achieved = work / (ms * 1e-3) / (1e9 if hbm else 1e12)
         peak = HBM_PEAK if hbm else PEAK[dtype]
         out[name] = dict(bound="hbm" if hbm else "mfma", achieved=achieved, peak=peak, unit="GB/s" if hbm else "TFLOP/s",
-                         frac=achieved / peak, launches=n, avg_us=ms * 1e3 / n, total_ms=ms, traffic=None)
+                         frac=achieved / peak, launches=n, avg_us=ms * 1e3 / n, total_ms=ms,
+                         traffic=TRAFFIC.get(workload, {}).get(name))
     return out
 
 
@@ -129,6 +136,16 @@ def main():
     from harness import Case
     from oracle import tsd_oracle as orc  # CPU-baseline leg and the throughput-law arithmetic only
 
+    if a.copy_calibration:
+        import paper_2511_18191_amd as tsd
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")      # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            tsd.bench_copy(dst, src)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:1024], src[:1024])
+        del src, dst
+
     case = Case(a.config, sigma=a.sigma)
     c = case.cfg
     sess = case.session()
@@ -148,7 +165,7 @@ def main():
     t_base = timed(torch, lambda: decode_target_only(sess, c.T), a.steps)
     ph = phase_times(torch, sess)
 
-    fam = kernel_rooflines(sess, c.dtype, max(2, a.steps // 4))
+    fam = kernel_rooflines(sess, c.dtype, max(2, a.steps // 4), c.name if a.sigma is None else None)
     dominant = max(fam, key=lambda k: fam[k]["total_ms"])
 
     alpha = st["accepted"] / max(1, st["tested"])

@@ -227,6 +227,10 @@ int tsd_profile_end(tsd_ctx* ctx, int64_t* launches_host, double* ms_host, doubl
 int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_dev, const void* Wt_dev, float* C_dev,
                    void* stream);
 
+/* Measurement tap: a plain copy kernel (dst[i] = src[i], 16 bytes per lane) of `bytes` bytes
+ * (a multiple of 16).  Its known traffic calibrates the profiler's memory counters. */
+int tsd_bench_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
+
 const char* tsd_last_error(tsd_ctx* ctx);
 
 /* ABI version of this header (bumped on incompatible change). */

@@ -59,6 +59,7 @@ SYMBOLS = {
     "tsd_profile_begin": ([C.c_void_p, C.c_int], C.c_int),
     "tsd_profile_end": ([C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p], C.c_int),
     "tsd_bench_gemm": ([C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_bench_copy": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
     "tsd_set_accept_override": ([C.c_void_p, C.c_float], C.c_int),
     "tsd_set_sigma": ([C.c_void_p, C.c_float, C.c_float], C.c_int),
 }
@@ -118,6 +119,14 @@ def bench_gemm(A, Wt, out=None, variant=0):
     _check(lib().tsd_bench_gemm(dt, variant, M, N, K, A.data_ptr(), Wt.data_ptr(), out.data_ptr(),
                                 torch.cuda.current_stream(A.device).cuda_stream))
     return out
+
+
+def bench_copy(dst, src):
+    """dst <- src with libtsd's plain copy kernel on torch's current stream (same-size GPU tensors)."""
+    import torch
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n
+    _check(lib().tsd_bench_copy(dst.data_ptr(), src.data_ptr(), n, torch.cuda.current_stream(src.device).cuda_stream))
 
 
 class Session:

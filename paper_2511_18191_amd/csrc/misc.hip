@@ -1,5 +1,6 @@
 // Small kernels around the transformer pass: weight packing, prefill statistics, the fused
 // acceptance / correction / commit / rollback kernel, and read-out helpers.
+#include <algorithm>
 #include <type_traits>
 
 #include "tsd_internal.h"
@@ -277,6 +278,16 @@ __global__ void sum_stats_kernel(const long long* stat, int B, long long* out5) 
 }
 hipError_t launch_sum_stats(const long long* stat, int B, long long* out5, hipStream_t st) {
   hipLaunchKernelGGL(sum_stats_kernel, dim3(1), dim3(64), 0, st, stat, B, out5);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(uint4* dst, const uint4* src, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {
+  const size_t n16 = bytes / 16;
+  const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 32);
+  hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, st, (uint4*)dst, (const uint4*)src, n16);
   return hipGetLastError();
 }
 

@@ -1058,6 +1058,14 @@ int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_de
   return TSD_OK;
 }
 
+int tsd_bench_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream) {
+  if (!dst_dev || !src_dev) return fail(nullptr, TSD_E_INVALID_ARG, "device pointers must not be NULL");
+  if (bytes == 0 || (bytes % 16) || ((uintptr_t)dst_dev % 16) || ((uintptr_t)src_dev % 16))
+    return fail(nullptr, TSD_E_INVALID_ARG, "bytes and both pointers must be non-zero multiples of 16");
+  HIP_TRY(nullptr, launch_copy(dst_dev, src_dev, bytes, (hipStream_t)stream));
+  return TSD_OK;
+}
+
 int tsd_set_accept_override(tsd_ctx* ctx, float alpha) {
   if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
   if (alpha > 1.f || alpha == 0.f || std::isnan(alpha)) return fail(ctx, TSD_E_INVALID_ARG, "alpha must be in (0, 1], or negative to disable");
