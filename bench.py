@@ -108,12 +108,13 @@ def kernel_rooflines(sess, dtype, steps, workload):
 
 def cpu_baseline(case, n_series):
     """The oracle, as it stands, on a bounded sample: n_series series, whole horizon,
-    single-pass mode, one process (numpy's BLAS threads)."""
+    single-pass mode, one process (numpy's BLAS threads).  The only place the oracle is used."""
     from oracle import tsd_oracle as orc
     c = case.cfg
+    Wt, Wd = orc.as_f64(case.wt), orc.as_f64(case.wd)
     t0 = time.perf_counter()
     for b in range(n_series):
-        orc.forecast_spec(case.Wt, c.target, case.Wd, c.draft, case.context[b], c.patch, c.horizon, c.K, c.sigma,
+        orc.forecast_spec(Wt, c.target, Wd, c.draft, case.context[b], c.patch, c.horizon, c.K, c.sigma,
                           c.sigma, case.seed, b)
     dt = time.perf_counter() - t0
     try:
@@ -132,12 +133,10 @@ def main():
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from harness import Case
-    from oracle import tsd_oracle as orc  # CPU-baseline leg and the throughput-law arithmetic only
+    import paper_2511_18191_amd as tsd
+    import synth
 
     if a.copy_calibration:
-        import paper_2511_18191_amd as tsd
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")      # 256 MiB
         dst = torch.empty_like(src)
         for _ in range(5):
@@ -146,9 +145,9 @@ def main():
         assert torch.equal(dst[:1024], src[:1024])
         del src, dst
 
-    case = Case(a.config, sigma=a.sigma)
+    case = synth.Inputs(a.config, sigma=a.sigma)
     c = case.cfg
-    sess = case.session()
+    sess = tsd.session_for(case)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     sess.prefill(case.context, c.n_ctx, c.horizon)
@@ -190,7 +189,7 @@ def main():
         "rounds_per_decode": rounds,
         "acceptance": alpha, "mean_committed_per_round": mean_L,
         "phase_ms": ph, "c": cc, "v": v,
-        "predicted_speedup_eq8": orc.predicted_speedup(alpha, c.K, cc, v),
+        "predicted_speedup_eq8": tsd.law.speedup(alpha, c.K, cc, v),
         "near_ties": st["near_ties"],
         # committed patches per unit time against one patch per target step (what Eq. 8 predicts)
         "patch_rate_speedup": mean_L * ph["target_step"] / (ph["draft"] + ph["verify"] + ph["accept"]),

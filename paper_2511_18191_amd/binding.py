@@ -272,3 +272,16 @@ class Session:
 
     def set_sigma(self, sigma_p, sigma_q=None):
         _check(lib().tsd_set_sigma(self.h, sigma_p, sigma_p if sigma_q is None else sigma_q), self.h)
+
+
+def session_for(inputs, flags=0, page_tokens=16, max_batch=None, sigma_q=None):
+    """A Session sized for `inputs` (an object with cfg, wt, wd, seed as synth.Inputs has) with both
+    models' weights loaded."""
+    import synth
+    c = inputs.cfg
+    tc = make_config(c.target, c.draft, c.patch, c.K, max_batch or c.batch, c.max_tokens, c.dtype, c.sigma, sigma_q,
+                     seed=inputs.seed, page_tokens=page_tokens, flags=flags)
+    s = Session(tc)
+    s.load_weights(TSD_TARGET, synth.flatten_weights(c.target, c.patch, inputs.wt))
+    s.load_weights(TSD_DRAFT, synth.flatten_weights(c.draft, c.patch, inputs.wd))
+    return s

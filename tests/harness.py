@@ -20,39 +20,17 @@ TOL = {"fp32": 1e-4, "bf16": 2e-2}
 PASS_TOL = {"fp32": 2e-5, "bf16": 8e-3}
 
 
-class Case:
-    """Seeded inputs of one configuration, for both implementations."""
+class Case(synth.Inputs):
+    """Seeded inputs of one configuration, for both implementations (adds the oracle's float64
+    view of the weights)."""
 
-    def __init__(self, name, B=None, sigma=None, K=None, horizon=None, random_gains=False, draft_is_target=False,
-                 seed=2021, **over):
-        cfg = synth.get_config(name, **over)
-        if K is not None or horizon is not None or sigma is not None or B is not None:
-            import dataclasses
-            cfg = dataclasses.replace(cfg, K=K or cfg.K, horizon=horizon or cfg.horizon,
-                                      sigma=sigma or cfg.sigma, batch=B or cfg.batch)
-        if draft_is_target:
-            import dataclasses
-            cfg = dataclasses.replace(cfg, draft=cfg.target)
-        self.cfg = cfg
-        self.seed = seed
-        rng = np.random.default_rng(cfg.weight_seed)
-        self.wt = synth.make_weights(cfg.target, cfg.patch, rng, cfg.dtype, random_gains=random_gains)
-        self.wd = self.wt if draft_is_target else synth.make_weights(cfg.draft, cfg.patch, rng, cfg.dtype,
-                                                                     random_gains=random_gains)
+    def __init__(self, *a, **k):
+        super().__init__(*a, **k)
         self.Wt, self.Wd = orc.as_f64(self.wt), orc.as_f64(self.wd)
-        self.series = synth.make_series(cfg.series_kind, cfg.batch, cfg.context + cfg.horizon, cfg.series_seed,
-                                        cfg.context)
-        self.context = np.ascontiguousarray(self.series[:, : cfg.context])
 
-    def session(self, flags=0, page_tokens=16, max_batch=None, sigma_q=None):
+    def session(self, **kw):
         import paper_2511_18191_amd as tsd
-        c = self.cfg
-        tc = tsd.make_config(c.target, c.draft, c.patch, c.K, max_batch or c.batch, c.max_tokens, c.dtype, c.sigma,
-                             sigma_q, seed=self.seed, page_tokens=page_tokens, flags=flags)
-        s = tsd.Session(tc)
-        s.load_weights(tsd.TSD_TARGET, synth.flatten_weights(c.target, c.patch, self.wt))
-        s.load_weights(tsd.TSD_DRAFT, synth.flatten_weights(c.draft, c.patch, self.wd))
-        return s
+        return tsd.session_for(self, **kw)
 
     def oracle_hist(self, b):
         ctx = self.context[b].astype(np.float64)
