@@ -63,6 +63,7 @@ extern "C" {
 #define TSD_FLAG_NO_TEMPERING 2u   /* ablation: use d * ell (drop the 1/d scaling of Eq. 5)    */
 #define TSD_FLAG_NO_GRAPH 4u       /* launch kernels one by one instead of replaying HIP graphs */
 #define TSD_FLAG_NO_COMPACT 8u     /* always run passes over the whole batch (see tsd_num_active) */
+#define TSD_FLAG_NO_SKINNY 16u     /* never use the <= 32-row weight-streaming GEMM                */
 
 typedef struct tsd_ctx tsd_ctx; /* opaque */
 

@@ -506,6 +506,7 @@ static hipError_t launch_t(int amode, int epi, const GemmP& p, hipStream_t st) {
 
 hipError_t launch_gemm(int dtype, int amode, int epi, const GemmP& p, hipStream_t st) {
   if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
+  if (p.allow_skinny && skinny_applicable(dtype, amode, epi, p)) return launch_gemm_skinny(amode, epi, p, st);
   return dtype == TSD_BF16 ? launch_t<bf16>(amode, epi, p, st) : launch_t<float>(amode, epi, p, st);
 }
 

@@ -53,6 +53,8 @@ struct tsd_ctx {
   char* xb;   // its bf16 shadow (GEMM A operand in bf16 mode)
   char *qbuf, *abuf, *hbuf;
   int rows_max;
+  int skinny;  // all decode passes have at most 32 rows: they take the skinny GEMM (fixed per handle so that a
+               // series' bits never depend on how many other series are still active)
   int* moe_ids;
   float* moe_gates;
   int *moe_src, *moe_slot;
@@ -137,7 +139,7 @@ int check_config(const tsd_config* c, std::string& why) {
   if (!(c->sigma_p > 0.f) || !(c->sigma_q > 0.f) || !std::isfinite(c->sigma_p) || !std::isfinite(c->sigma_q))
     return bad("sigma_p and sigma_q must be positive and finite");
   if (c->fallback_r != 0.f) return bad("fallback_r must be 0 (target-mean fallback)");
-  if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING | TSD_FLAG_NO_GRAPH | TSD_FLAG_NO_COMPACT)) return bad("unknown flag bits");
+  if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING | TSD_FLAG_NO_GRAPH | TSD_FLAG_NO_COMPACT | TSD_FLAG_NO_SKINNY)) return bad("unknown flag bits");
   if ((c->max_tokens + c->page_tokens - 1) / c->page_tokens > 64)
     return bad("max_tokens / page_tokens must not exceed 64 pages per series");
   for (const tsd_model_cfg* m : {&c->target, &c->draft})
@@ -256,6 +258,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
     ctx->abuf = at(o_a);
     ctx->hbuf = at(o_h);
     ctx->rows_max = (int)rows;
+    ctx->skinny = (c.dtype == TSD_BF16 && !(c.flags & TSD_FLAG_NO_SKINNY) && (size_t)B * (K + 1) <= 32) ? 1 : 0;
     ctx->count_out = (int*)at(o_cnt);
     ctx->act_list = (int*)at(o_alist);
     ctx->moe_ids = topk ? (int*)at(o_ids) : nullptr;
@@ -319,6 +322,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
   if (M > ctx->rows_max) return fail(ctx, TSD_E_OUT_OF_RANGE, "pass exceeds the activation workspace");
   GemmP g;
   std::memset(&g, 0, sizeof(g));
+  g.allow_skinny = ctx->skinny;
   g.M = M;
   g.nq = ps.nq;
   // patch embedding
@@ -339,6 +343,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     char* pool = md.kv_pool + (size_t)l * md.layer_pool_bytes;
     GemmP q;
     std::memset(&q, 0, sizeof(q));
+    q.allow_skinny = ctx->skinny;
     q.M = M;
     q.nq = ps.nq;
     q.N = 3 * D;
@@ -387,6 +392,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     HIP_TRY(ctx, timed_launch(ctx, TSD_K_ATTN, attn_bytes, st, [&] { return launch_attention(c.dtype, a, c.max_tokens, st); }));
     GemmP o;
     std::memset(&o, 0, sizeof(o));
+    o.allow_skinny = ctx->skinny;
     o.M = M;
     o.nq = ps.nq;
     o.N = D;
@@ -443,6 +449,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     }
     GemmP f1;
     std::memset(&f1, 0, sizeof(f1));
+    f1.allow_skinny = ctx->skinny;
     f1.M = M;
     f1.nq = ps.nq;
     f1.N = F;
@@ -453,6 +460,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     HIP_TRY(ctx, timed_launch(ctx, TSD_K_GELU, 2.0 * M * D * F, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_GELU, f1, st); }));
     GemmP f2;
     std::memset(&f2, 0, sizeof(f2));
+    f2.allow_skinny = ctx->skinny;
     f2.M = M;
     f2.nq = ps.nq;
     f2.N = D;
@@ -466,6 +474,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
   if (ps.out) {
     GemmP h;
     std::memset(&h, 0, sizeof(h));
+    h.allow_skinny = ctx->skinny;
     h.M = M;
     h.nq = ps.nq;
     h.N = P;
@@ -1047,6 +1056,7 @@ int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_de
   }
   GemmP g;
   std::memset(&g, 0, sizeof(g));
+  g.allow_skinny = 1;  // products of at most 32 rows take the skinny kernel, as in a small-batch handle
   g.M = M;
   g.N = N;
   g.K = K;

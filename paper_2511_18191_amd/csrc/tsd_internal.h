@@ -69,6 +69,7 @@ struct GemmP {
   long w_stride;         // elements between consecutive experts' matrices in W
   int n_mtiles;          // entries of tile_map
   int force_bm;          // row-tile size the map was built for (0 = pick by problem size)
+  int allow_skinny;      // the handle runs its <= 32-row passes through the skinny kernel
   // EP_HEAD
   float* out;
   long out_stride_b;
@@ -94,6 +95,9 @@ struct AttnP {
 // ---- launchers (each returns the hipError_t of the launch) ---------------------------------
 hipError_t launch_gemm(int dtype, int amode, int epi, const GemmP& p, hipStream_t st);
 hipError_t prepare_gemm(int dtype);
+// skinny path (at most 32 rows): see gemm_skinny.hip
+bool skinny_applicable(int dtype, int amode, int epi, const GemmP& p);
+hipError_t launch_gemm_skinny(int amode, int epi, const GemmP& p, hipStream_t st);
 int gemm_row_tile(int dtype, int M, int N, int force_bm);
 // s_max: upper bound on (position of the pass's last token) + 1 over all series; sizes the score buffer.
 hipError_t launch_attention(int dtype, const AttnP& p, int s_max, hipStream_t st);

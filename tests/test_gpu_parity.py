@@ -315,9 +315,11 @@ def test_full_size_sampled_series(name, dtype, subset, rounds):
     assert torch.isfinite(sess.get_forecast()).all()
 
 
-@pytest.mark.parametrize("M,N,K", [(40, 96, 16), (77, 200, 264), (1280, 1536, 512), (300, 512, 2048), (2304, 1024, 1024)])
+@pytest.mark.parametrize("M,N,K", [(40, 96, 16), (77, 200, 264), (1280, 1536, 512), (300, 512, 2048), (2304, 1024, 1024),
+                                   (1, 96, 96), (9, 1024, 4096), (32, 3072, 1024), (17, 512, 264), (5, 256, 40)])
 def test_gemm_tap_matches_fp64_product(M, N, K):
-    # the tiled GEMM alone (ragged M/N/K tails, both tile sizes, XCD tile order) against a float64 product
+    # the GEMM kernels alone (tiled: ragged M/N/K tails, both tile sizes, XCD tile order; at most 32
+    # rows in bf16: the skinny weight-streaming kernel) against a float64 product
     import paper_2511_18191_amd as tsd
     g = torch.Generator().manual_seed(M * 7 + N)
     A = torch.randn(M, K, generator=g)
