@@ -26,7 +26,7 @@ def parse():
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--sigma", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-series", type=int, default=4, help="series in the oracle's bounded sample")
+    ap.add_argument("--cpu-series", type=int, default=64, help="series in the oracle's bounded sample (~10-20 s of CPU work at cfg2)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB copy kernel 5 times (known traffic, to scale profiler memory counters)")
     return ap.parse_args()

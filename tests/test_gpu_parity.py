@@ -377,3 +377,49 @@ def test_batch_position_invariance():
             ref = (X, mu_p)
         else:
             assert torch.equal(X, ref[0][perm]) and torch.equal(mu_p, ref[1][perm])
+
+
+def test_handle_reuse_and_error_paths():
+    import ctypes as C
+    import paper_2511_18191_amd as tsd
+    case = Case("mini2", sigma=0.5)
+    c = case.cfg
+    L = tsd.lib()
+    sess = case.session(max_batch=8)
+    # calls out of order are errors, not crashes
+    assert L.tsd_round(sess.h, sess._stream()) == -2 and b"prefill" in L.tsd_last_error(sess.h)
+    assert L.tsd_target_step(sess.h, sess._stream()) == -2
+    n = C.c_int32()
+    assert L.tsd_num_active(sess.h, C.byref(n), sess._stream()) == -2
+    # sizes beyond what the handle was created for
+    big = np.zeros((9, c.context), np.float32)
+    with pytest.raises(tsd.TsdError) as e:
+        sess.prefill(big, c.n_ctx, c.horizon)
+    assert e.value.code == -3
+    with pytest.raises(tsd.TsdError) as e:
+        sess.prefill(case.context, c.n_ctx, c.horizon + 96 * 5)
+    assert e.value.code == -3
+    with pytest.raises(tsd.TsdError) as e:
+        sess.prefill(case.context[:, :96], 1, c.horizon)          # a one-patch context
+    assert e.value.code == -1
+    blob = torch.zeros(17, device="cuda")
+    assert L.tsd_load_weights(sess.h, 0, blob.data_ptr(), 17, sess._stream()) == -1
+    assert L.tsd_profile_begin(sess.h, 99) == -1
+    with pytest.raises(tsd.TsdError):
+        sess.set_accept_override(1.5)
+
+    # one handle, several forecasts of different batch size / horizon: each equals a fresh handle's
+    def decode(s, ctx, horizon):
+        s.prefill(ctx, c.n_ctx, horizon)
+        while s.num_active() > 0:
+            s.round()
+        return s.get_forecast().cpu(), s.get_stats()
+
+    a1 = decode(sess, case.context, c.horizon)
+    a2 = decode(sess, case.context[:3], 96 * 2)
+    a3 = decode(sess, case.context, c.horizon)
+    f1 = decode(case.session(max_batch=8), case.context, c.horizon)
+    f2 = decode(case.session(max_batch=8), case.context[:3], 96 * 2)
+    assert torch.equal(a1[0], f1[0]) and a1[1] == f1[1]
+    assert torch.equal(a2[0], f2[0]) and a2[1] == f2[1]
+    assert torch.equal(a3[0], a1[0]) and a3[1] == a1[1]
