@@ -10,6 +10,7 @@
 #include <type_traits>
 
 #include "tsd_internal.h"
+#include "attn_mfma.h"
 
 namespace tsd {
 
@@ -214,131 +215,22 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
   }
 }
 
-// ---- bf16, head_dim 64: attention on the matrix cores, no LDS ---------------------------------
-// V is cached transposed inside a page ([head][dim][token]) so that both MFMA B-operands are
-// single 16-byte loads.  One wavefront per (series, head), 16 query rows per tile (K+1 <= 16 in
-// a round; prefill loops over tiles), keys in steps of 32:
-//   S^T = K Q^T   two 16x16x32 MFMAs per 16 keys; key rows are permuted so that lane group g
-//                 (lane / 16) ends up with scores of the 8 consecutive keys 8g .. 8g+7 of the step
-//                 for query lane % 16 -- exactly the A-operand layout of the next product;
-//   online softmax in fp32 (running max / sum per query, shared by its 4 lanes);
-//   O += P V      four 16x16x32 MFMAs (one per 16 output dims), V^T chunks straight from HBM.
-// Every K and V byte of the head is read exactly once per 16-query tile.
+// ---- bf16, head_dim 64: attention on the matrix cores, no LDS (core in attn_mfma.h) -------------
 __global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnP p) {
   const int lane = threadIdx.x;
   const int bl = blockIdx.x / p.Hh, h = blockIdx.x % p.Hh;
   const int b = p.act ? p.act[bl] : p.s0 + bl;
-  const int PT = p.PT, Hh = p.Hh, pts = p.pt_shift;
   const bf16* q = reinterpret_cast<const bf16*>(p.q);
   bf16* out = reinterpret_cast<bf16*>(p.out);
   const bf16* pool = reinterpret_cast<const bf16*>(p.kv_pool);
   const int my_page = p.page_table[(long)b * p.pt_stride + min(lane, p.pt_stride - 1)];
   const int base = (p.base_pos ? p.base_pos[b] : 0) + p.pos_off;
-  const int qi = lane & 15, g = lane >> 4;
-  const long page_elems = (long)2 * Hh * PT * 64;
-  const long v_off = (long)Hh * PT * 64;
-
   for (int q0 = 0; q0 < p.nq; q0 += 16) {
     const int nqt = min(16, p.nq - q0);
-    const int qrow = q0 + min(qi, nqt - 1);          // rows past the tile clone its last row
-    const int qpos = base + qrow;                    // last key this query may see
-    const int total = base + q0 + nqt;               // keys the tile's last query sees
-    bf16x8 qf[2];
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk)
-      qf[kk] = *reinterpret_cast<const bf16x8*>(q + ((long)bl * p.nq + qrow) * p.D + h * 64 + kk * 32 + g * 8);
-    f32x4 o[4];
-#pragma unroll
-    for (int nb = 0; nb < 4; ++nb) o[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY, l_run = 0.f;
-
-    for (int s0 = 0; s0 < total; s0 += 64) {        // two 32-key steps per trip, loads issued together
-      bf16x8 kf[2][2][2], vf[2][4];
-#pragma unroll
-      for (int st = 0; st < 2; ++st) {
-        const int sb = s0 + st * 32;
-#pragma unroll
-        for (int bi = 0; bi < 2; ++bi) {
-          // A-operand row qi of block bi holds key sb + 8*(qi/4) + 4*bi + qi%4
-          const int key = min(sb + 8 * (qi >> 2) + 4 * bi + (qi & 3), total - 1);
-          const int page = __shfl(my_page, key >> pts);
-          const bf16* kp = pool + page * page_elems + ((long)h * PT + (key & (PT - 1))) * 64;
-#pragma unroll
-          for (int kk = 0; kk < 2; ++kk) kf[st][bi][kk] = *reinterpret_cast<const bf16x8*>(kp + kk * 32 + g * 8);
-        }
-        // B-operand of P.V: 8 consecutive tokens sb + 8g .. of one dim, from the transposed V block
-        const int vkey = min(sb + 8 * g, ((total - 1) >> 3) << 3);
-        const int vpage = __shfl(my_page, vkey >> pts);
-        const bf16* vp = pool + vpage * page_elems + v_off + (long)h * 64 * PT + (vkey & (PT - 1));
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb) vf[st][nb] = *reinterpret_cast<const bf16x8*>(vp + (long)(nb * 16 + qi) * PT);
-      }
-#pragma unroll
-      for (int st = 0; st < 2; ++st) {
-        const int sb = s0 + st * 32;
-        if (sb >= total) break;                      // uniform across the wavefront
-        f32x4 sc[2];
-#pragma unroll
-        for (int bi = 0; bi < 2; ++bi) {
-          sc[bi] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int kk = 0; kk < 2; ++kk)
-            sc[bi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[st][bi][kk], qf[kk], sc[bi], 0, 0, 0);
-        }
-        // this lane now holds query qi's scores for keys sb + 8g + j, j = 4*bi + r
-        float sv[8];
-        float mx = -INFINITY;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int key = sb + 8 * g + j;
-          sv[j] = (key <= qpos) ? sc[j >> 2][j & 3] * p.scale : -INFINITY;
-          mx = fmaxf(mx, sv[j]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);        // finite: key 0 is visible to every query
-        const float alpha = __expf(m_run - m_new);
-        bf16x8 pf;
-        float psum = 0.f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const float e = __expf(sv[j] - m_new);
-          psum += e;
-          pf[j] = (bf16)e;
-        }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-        // accumulator rows of O are queries 4g + r: fetch their rescale factors from those lanes
-        float ar[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) ar[r] = __shfl(alpha, 4 * g + r);
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb) {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) o[nb][r] *= ar[r];
-          // tokens past the cached length may hold anything (even NaN bit patterns): P is 0 there,
-          // so zero V as well to keep 0 * x out of the accumulators
-          bf16x8 vv = vf[st][nb];
-#pragma unroll
-          for (int j = 0; j < 8; ++j)
-            if (sb + 8 * g + j >= total) vv[j] = (bf16)0.f;
-          o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf, vv, o[nb], 0, 0, 0);
-        }
-      }
-    }
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-    const float inv = 1.f / l_run;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const float ir = __shfl(inv, 4 * g + r);
-      const int qq = 4 * g + r;
-      if (qq < nqt) {
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-          out[((long)bl * p.nq + q0 + qq) * p.D + h * 64 + nb * 16 + qi] = (bf16)(o[nb][r] * ir);
-      }
-    }
+    const bf16* qt = q + ((long)bl * p.nq + q0) * p.D + h * 64;
+    bf16* ot = out + ((long)bl * p.nq + q0) * p.D + h * 64;
+    attn_tile_mfma(pool, h, p.Hh, p.PT, p.pt_shift, my_page, base + q0, nqt, p.scale,
+                   [&](int r) { return qt + (long)r * p.D; }, [&](int r) { return ot + (long)r * p.D; });
   }
 }
 
