@@ -25,7 +25,10 @@ What the paper fixes and what it leaves open
 Pins (tests/test_oracle_*.py): Philox known-answer vectors; closed forms of Eq. 5 / Eq. 6 and
 of the fidelity identity (Eq. 9); the model collapsing to a two-matmul closed form when the
 mixing matrices are zero; causality; single pass == K+1 passes; brute force over accept
-patterns; draft == target; sigma -> 0; the capped-geometric block-length law (Eq. 7).
+patterns; draft == target; sigma -> 0; the capped-geometric block-length law (Eq. 7); for the
+sampled variants a Kolmogorov-Smirnov test of the normal draws, the equal-covariance closed form
+2 Phi(-Delta/2) of the unscaled stochastic rule, a quadrature of the tempered rule's mean
+acceptance, and the fallback-noise energy r^2.
 The full transformer forward has no external reference value to compare against: beyond
 those structural pins it is "parity unpinned".
 """
@@ -60,8 +63,9 @@ def philox4x32_10(counter, key):
     return c0, c1, c2, c3
 
 
-def philox4x32_10_bulk(c0, c1, c2, c3, key):
-    """Vectorised form of `philox4x32_10` over uint64 arrays of counters (word 0 only)."""
+def philox4x32_10_bulk(c0, c1, c2, c3, key, all_words=False):
+    """Vectorised form of `philox4x32_10` over uint64 arrays of counters (word 0 only, or the four
+    output words stacked on a new last axis with all_words=True)."""
     c0, c1, c2, c3 = (np.asarray(c, dtype=np.uint64) & np.uint64(_MASK32) for c in np.broadcast_arrays(c0, c1, c2, c3))
     k0, k1 = int(key[0]) & _MASK32, int(key[1]) & _MASK32
     m32 = np.uint64(_MASK32)
@@ -72,7 +76,7 @@ def philox4x32_10_bulk(c0, c1, c2, c3, key):
         c0, c1, c2, c3 = (p1 >> s32) ^ c1 ^ np.uint64(k0), p1 & m32, (p0 >> s32) ^ c3 ^ np.uint64(k1), p0 & m32
         k0 = (k0 + _PHILOX_W0) & _MASK32
         k1 = (k1 + _PHILOX_W1) & _MASK32
-    return c0
+    return np.stack([c0, c1, c2, c3], axis=-1) if all_words else c0
 
 
 def word_to_uniform(w):
@@ -85,6 +89,42 @@ def uniform(seed, b, r, i):
     (from 0) and proposal position i (1-based).  Key = (low, high) 32 bits of the seed."""
     w = philox4x32_10((b, r, i, 0), (seed & _MASK32, (seed >> 32) & _MASK32))
     return word_to_uniform(w[0])
+
+
+# Standard normal draws for the sampled variants (Sec. "Fallback Correction and Sampled Variants").
+# The paper only says "epsilon"; fixed here: element e of the patch drawn for (series b, round r,
+# position i) in stream s comes from the Philox block with counter (b, r, i, s * 2^16 + e // 4);
+# its four words give four lattice uniforms u0..u3 (as above) and two Box-Muller pairs
+#   z0, z1 = sqrt(-2 ln u0) * (cos, sin)(2 pi u1),   z2, z3 = sqrt(-2 ln u2) * (cos, sin)(2 pi u3),
+# and element e takes z_(e mod 4).  Stream 1 feeds proposals, stream 2 the fallback / bonus patch;
+# the acceptance uniform keeps the fourth counter word 0, so the three never share a block.
+STREAM_PROPOSAL = 1
+STREAM_FALLBACK = 2
+
+
+def _box_muller(words):
+    """[..., 4] Philox words -> [..., 4] standard normals."""
+    u = ((np.asarray(words, dtype=np.uint64) >> np.uint64(9)).astype(np.float64) + 0.5) * 2.0 ** -23
+    rad0, rad1 = np.sqrt(-2.0 * np.log(u[..., 0])), np.sqrt(-2.0 * np.log(u[..., 2]))
+    a0, a1 = 2.0 * np.pi * u[..., 1], 2.0 * np.pi * u[..., 3]
+    return np.stack([rad0 * np.cos(a0), rad0 * np.sin(a0), rad1 * np.cos(a1), rad1 * np.sin(a1)], axis=-1)
+
+
+def normal(seed, b, r, i, stream, P):
+    """The P standard normal draws of series b, round r, position i (1-based), stream `stream`."""
+    key = (seed & _MASK32, (seed >> 32) & _MASK32)
+    blocks = [philox4x32_10((b, r, i, (stream << 16) + j), key) for j in range(-(-P // 4))]
+    return _box_muller(np.array(blocks, dtype=np.uint64)).reshape(-1)[:P]
+
+
+def normal_bulk(seed, b, r, i, stream, P):
+    """`normal` over broadcastable integer arrays b, r, i: returns [..., P]."""
+    key = (seed & _MASK32, (seed >> 32) & _MASK32)
+    b, r, i = np.broadcast_arrays(np.asarray(b, dtype=np.uint64), np.asarray(r, dtype=np.uint64), np.asarray(i, dtype=np.uint64))
+    j = np.arange(-(-P // 4), dtype=np.uint64) + np.uint64(stream << 16)
+    w = philox4x32_10_bulk(b[..., None], r[..., None], i[..., None], j, key, all_words=True)   # [..., P/4, 4]
+    z = _box_muller(w)
+    return z.reshape(z.shape[:-2] + (-1,))[..., :P]
 
 
 # ----------------------------------------------------------------------------------------------
@@ -196,13 +236,19 @@ def log_ratio(x, mu_p, mu_q, sigma_p, sigma_q):
             + 0.5 * math.log(sigma_q ** 2 / sigma_p ** 2))
 
 
-def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True, alpha_override=None):
+def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True, alpha_override=None,
+               eps_fn=None, sample_proposals=False, fallback_r=0.0):
     """One speculative round for one series.
 
     hist: [n, P] normalised history (context patches then committed patches).
     u_fn(i) -> the uniform for proposal position i (1-based).
     alpha_override: if not None, the acceptance probability of every position is this constant
         (used to test the block-length law under an i.i.d. acceptance rate).
+    Sampled variants (Sec. "Fallback Correction and Sampled Variants", "Bonus Patch"):
+    eps_fn(stream, i) -> P standard normals for position i; with sample_proposals the draft
+    proposes x_i = mu_q^(i) + sigma_q eps (and conditions its next step on that draw); with
+    fallback_r = r > 0 the corrected / bonus patch is mu_p^(n+1) + r eps.  The defaults are the
+    deployed mean-propagating scheme (x_i = mu_q^(i), t = mu_p^(n+1)).
     Returns a dict with X, mu_q [K, P], mu_p [K+1, P], ell, logu [K] (nan where untested),
     n (accepted count) and commits [n + 1, P].
     """
@@ -211,9 +257,9 @@ def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True
     X = np.empty((K, P))
     mu_q = np.empty((K, P))
     cur = hist
-    for i in range(K):                               # K sequential draft passes, mean proposals
+    for i in range(K):                               # K sequential draft passes
         mu_q[i] = forward(Wd, md, cur)[-1]
-        X[i] = mu_q[i]
+        X[i] = mu_q[i] + sigma_q * eps_fn(STREAM_PROPOSAL, i + 1) if sample_proposals else mu_q[i]
         cur = np.vstack([cur, X[i][None, :]])
     n0 = hist.shape[0]
     if single_pass:                                  # one causal pass, read at the K+1 boundaries
@@ -231,12 +277,14 @@ def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True
             n += 1
         else:
             break
-    commits = np.vstack([X[:n], mu_p[n][None, :]])   # fallback (n < K) or bonus (n == K)
+    t = mu_p[n] + fallback_r * eps_fn(STREAM_FALLBACK, n + 1) if fallback_r > 0.0 else mu_p[n]
+    commits = np.vstack([X[:n], t[None, :]])         # fallback (n < K) or bonus (n == K)
     return dict(X=X, mu_q=mu_q, mu_p=mu_p, ell=ell, logu=logu, n=n, commits=commits)
 
 
 def forecast_spec(Wt, mt, Wd, md, series_context, P, horizon, K, sigma_p, sigma_q, seed, b,
-                  single_pass=True, alpha_override=None, u_fn=None, trace=None):
+                  single_pass=True, alpha_override=None, u_fn=None, trace=None, sample_proposals=False,
+                  fallback_r=0.0):
     """Speculative forecast of one series.  series_context: raw context steps (length N * P).
     Returns (forecast [horizon] in raw units, stats dict).  `trace`, if a list, receives each
     round's record."""
@@ -249,8 +297,10 @@ def forecast_spec(Wt, mt, Wd, md, series_context, P, horizon, K, sigma_p, sigma_
     r = 0
     while Y.shape[0] < T:
         draw = (lambda i, r=r: u_fn(b, r, i)) if u_fn is not None else (lambda i, r=r: uniform(seed, b, r, i))
+        eps = lambda stream, i, r=r: normal(seed, b, r, i, stream, P)
         rec = spec_round(Wt, mt, Wd, md, np.vstack([hist, Y]), K, sigma_p, sigma_q, draw,
-                         single_pass=single_pass, alpha_override=alpha_override)
+                         single_pass=single_pass, alpha_override=alpha_override, eps_fn=eps,
+                         sample_proposals=sample_proposals, fallback_r=fallback_r)
         if trace is not None:
             trace.append(rec)
         n = rec["n"]

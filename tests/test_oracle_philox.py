@@ -68,3 +68,14 @@ def test_uniform_statistics():
     w2 = orc.philox4x32_10_bulk(b, r, 2, 0, (2021, 0))
     u2 = ((w2 >> np.uint64(9)).astype(np.float64) + 0.5) * 2.0 ** -23
     assert abs(np.corrcoef(u, u2)[0, 1]) < 4 / math.sqrt(n)
+
+
+def test_bulk_all_words_equals_scalar():
+    # the sampled variants consume all four output words of a block
+    rng = np.random.default_rng(5)
+    c = rng.integers(0, 2 ** 32, size=(50, 4), dtype=np.uint64)
+    key = (0xA4093822, 0x299F31D0)
+    w = orc.philox4x32_10_bulk(c[:, 0], c[:, 1], c[:, 2], c[:, 3], key, all_words=True)
+    assert w.shape == (50, 4)
+    for row, ctr in zip(w, c):
+        assert tuple(int(x) for x in row) == orc.philox4x32_10(tuple(int(x) for x in ctr), key)
