@@ -64,6 +64,7 @@ extern "C" {
 #define TSD_FLAG_NO_GRAPH 4u       /* launch kernels one by one instead of replaying HIP graphs */
 #define TSD_FLAG_NO_COMPACT 8u     /* always run passes over the whole batch (see tsd_num_active) */
 #define TSD_FLAG_NO_SKINNY 16u     /* never use the <= 32-row weight-streaming GEMM                */
+#define TSD_FLAG_SAMPLE_PROPOSALS 32u /* ablation: x_i = mu_q^(i) + sigma_q eps instead of the mean */
 
 typedef struct tsd_ctx tsd_ctx; /* opaque */
 
@@ -83,7 +84,7 @@ typedef struct {
   int32_t page_tokens; /* tokens per KV page (power of two, 1..64)                              */
   float sigma_p;       /* acceptance temperature of the target surrogate (Eq. 4)                */
   float sigma_q;       /* ... of the draft surrogate; equal to sigma_p in the deployed scheme   */
-  float fallback_r;    /* fallback noise; must be 0 (target-mean fallback)                      */
+  float fallback_r;    /* fallback noise r in [0, sigma_p]; 0 = target-mean fallback (deployed) */
   uint32_t flags;
   uint64_t seed;       /* Philox key = (low 32 bits, high 32 bits)                              */
 } tsd_config;
@@ -135,7 +136,14 @@ int tsd_reset_decode(tsd_ctx* ctx, void* stream);
 
 /* Algorithm "One speculative round", first loop: K sequential draft passes; proposal i is the
  * draft's mean given the history and proposals 1..i-1 (mean-propagating scheme, x_i = mu_q^(i)).
- * Fills the internal X [B,K,P]. */
+ * With TSD_FLAG_SAMPLE_PROPOSALS (Sec. "Fallback Correction and Sampled Variants", an ablation
+ * knob) proposal i is the draw x_i = mu_q^(i) + sigma_q eps_i, which the next draft step and the
+ * target then consume.  eps: element e of the patch of (series b, that series' round r, position
+ * i) comes from Philox4x32-10 with counter (b, r, i, stream * 2^16 + e / 4), stream = 1 for
+ * proposals and 2 for the fallback patch: the block's four words give lattice uniforms u0..u3
+ * (as for the acceptance uniform) and the Box-Muller pairs sqrt(-2 ln u0) (cos, sin)(2 pi u1),
+ * sqrt(-2 ln u2) (cos, sin)(2 pi u3); element e takes number e mod 4.
+ * Fills the internal X [B,K,P] (and mu_q [B,K,P] when sampling). */
 int tsd_draft_propose(tsd_ctx* ctx, void* stream);
 
 /* Single-pass verification (Sec. "Single-Pass Verification"): one causal target pass over the
@@ -151,7 +159,8 @@ int tsd_target_verify(tsd_ctx* ctx, void* stream);
  *   n = number of leading accepts; commit x_1..x_n then mu_p^(n+1) (fallback if n < K, bonus
  *   if n = K), truncated at T = ceil(H/P) patches; both KV caches keep exactly the entries of
  *   the committed history; mu_p^(n+1) becomes the pending token; a series with T patches
- *   becomes inactive.
+ *   becomes inactive.  With fallback_r = r > 0 the corrected / bonus patch is the draw
+ *   mu_p^(n+1) + r eps (stream 2, position n+1; Sec. "Bonus Patch on Full Acceptance").
  * forced_len_dev (nullable): int32 [B]; entry b in 0..K overrides n for series b after the test
  * has been evaluated and recorded (used to keep two implementations in lock-step); -1 = free. */
 int tsd_accept_commit(tsd_ctx* ctx, const int32_t* forced_len_dev, void* stream);

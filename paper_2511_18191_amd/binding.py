@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 TSD_F32, TSD_BF16 = 0, 1
 TSD_TARGET, TSD_DRAFT = 0, 1
-TSD_FLAG_SCRAMBLE_PAGES, TSD_FLAG_NO_TEMPERING, TSD_FLAG_NO_GRAPH, TSD_FLAG_NO_COMPACT, TSD_FLAG_NO_SKINNY = 1, 2, 4, 8, 16
+TSD_FLAG_SCRAMBLE_PAGES, TSD_FLAG_NO_TEMPERING, TSD_FLAG_NO_GRAPH, TSD_FLAG_NO_COMPACT, TSD_FLAG_NO_SKINNY, TSD_FLAG_SAMPLE_PROPOSALS = 1, 2, 4, 8, 16, 32
 KERNEL_CLASSES = ["embed", "qkv", "attn", "resid", "gelu", "head", "accept", "route"]   # TSD_K_* order
 
 
@@ -92,12 +92,12 @@ def lib():
 
 
 def make_config(target, draft, patch, K, max_batch, max_tokens, dtype, sigma_p, sigma_q=None, seed=0,
-                page_tokens=16, flags=0):
+                page_tokens=16, flags=0, fallback_r=0.0):
     """target/draft: objects with n_layers, d_model, n_heads, d_ff, n_experts, top_k."""
     mk = lambda m: TsdModelCfg(m.n_layers, m.d_model, m.n_heads, m.d_ff, getattr(m, "n_experts", 0), getattr(m, "top_k", 0))
     dt = {"fp32": TSD_F32, "bf16": TSD_BF16}.get(dtype, dtype)
     return TsdConfig(mk(target), mk(draft), patch, K, max_batch, max_tokens, dt, page_tokens, sigma_p,
-                     sigma_p if sigma_q is None else sigma_q, 0.0, flags, seed)
+                     sigma_p if sigma_q is None else sigma_q, fallback_r, flags, seed)
 
 
 def _check(rc, ctx=None):
@@ -274,13 +274,13 @@ class Session:
         _check(lib().tsd_set_sigma(self.h, sigma_p, sigma_p if sigma_q is None else sigma_q), self.h)
 
 
-def session_for(inputs, flags=0, page_tokens=16, max_batch=None, sigma_q=None):
+def session_for(inputs, flags=0, page_tokens=16, max_batch=None, sigma_q=None, fallback_r=0.0):
     """A Session sized for `inputs` (an object with cfg, wt, wd, seed as synth.Inputs has) with both
     models' weights loaded."""
     import synth
     c = inputs.cfg
     tc = make_config(c.target, c.draft, c.patch, c.K, max_batch or c.batch, c.max_tokens, c.dtype, c.sigma, sigma_q,
-                     seed=inputs.seed, page_tokens=page_tokens, flags=flags)
+                     seed=inputs.seed, page_tokens=page_tokens, flags=flags, fallback_r=fallback_r)
     s = Session(tc)
     s.load_weights(TSD_TARGET, synth.flatten_weights(c.target, c.patch, inputs.wt))
     s.load_weights(TSD_DRAFT, synth.flatten_weights(c.draft, c.patch, inputs.wd))

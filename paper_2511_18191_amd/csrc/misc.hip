@@ -104,9 +104,9 @@ hipError_t launch_reset(const PrefillP& p, hipStream_t st) {
 }
 
 // ---- acceptance + correction + commit + rollback ---------------------------------------------
-// Philox4x32-10 (Salmon et al., SC'11): counter (c0..c3), key (k0, k1); returns output word 0.
-__device__ __forceinline__ unsigned philox_word0(unsigned c0, unsigned c1, unsigned c2, unsigned c3, unsigned k0,
-                                                 unsigned k1) {
+// Philox4x32-10 (Salmon et al., SC'11): counter (c0..c3), key (k0, k1) -> four output words.
+__device__ __forceinline__ void philox4(unsigned c0, unsigned c1, unsigned c2, unsigned c3, unsigned k0, unsigned k1,
+                                        unsigned (&w)[4]) {
   const unsigned M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
@@ -120,7 +120,50 @@ __device__ __forceinline__ unsigned philox_word0(unsigned c0, unsigned c1, unsig
     k0 += 0x9E3779B9u;
     k1 += 0xBB67AE85u;
   }
-  return c0;
+  w[0] = c0;
+  w[1] = c1;
+  w[2] = c2;
+  w[3] = c3;
+}
+__device__ __forceinline__ unsigned philox_word0(unsigned c0, unsigned c1, unsigned c2, unsigned c3, unsigned k0,
+                                                 unsigned k1) {
+  unsigned w[4];
+  philox4(c0, c1, c2, c3, k0, k1, w);
+  return w[0];
+}
+// 23-bit mid-point lattice uniform of a Philox word: exact in fp32, strictly inside (0, 1).
+__device__ __forceinline__ float word_uniform(unsigned w) { return ((float)(w >> 9) + 0.5f) * 1.1920928955078125e-07f; }
+
+// Standard normal draw for element e of the patch of (series b, round r, position i) in `stream`
+// (1 = proposals, 2 = fallback / bonus patch; Sec. "Fallback Correction and Sampled Variants"):
+// Philox block (b, r, i, stream * 2^16 + e / 4) gives uniforms u0..u3 and the Box-Muller pairs
+// sqrt(-2 ln u0) (cos, sin)(2 pi u1), sqrt(-2 ln u2) (cos, sin)(2 pi u3); element e takes
+// number e % 4.  sincospi keeps the angle exact (2 u is representable).
+constexpr unsigned kStreamProposal = 1u, kStreamFallback = 2u;
+__device__ __forceinline__ float normal_draw(unsigned b, unsigned r, unsigned i, unsigned stream, int e, unsigned k0,
+                                             unsigned k1) {
+  unsigned w[4];
+  philox4(b, r, i, (stream << 16) + (unsigned)(e >> 2), k0, k1, w);
+  const int pair = (e >> 1) & 1;
+  const float rad = sqrtf(-2.0f * logf(word_uniform(w[2 * pair])));
+  float sn, cs;
+  sincospif(2.0f * word_uniform(w[2 * pair + 1]), &sn, &cs);
+  return rad * ((e & 1) ? sn : cs);
+}
+
+// Sampled proposals: X[b, i-1, :] = mu_q[b, i-1, :] + sigma_q * eps for the covered series, with
+// each series' own round counter.  One 64-thread block per series.
+__global__ __launch_bounds__(64) void sample_kernel(const SampleP p) {
+  const int b = p.act ? p.act[blockIdx.x] : (int)blockIdx.x;
+  const unsigned r = (unsigned)p.round[b];
+  const long off = ((long)b * p.K + (p.i - 1)) * p.P;
+  for (int e = threadIdx.x; e < p.P; e += 64)
+    p.X[off + e] = p.mu_q[off + e] + p.sigma_q * normal_draw((unsigned)b, r, (unsigned)p.i, kStreamProposal, e, p.key0, p.key1);
+}
+hipError_t launch_sample(const SampleP& p, hipStream_t st) {
+  if (p.n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(sample_kernel, dim3(p.n), dim3(64), 0, st, p);
+  return hipGetLastError();
 }
 
 // One wavefront per series.  Energies are reduced across lanes per proposal, then lane i owns
@@ -169,7 +212,7 @@ __global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
     // Eq. 5 with per-dimension energies ||.||^2 / P
     ell = p.temper * (-(my_ep / (float)P) * p.inv2sp2 + (my_eq / (float)P) * p.inv2sq2 + p.logdet);
     unsigned w = philox_word0((unsigned)b, (unsigned)r, (unsigned)(lane + 1), 0u, p.key0, p.key1);
-    float u = ((float)(w >> 9) + 0.5f) * 1.1920928955078125e-07f;  // 2^-23; exact in fp32
+    float u = word_uniform(w);
     logu = logf(u);
     thr = (p.log_alpha_override <= 0.f) ? p.log_alpha_override : fminf(0.f, ell);
     reject = !(logu <= thr);
@@ -192,14 +235,17 @@ __global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
   const int L = n + 1;
   const int Lc = min(L, p.T - c0);
   float* fc = p.forecast + ((long)b * p.T + c0) * P;
-  for (int j = 0; j < Lc; ++j) {
-    const float* src = (j < n) ? X + j * P : MP + n * P;
-    for (int e = lane; e < P; e += 64) fc[j * P + e] = src[e];
-  }
+  for (int j = 0; j < min(Lc, n); ++j)
+    for (int e = lane; e < P; e += 64) fc[j * P + e] = X[j * P + e];
+  // corrected (n < K) or bonus (n = K) patch: the target mean, plus r * eps when fallback noise is on
   for (int e = lane; e < P; e += 64) {
+    float t = MP[n * P + e];
+    if (p.fallback_r > 0.f)
+      t += p.fallback_r * normal_draw((unsigned)b, (unsigned)r, (unsigned)(n + 1), kStreamFallback, e, p.key0, p.key1);
+    if (n < Lc) fc[n * P + e] = t;
     float old_pending = p.pending[(long)b * P + e];
     p.prev[(long)b * P + e] = (n >= 1) ? X[(n - 1) * P + e] : old_pending;
-    p.pending[(long)b * P + e] = MP[n * P + e];
+    p.pending[(long)b * P + e] = t;
   }
   if (lane == 0) {
     p.n_acc[b] = n_free;

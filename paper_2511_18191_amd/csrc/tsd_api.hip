@@ -138,8 +138,8 @@ int check_config(const tsd_config* c, std::string& why) {
   if (!is_pow2(c->page_tokens) || c->page_tokens > 64) return bad("page_tokens must be a power of two <= 64");
   if (!(c->sigma_p > 0.f) || !(c->sigma_q > 0.f) || !std::isfinite(c->sigma_p) || !std::isfinite(c->sigma_q))
     return bad("sigma_p and sigma_q must be positive and finite");
-  if (c->fallback_r != 0.f) return bad("fallback_r must be 0 (target-mean fallback)");
-  if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING | TSD_FLAG_NO_GRAPH | TSD_FLAG_NO_COMPACT | TSD_FLAG_NO_SKINNY)) return bad("unknown flag bits");
+  if (!(c->fallback_r >= 0.f) || c->fallback_r > c->sigma_p) return bad("fallback_r must lie in [0, sigma_p]");
+  if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING | TSD_FLAG_NO_GRAPH | TSD_FLAG_NO_COMPACT | TSD_FLAG_NO_SKINNY | TSD_FLAG_SAMPLE_PROPOSALS)) return bad("unknown flag bits");
   if ((c->max_tokens + c->page_tokens - 1) / c->page_tokens > 64)
     return bad("max_tokens / page_tokens must not exceed 64 pages per series");
   for (const tsd_model_cfg* m : {&c->target, &c->draft})
@@ -553,7 +553,8 @@ int accept_commit_impl(tsd_ctx* ctx, const int32_t* forced, int K, hipStream_t s
   AcceptP a;
   std::memset(&a, 0, sizeof(a));
   a.X = ctx->X;
-  a.mu_q = ctx->injected ? ctx->mu_q : ctx->X;  // mean-propagating scheme: x_i = mu_q^(i)
+  const bool sampled = (c.flags & TSD_FLAG_SAMPLE_PROPOSALS) != 0;
+  a.mu_q = (ctx->injected || sampled) ? ctx->mu_q : ctx->X;  // mean-propagating scheme: x_i = mu_q^(i)
   a.mu_p = ctx->mu_p;
   a.forced = forced;
   a.pending = ctx->pending;
@@ -579,6 +580,7 @@ int accept_commit_impl(tsd_ctx* ctx, const int32_t* forced, int K, hipStream_t s
   a.logdet = 0.5f * std::log((c.sigma_q * c.sigma_q) / (c.sigma_p * c.sigma_p));
   a.temper = (c.flags & TSD_FLAG_NO_TEMPERING) ? (float)c.patch : 1.0f;
   a.log_alpha_override = ctx->alpha_override > 0.f ? std::log(ctx->alpha_override) : 1.0f;
+  a.fallback_r = K > 0 ? c.fallback_r : 0.f;  // the target-only step commits the target mean
   a.key0 = (unsigned)(c.seed & 0xFFFFFFFFull);
   a.key1 = (unsigned)(c.seed >> 32);
   HIP_TRY(ctx, timed_launch(ctx, TSD_K_ACCEPT, 4.0 * ctx->B * c.patch * (2.0 * K + 2), st, [&] { return launch_accept(a, st); }));
@@ -842,10 +844,33 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
   ps.n0 = 1;
   ps.src1 = ctx->pending;
   ps.stride1 = P;
-  ps.out = ctx->X;
+  // Sampled proposals: the head writes mu_q^(i) to its own buffer and a small kernel adds
+  // sigma_q * eps into X, which the next step (and the target) then consume.
+  const bool sampled = (c.flags & TSD_FLAG_SAMPLE_PROPOSALS) != 0;
+  float* head_out = sampled ? ctx->mu_q : ctx->X;
+  auto draw = [&](int i) -> int {
+    if (!sampled) return TSD_OK;
+    SampleP sp;
+    std::memset(&sp, 0, sizeof(sp));
+    sp.mu_q = ctx->mu_q;
+    sp.X = ctx->X;
+    sp.act = cv.act;
+    sp.round = ctx->round;
+    sp.n = cv.n;
+    sp.K = K;
+    sp.P = P;
+    sp.i = i;
+    sp.sigma_q = c.sigma_q;
+    sp.key0 = (unsigned)(c.seed & 0xFFFFFFFFull);
+    sp.key1 = (unsigned)(c.seed >> 32);
+    HIP_TRY(ctx, launch_sample(sp, st));
+    return TSD_OK;
+  };
+  ps.out = head_out;
   ps.out_stride_b = (long)K * P;
   ps.t_skip = 1;
   if ((rc = run_pass(ctx, ps, st))) return rc;
+  if ((rc = draw(1))) return rc;
   for (int i = 2; i <= K; ++i) {  // step i consumes x_{i-1} at position len + i - 1, emits x_i
     std::memset(&ps, 0, sizeof(ps));
     ps.which = TSD_DRAFT;
@@ -857,10 +882,11 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
     ps.src0 = ctx->X + (size_t)(i - 2) * P;
     ps.stride0 = (long)K * P;
     ps.n0 = 1;
-    ps.out = ctx->X + (size_t)(i - 1) * P;
+    ps.out = head_out + (size_t)(i - 1) * P;
     ps.out_stride_b = (long)K * P;
     ps.t_skip = 0;
     if ((rc = run_pass(ctx, ps, st))) return rc;
+    if ((rc = draw(i))) return rc;
   }
   return TSD_OK;
 }
@@ -966,7 +992,8 @@ int tsd_get_round_io(tsd_ctx* ctx, float* X_dev, float* mu_q_dev, float* mu_p_de
     return dst ? hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, st) : hipSuccess;
   };
   HIP_TRY(ctx, cp(X_dev, ctx->X, B * K * P * 4));
-  HIP_TRY(ctx, cp(mu_q_dev, ctx->X, B * K * P * 4));  // proposals are the draft means
+  // mean proposals: x_i = mu_q^(i), one buffer; sampled proposals keep the means beside the draws
+  HIP_TRY(ctx, cp(mu_q_dev, (ctx->cfg.flags & TSD_FLAG_SAMPLE_PROPOSALS) ? ctx->mu_q : ctx->X, B * K * P * 4));
   HIP_TRY(ctx, cp(mu_p_dev, ctx->mu_p, B * (K + 1) * P * 4));
   HIP_TRY(ctx, cp(n_acc_dev, ctx->n_acc, B * 4));
   HIP_TRY(ctx, cp(ell_dev, ctx->ell, B * K * 4));

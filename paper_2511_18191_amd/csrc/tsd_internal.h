@@ -150,9 +150,21 @@ struct AcceptP {
   int B, K, P, T;
   float inv2sp2, inv2sq2, logdet, temper;  // temper = 1 (Eq. 5) or P (ablation without 1/d)
   float log_alpha_override;                // > 0 means "no override"
+  float fallback_r;                        // noise scale of the corrected / bonus patch (0: target mean)
   unsigned key0, key1;
 };
 hipError_t launch_accept(const AcceptP& p, hipStream_t st);
+
+struct SampleP {  // X[b, i-1] = mu_q[b, i-1] + sigma_q * eps(b, round[b], i)
+  const float* mu_q;
+  float* X;
+  const int* act;    // block j handles series act[j] (NULL: series j)
+  const int* round;
+  int n, K, P, i;
+  float sigma_q;
+  unsigned key0, key1;
+};
+hipError_t launch_sample(const SampleP& p, hipStream_t st);
 
 hipError_t prepare_moe();
 hipError_t launch_router(const float* x, const float* Wr, int M, int D, int E, int topk, int* ids, float* gates,

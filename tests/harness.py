@@ -38,10 +38,13 @@ class Case(synth.Inputs):
         return ((ctx - m) / s).reshape(-1, self.cfg.patch), m, s
 
 
-def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=True, tol=None, subset=None):
+def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=True, tol=None, subset=None,
+             sample_proposals=False, fallback_r=0.0):
     """Run GPU and oracle round by round on the same histories.  The GPU evaluates its own
     acceptance test (recorded) but commits the oracle's accepted length, so the two histories
-    stay aligned and every round's tensors can be compared.  Returns a report dict."""
+    stay aligned and every round's tensors can be compared.  Returns a report dict.
+    sample_proposals / fallback_r: the oracle's noise knobs; the session must have been created
+    with the matching flag / fallback_r."""
     import torch
     c = case.cfg
     B, K, P, T = c.batch, c.K, c.patch, c.T
@@ -65,14 +68,16 @@ def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=Tru
             if Y[b].shape[0] >= T:
                 continue
             recs[b] = orc.spec_round(case.Wt, c.target, case.Wd, c.draft, np.vstack([hist[b], Y[b]]), K, c.sigma, sq,
-                                     (lambda i, b=b: orc.uniform(case.seed, b, rnd[b], i)))
+                                     (lambda i, b=b: orc.uniform(case.seed, b, rnd[b], i)),
+                                     eps_fn=(lambda stream, i, b=b: orc.normal(case.seed, b, rnd[b], i, stream, P)),
+                                     sample_proposals=sample_proposals, fallback_r=fallback_r)
             forced[b] = recs[b]["n"]
         sess.accept_commit(torch.from_numpy(forced))
         io = {k: v.cpu().numpy() for k, v in sess.get_round_io().items()}
         for b, rec in recs.items():
             n = rec["n"]
             # compare what both sides computed from (nearly) identical histories
-            rx = rel_err(io["X"][b], rec["X"]).max()
+            rx = max(rel_err(io["X"][b], rec["X"]).max(), rel_err(io["mu_q"][b], rec["mu_q"]).max())
             rp = rel_err(io["mu_p"][b], rec["mu_p"]).max()
             rep["max_rel_X"] = max(rep["max_rel_X"], rx)
             rep["max_rel_mu_p"] = max(rep["max_rel_mu_p"], rp)
@@ -84,13 +89,16 @@ def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=Tru
                 Xg, n0 = io["X"][b].astype(np.float64), hg.shape[0]
                 for i in range(K):
                     q_ref = orc.forward(case.Wd, c.draft, np.vstack([hg, Xg[:i]]))[-1]
-                    rep["pass_rel_q"] = max(rep["pass_rel_q"], rel_err(Xg[i], q_ref))
+                    rep["pass_rel_q"] = max(rep["pass_rel_q"], rel_err(io["mu_q"][b][i], q_ref))
                 p_ref = orc.forward(case.Wt, c.target, np.vstack([hg, Xg]))[n0 - 1:]
                 rep["pass_rel_p"] = max(rep["pass_rel_p"], rel_err(io["mu_p"][b], p_ref).max())
                 if check:
                     assert rep["pass_rel_q"] <= PASS_TOL[c.dtype] and rep["pass_rel_p"] <= PASS_TOL[c.dtype], \
                         f"series {b} round {rnd[b]}: per-pass error {rep['pass_rel_q']:.3e} / {rep['pass_rel_p']:.3e}"
-                Yg[b] = np.vstack([Yg[b], Xg[:n], io["mu_p"][b][n][None, :].astype(np.float64)])[:T]
+                t_g = io["mu_p"][b][n].astype(np.float64)
+                if fallback_r > 0.0:    # what the GPU committed, up to the rounding of its own draw
+                    t_g = t_g + fallback_r * orc.normal(case.seed, b, rnd[b], n + 1, orc.STREAM_FALLBACK, P)
+                Yg[b] = np.vstack([Yg[b], Xg[:n], t_g[None, :]])[:T]
             tested = n + (1 if n < K else 0)
             gap = np.abs(np.minimum(0.0, rec["ell"][:tested]) - rec["logu"][:tested])
             near = bool(np.any(gap < 1e-4))
