@@ -65,6 +65,7 @@ extern "C" {
 #define TSD_FLAG_NO_COMPACT 8u     /* always run passes over the whole batch (see tsd_num_active) */
 #define TSD_FLAG_NO_SKINNY 16u     /* never use the <= 32-row weight-streaming GEMM                */
 #define TSD_FLAG_SAMPLE_PROPOSALS 32u /* ablation: x_i = mu_q^(i) + sigma_q eps instead of the mean */
+#define TSD_FLAG_NAIVE_VERIFY 64u  /* ablation: one target pass per prefix instead of one causal pass */
 
 typedef struct tsd_ctx tsd_ctx; /* opaque */
 
@@ -148,7 +149,10 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream);
 
 /* Single-pass verification (Sec. "Single-Pass Verification"): one causal target pass over the
  * pending token and x_1..x_K against the paged KV cache; the output at token j is the target
- * mean at prefix boundary j+1.  Fills the internal mu_p [B,K+1,P]. */
+ * mean at prefix boundary j+1.  Fills the internal mu_p [B,K+1,P].
+ * With TSD_FLAG_NAIVE_VERIFY (the component ablation's "w/o single-pass verification") each of
+ * the K+1 prefixes is re-encoded by its own pass against the cached context and only its last
+ * boundary is read: same mu_p up to rounding, (K+1)(K+2)/2 target tokens per round. */
 int tsd_target_verify(tsd_ctx* ctx, void* stream);
 
 /* Acceptance (Eq. 5 / Eq. 6), correction, commit and KV rollback for every active series:

@@ -139,7 +139,8 @@ int check_config(const tsd_config* c, std::string& why) {
   if (!(c->sigma_p > 0.f) || !(c->sigma_q > 0.f) || !std::isfinite(c->sigma_p) || !std::isfinite(c->sigma_q))
     return bad("sigma_p and sigma_q must be positive and finite");
   if (!(c->fallback_r >= 0.f) || c->fallback_r > c->sigma_p) return bad("fallback_r must lie in [0, sigma_p]");
-  if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING | TSD_FLAG_NO_GRAPH | TSD_FLAG_NO_COMPACT | TSD_FLAG_NO_SKINNY | TSD_FLAG_SAMPLE_PROPOSALS)) return bad("unknown flag bits");
+  if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING | TSD_FLAG_NO_GRAPH | TSD_FLAG_NO_COMPACT | TSD_FLAG_NO_SKINNY | TSD_FLAG_SAMPLE_PROPOSALS |
+                   TSD_FLAG_NAIVE_VERIFY)) return bad("unknown flag bits");
   if ((c->max_tokens + c->page_tokens - 1) / c->page_tokens > 64)
     return bad("max_tokens / page_tokens must not exceed 64 pages per series");
   for (const tsd_model_cfg* m : {&c->target, &c->draft})
@@ -914,6 +915,18 @@ int tsd_target_verify(tsd_ctx* ctx, void* stream) {
   ps.out = ctx->mu_p;
   ps.out_stride_b = (long)(K + 1) * P;
   ps.t_skip = 0;
+  if (c.flags & TSD_FLAG_NAIVE_VERIFY) {
+    // Ablation "w/o single-pass verification": every prefix [pending, x_1..x_{i-1}] is encoded by
+    // a pass of its own and only its last boundary is read, so a round costs (K+1)(K+2)/2 target
+    // tokens instead of K+1.  (Each pass rewrites the same KV entries with the same values.)
+    for (int i = 1; i <= K + 1; ++i) {
+      ps.nq = i;
+      ps.t_skip = i - 1;
+      ps.out = ctx->mu_p + (size_t)(i - 1) * P;
+      if ((rc = run_pass(ctx, ps, (hipStream_t)stream))) return rc;
+    }
+    return TSD_OK;
+  }
   return run_pass(ctx, ps, (hipStream_t)stream);
 }
 
