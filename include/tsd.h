@@ -205,9 +205,22 @@ int tsd_get_state(tsd_ctx* ctx, int32_t* len_dev, int32_t* committed_dev, float*
 /* Aggregate counters since prefill / reset.  Synchronises `stream`. */
 int tsd_get_stats(tsd_ctx* ctx, tsd_stats* out_host, void* stream);
 
+/* The same five counters per series: out_dev int64 [B,5] in the field order of tsd_stats.  A
+ * series' accepted / tested is one [0,1]-valued, independent per-history term of the plug-in
+ * acceptance estimate (Proposition "Unbiased plug-in estimator", Theorem "Hoeffding
+ * concentration"). */
+int tsd_get_series_stats(tsd_ctx* ctx, int64_t* out_dev, void* stream);
+
 /* alpha in (0, 1]: every tested position is accepted with this constant probability instead of
  * min(1, e^ell) (block-length law under an i.i.d. rate, Eq. 7).  alpha < 0 restores the rule. */
 int tsd_set_accept_override(tsd_ctx* ctx, float alpha);
+
+/* Change the number of proposals per round to K in 1..(K given to tsd_create), between rounds
+ * (Proposition "Marginal-gain condition for K": the block size is chosen from the measured
+ * acceptance and cost ratios, which are known only after some rounds have run).  All state a
+ * round depends on (cache lengths, pending token, counters) is independent of K; the round
+ * tensors are re-laid out for the new K, so tensors injected with tsd_set_round_io are dropped. */
+int tsd_set_block_size(tsd_ctx* ctx, int32_t K);
 
 /* Change the acceptance temperatures (temperature sweeps without re-creating the handle). */
 int tsd_set_sigma(tsd_ctx* ctx, float sigma_p, float sigma_q);

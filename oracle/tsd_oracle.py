@@ -344,3 +344,20 @@ def predicted_speedup(alpha, K, c, v):
 def next_position_pays(alpha, K, c, v):
     """S(K+1) >= S(K)  iff  alpha^(K+1) (cK + v) >= c E[L_K]."""
     return alpha ** (K + 1) * (c * K + v) >= c * expected_block_length(alpha, K)
+
+
+def choose_block_size(alpha, c, v, k_max):
+    """Proposition "Marginal-gain condition for K": S(K+1) >= S(K) iff alpha^(K+1) (cK + v) >= c E[L_K].
+    The left side minus the right side falls strictly with K, so S is unimodal; returned is the
+    first K at which one more position no longer pays, i.e. the maximiser of S on 1..k_max.  (The
+    paper words K* as the largest K for which the condition still holds, which is one less.)"""
+    K = 1
+    while K < k_max and next_position_pays(alpha, K, c, v):
+        K += 1
+    return K
+
+
+def hoeffding_halfwidth(n, delta):
+    """Theorem "Hoeffding concentration": with n i.i.d. per-history terms in [0, 1],
+    P(|estimate - mean| >= eps) <= 2 exp(-2 n eps^2); the eps at which that bound equals delta."""
+    return math.sqrt(math.log(2.0 / delta) / (2.0 * n))

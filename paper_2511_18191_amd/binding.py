@@ -61,6 +61,8 @@ SYMBOLS = {
     "tsd_bench_gemm": ([C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_bench_copy": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
     "tsd_set_accept_override": ([C.c_void_p, C.c_float], C.c_int),
+    "tsd_get_series_stats": ([C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_set_block_size": ([C.c_void_p, C.c_int32], C.c_int),
     "tsd_set_sigma": ([C.c_void_p, C.c_float, C.c_float], C.c_int),
 }
 
@@ -247,6 +249,10 @@ class Session:
         self._inj = [self._to_dev(t, torch.float32) for t in (X, mu_q, mu_p)]
         _check(lib().tsd_set_round_io(self.h, *[t.data_ptr() for t in self._inj], self._stream()), self.h)
 
+    def set_block_size(self, K):
+        _check(lib().tsd_set_block_size(self.h, K), self.h)
+        self.cfg.K = K
+
     def get_state(self):
         torch, B, P = self.torch, self.B, self.cfg.patch
         ln, cm, pend = self._new(B, dtype=torch.int32), self._new(B, dtype=torch.int32), self._new(B, P)
@@ -258,6 +264,13 @@ class Session:
         s = TsdStats()
         _check(lib().tsd_get_stats(self.h, C.byref(s), self._stream()), self.h)
         return {k: getattr(s, k) for k, _ in TsdStats._fields_}
+
+    def get_series_stats(self):
+        """int64 [B, 5]: rounds, tested, accepted, committed, near_ties of every series."""
+        out = self._new(self.B, 5, dtype=self.torch.int64)
+        _check(lib().tsd_get_series_stats(self.h, out.data_ptr(), self._stream()), self.h)
+        self.sync()
+        return out
 
     def profile_begin(self, kernel_class):
         _check(lib().tsd_profile_begin(self.h, kernel_class), self.h)

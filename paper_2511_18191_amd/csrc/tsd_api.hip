@@ -74,6 +74,7 @@ struct tsd_ctx {
   // captured launch sequences of tsd_round / tsd_target_step (rebuilt when anything they bake in changes)
   hipGraphExec_t graph_round = nullptr, graph_step = nullptr;
   // measurement tap: event pairs around every launch of one kernel family
+  int K_max = 0;  // K the handle was created with: buffers, pages and the skinny decision are sized for it
   int prof_class = -1;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
   size_t prof_used = 0;
@@ -259,6 +260,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
     ctx->abuf = at(o_a);
     ctx->hbuf = at(o_h);
     ctx->rows_max = (int)rows;
+    ctx->K_max = K;
     ctx->skinny = (c.dtype == TSD_BF16 && !(c.flags & TSD_FLAG_NO_SKINNY) && (size_t)B * (K + 1) <= 32) ? 1 : 0;
     ctx->count_out = (int*)at(o_cnt);
     ctx->act_list = (int*)at(o_alist);
@@ -758,13 +760,13 @@ int tsd_prefill(tsd_ctx* ctx, const float* series_dev, int32_t B, int32_t n_ctx_
   if (B < 1 || n_ctx_patches < 2 || horizon_steps < 1) return fail(ctx, TSD_E_INVALID_ARG, "need B >= 1, n_ctx_patches >= 2, horizon_steps >= 1");
   if (B > c.max_batch) return fail(ctx, TSD_E_OUT_OF_RANGE, "B exceeds max_batch");
   const int P = c.patch, N = n_ctx_patches, T = (horizon_steps + P - 1) / P;
-  if ((long)N + T + c.K > c.max_tokens) return fail(ctx, TSD_E_OUT_OF_RANGE, "n_ctx_patches + ceil(horizon/P) + K exceeds max_tokens");
+  if ((long)N + T + ctx->K_max > c.max_tokens) return fail(ctx, TSD_E_OUT_OF_RANGE, "n_ctx_patches + ceil(horizon/P) + K exceeds max_tokens");
   hipStream_t st = (hipStream_t)stream;
   ctx->prefilled = false;
   ctx->n_act = -1;
   drop_graphs(ctx);  // batch size, context length and horizon are baked into the captured launches
   // page table: every series reserves the pages its whole forecast can touch
-  const int need = (N + T + c.K + c.page_tokens - 1) / c.page_tokens;
+  const int need = (N + T + ctx->K_max + c.page_tokens - 1) / c.page_tokens;
   std::vector<int> perm;
   if (c.flags & TSD_FLAG_SCRAMBLE_PAGES) {
     perm.resize(ctx->n_pages);
@@ -1055,6 +1057,15 @@ int tsd_get_stats(tsd_ctx* ctx, tsd_stats* out_host, void* stream) {
   return TSD_OK;
 }
 
+int tsd_get_series_stats(tsd_ctx* ctx, int64_t* out_dev, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  if (!out_dev) return fail(ctx, TSD_E_INVALID_ARG, "out_dev is NULL");
+  static_assert(sizeof(long long) == sizeof(int64_t), "counter width");
+  HIP_TRY(ctx, hipMemcpyAsync(out_dev, ctx->stat, (size_t)ctx->B * 5 * sizeof(int64_t), hipMemcpyDeviceToDevice, (hipStream_t)stream));
+  return TSD_OK;
+}
+
 int tsd_profile_begin(tsd_ctx* ctx, int kernel_class) {
   if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
   if (kernel_class < -1 || kernel_class >= TSD_K_COUNT) return fail(ctx, TSD_E_INVALID_ARG, "kernel_class must be a TSD_K_* value or -1");
@@ -1121,6 +1132,17 @@ int tsd_set_accept_override(tsd_ctx* ctx, float alpha) {
   if (alpha > 1.f || alpha == 0.f || std::isnan(alpha)) return fail(ctx, TSD_E_INVALID_ARG, "alpha must be in (0, 1], or negative to disable");
   ctx->alpha_override = alpha < 0.f ? -1.f : alpha;
   drop_graphs(ctx);
+  return TSD_OK;
+}
+
+int tsd_set_block_size(tsd_ctx* ctx, int32_t K) {
+  if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
+  if (K < 1 || K > ctx->K_max) return fail(ctx, TSD_E_OUT_OF_RANGE, "K must be in 1..K of tsd_create");
+  if (K != ctx->cfg.K) {
+    ctx->cfg.K = K;
+    ctx->injected = false;  // injected round tensors were laid out for the old K
+    drop_graphs(ctx);
+  }
   return TSD_OK;
 }
 

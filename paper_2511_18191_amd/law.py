@@ -1,4 +1,4 @@
-"""Host arithmetic of the paper's throughput law, used for reporting next to measured numbers.
+"""Host arithmetic of the paper's throughput law: reporting next to measured numbers, and the planner.
 
 Eq. 7: under a per-position acceptance rate alpha the committed patches per round follow a capped
 geometric law with mean E[L] = (1 - alpha^(K+1)) / (1 - alpha).  Eq. 8: with c the draft-to-target
@@ -28,3 +28,10 @@ def best_block_size(alpha, c, v, k_max=16):
     while K < k_max and one_more_position_pays(alpha, K, c, v):
         K += 1
     return K
+
+
+def acceptance_confidence(n_histories, delta=0.05):
+    """Half-width eps of the two-sided interval around the plug-in acceptance estimate from
+    n independent histories (Theorem "Hoeffding concentration"): 2 exp(-2 n eps^2) = delta."""
+    import math
+    return math.sqrt(math.log(2.0 / delta) / (2.0 * n_histories))

@@ -25,3 +25,12 @@ def test_best_block_size_is_where_the_marginal_gain_stops():
         assert all(S[k] >= S[k - 1] - 1e-15 for k in range(1, K))         # every step up to K paid
         if K < 16:
             assert S[K] < S[K - 1]                                           # the next one does not
+
+
+def test_planner_arithmetic_agrees_with_oracle():
+    rng = np.random.default_rng(2)
+    for _ in range(300):
+        a, c, v = rng.uniform(0.05, 0.995), rng.uniform(0.005, 0.8), rng.uniform(0.8, 5.0)
+        assert law.best_block_size(a, c, v, k_max=16) == orc.choose_block_size(a, c, v, 16)
+    for n, d in ((10, 0.05), (256, 0.01)):
+        assert math.isclose(law.acceptance_confidence(n, d), orc.hoeffding_halfwidth(n, d), rel_tol=1e-12)

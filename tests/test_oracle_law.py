@@ -42,3 +42,30 @@ def test_consistent_with_paper_block_size_sweep():
     assert np.abs(np.polyval([c, v], K) - cost).max() < 0.06
     for r in rows:
         assert abs(orc.predicted_speedup(r[1], int(r[0]), c, v) - r[2]) < 0.12
+
+
+def test_choose_block_size_is_the_argmax_of_eq8():
+    # the marginal condition's slack falls strictly with K, so the first K at which it fails maximises S
+    rng = np.random.default_rng(3)
+    for _ in range(400):
+        a, c, v = rng.uniform(0.05, 0.995), rng.uniform(0.005, 0.8), rng.uniform(0.8, 5.0)
+        S = [orc.predicted_speedup(a, K, c, v) for K in range(1, 33)]
+        assert orc.choose_block_size(a, c, v, 32) == int(np.argmax(S)) + 1
+        slack = [a ** (K + 1) * (c * K + v) - c * orc.expected_block_length(a, K) for K in range(1, 33)]
+        assert all(x > y - 1e-15 for x, y in zip(slack, slack[1:])) and slack[0] > slack[4]
+    assert orc.choose_block_size(0.9, 0.1, 1.0, 3) == 3            # capped
+    assert orc.choose_block_size(0.1, 0.9, 1.0, 16) == 1            # nothing pays
+
+
+def test_hoeffding_halfwidth_bound_and_coverage():
+    for n, delta in ((64, 0.05), (256, 0.01), (1024, 0.1)):
+        eps = orc.hoeffding_halfwidth(n, delta)
+        assert math.isclose(2 * math.exp(-2 * n * eps * eps), delta, rel_tol=1e-12)
+    # Monte Carlo: per-history terms in [0, 1] (accepted fraction of a few Bernoulli positions)
+    rng = np.random.default_rng(4)
+    n, delta, p = 128, 0.05, 0.7
+    eps = orc.hoeffding_halfwidth(n, delta)
+    terms = rng.binomial(4, p, size=(20000, n)) / 4.0
+    miss = np.mean(np.abs(terms.mean(axis=1) - p) >= eps)
+    assert miss <= delta                                             # the bound holds (it is loose: miss ~ 0)
+    assert eps < 0.13 and orc.hoeffding_halfwidth(4 * n, delta) == eps / 2
