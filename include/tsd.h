@@ -222,8 +222,18 @@ int tsd_set_accept_override(tsd_ctx* ctx, float alpha);
  * tensors are re-laid out for the new K, so tensors injected with tsd_set_round_io are dropped. */
 int tsd_set_block_size(tsd_ctx* ctx, int32_t K);
 
-/* Change the acceptance temperatures (temperature sweeps without re-creating the handle). */
+/* Change the acceptance temperatures (temperature sweeps without re-creating the handle).
+ * Returns to the isotropic surrogate if tsd_set_sigma_diag was in effect. */
 int tsd_set_sigma(tsd_ctx* ctx, float sigma_p, float sigma_q);
+
+/* Diagonal-covariance surrogate (Remark "General covariances"): sigma_p_dev, sigma_q_dev are
+ * float32 [P] per-dimension scales on the device (copied; both required, all positive).  The
+ * statistic becomes
+ *   ell_i = -(1/2P) sum_e (x - mu_p)_e^2 / s_p[e]^2 + (1/2P) sum_e (x - mu_q)_e^2 / s_q[e]^2
+ *           + (1/2P) sum_e log(s_q[e]^2 / s_p[e]^2),
+ * and sampled proposals draw x_i = mu_q^(i) + s_q * eps element-wise.  Synchronises `stream`
+ * (the scales are validated and the inverse variances and the log-det term formed on the host). */
+int tsd_set_sigma_diag(tsd_ctx* ctx, const float* sigma_p_dev, const float* sigma_q_dev, void* stream);
 
 /* Measurement tap (not part of the method): time every launch of one kernel family with HIP
  * events recorded on the launching stream.  kernel_class: TSD_K_*; while a class is selected,

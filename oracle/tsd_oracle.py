@@ -236,6 +236,20 @@ def log_ratio(x, mu_p, mu_q, sigma_p, sigma_q):
             + 0.5 * math.log(sigma_q ** 2 / sigma_p ** 2))
 
 
+def log_ratio_diag(x, mu_p, mu_q, s_p, s_q):
+    """Remark "General covariances", diagonal case: Eq. 5 with the scaled Euclidean energies
+    replaced by scaled Mahalanobis energies (1/d) (x - mu)^T Sigma^-1 (x - mu) and the normalisation
+    term by (1/2d) log(|Sigma_q| / |Sigma_p|), Sigma = diag(s^2).  s_p, s_q: per-dimension scales."""
+    x, mu_p, mu_q = (np.asarray(a, dtype=np.float64) for a in (x, mu_p, mu_q))
+    s_p = np.broadcast_to(np.asarray(s_p, dtype=np.float64), x.shape)
+    s_q = np.broadcast_to(np.asarray(s_q, dtype=np.float64), x.shape)
+    d = x.size
+    maha_p = float(np.sum(((x - mu_p) / s_p) ** 2)) / d
+    maha_q = float(np.sum(((x - mu_q) / s_q) ** 2)) / d
+    logdet = float(np.sum(np.log(s_q ** 2)) - np.sum(np.log(s_p ** 2)))
+    return -0.5 * maha_p + 0.5 * maha_q + logdet / (2.0 * d)
+
+
 def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True, alpha_override=None,
                eps_fn=None, sample_proposals=False, fallback_r=0.0):
     """One speculative round for one series.
@@ -249,6 +263,8 @@ def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True
     proposes x_i = mu_q^(i) + sigma_q eps (and conditions its next step on that draw); with
     fallback_r = r > 0 the corrected / bonus patch is mu_p^(n+1) + r eps.  The defaults are the
     deployed mean-propagating scheme (x_i = mu_q^(i), t = mu_p^(n+1)).
+    sigma_p / sigma_q may be length-P vectors: the diagonal-covariance surrogate (Remark "General
+    covariances"); scalars are the isotropic surrogate of Eq. 4.
     Returns a dict with X, mu_q [K, P], mu_p [K+1, P], ell, logu [K] (nan where untested),
     n (accepted count) and commits [n + 1, P].
     """
@@ -257,6 +273,7 @@ def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True
     X = np.empty((K, P))
     mu_q = np.empty((K, P))
     cur = hist
+    sigma_q = np.asarray(sigma_q, dtype=np.float64) if np.ndim(sigma_q) else sigma_q
     for i in range(K):                               # K sequential draft passes
         mu_q[i] = forward(Wd, md, cur)[-1]
         X[i] = mu_q[i] + sigma_q * eps_fn(STREAM_PROPOSAL, i + 1) if sample_proposals else mu_q[i]
@@ -270,7 +287,10 @@ def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True
     logu = np.full(K, np.nan)
     n = 0
     for i in range(K):                               # left to right, stop at the first rejection
-        ell[i] = log_ratio(X[i], mu_p[i], mu_q[i], sigma_p, sigma_q)
+        if np.ndim(sigma_p) or np.ndim(sigma_q):
+            ell[i] = log_ratio_diag(X[i], mu_p[i], mu_q[i], sigma_p, sigma_q)
+        else:
+            ell[i] = log_ratio(X[i], mu_p[i], mu_q[i], sigma_p, sigma_q)
         logu[i] = math.log(u_fn(i + 1))
         thresh = math.log(alpha_override) if alpha_override is not None else min(0.0, ell[i])
         if logu[i] <= thresh:

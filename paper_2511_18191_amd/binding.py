@@ -63,6 +63,7 @@ SYMBOLS = {
     "tsd_set_accept_override": ([C.c_void_p, C.c_float], C.c_int),
     "tsd_get_series_stats": ([C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_set_block_size": ([C.c_void_p, C.c_int32], C.c_int),
+    "tsd_set_sigma_diag": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_set_sigma": ([C.c_void_p, C.c_float, C.c_float], C.c_int),
 }
 
@@ -285,6 +286,12 @@ class Session:
 
     def set_sigma(self, sigma_p, sigma_q=None):
         _check(lib().tsd_set_sigma(self.h, sigma_p, sigma_p if sigma_q is None else sigma_q), self.h)
+
+    def set_sigma_diag(self, sigma_p_vec, sigma_q_vec):
+        """Per-dimension scales [P] of the diagonal-covariance surrogate (arrays or tensors)."""
+        sp, sq = self._to_dev(sigma_p_vec, self.torch.float32), self._to_dev(sigma_q_vec, self.torch.float32)
+        assert sp.numel() == self.cfg.patch and sq.numel() == self.cfg.patch
+        _check(lib().tsd_set_sigma_diag(self.h, sp.data_ptr(), sq.data_ptr(), self._stream()), self.h)
 
 
 def session_for(inputs, flags=0, page_tokens=16, max_batch=None, sigma_q=None, fallback_r=0.0):

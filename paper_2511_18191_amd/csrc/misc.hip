@@ -158,7 +158,7 @@ __global__ __launch_bounds__(64) void sample_kernel(const SampleP p) {
   const unsigned r = (unsigned)p.round[b];
   const long off = ((long)b * p.K + (p.i - 1)) * p.P;
   for (int e = threadIdx.x; e < p.P; e += 64)
-    p.X[off + e] = p.mu_q[off + e] + p.sigma_q * normal_draw((unsigned)b, r, (unsigned)p.i, kStreamProposal, e, p.key0, p.key1);
+    p.X[off + e] = p.mu_q[off + e] + (p.sigma_q_vec ? p.sigma_q_vec[e] : p.sigma_q) * normal_draw((unsigned)b, r, (unsigned)p.i, kStreamProposal, e, p.key0, p.key1);
 }
 hipError_t launch_sample(const SampleP& p, hipStream_t st) {
   if (p.n <= 0) return hipSuccess;
@@ -193,8 +193,13 @@ __global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
     for (int e = lane; e < P; e += 64) {
       float x = X[i * P + e];
       float dp = x - MP[i * P + e], dq = x - MQ[i * P + e];
-      ep = fmaf(dp, dp, ep);
-      eq = fmaf(dq, dq, eq);
+      if (p.inv2sp2_vec) {  // Mahalanobis energies of the diagonal surrogate, already halved
+        ep = fmaf(dp * dp, p.inv2sp2_vec[e], ep);
+        eq = fmaf(dq * dq, p.inv2sq2_vec[e], eq);
+      } else {
+        ep = fmaf(dp, dp, ep);
+        eq = fmaf(dq, dq, eq);
+      }
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) {
@@ -210,7 +215,10 @@ __global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
   float ell = NAN, logu = NAN, thr = 0.f;
   if (lane < K) {
     // Eq. 5 with per-dimension energies ||.||^2 / P
-    ell = p.temper * (-(my_ep / (float)P) * p.inv2sp2 + (my_eq / (float)P) * p.inv2sq2 + p.logdet);
+    if (p.inv2sp2_vec)
+      ell = p.temper * (-(my_ep / (float)P) + (my_eq / (float)P) + p.logdet_dev[0]);
+    else
+      ell = p.temper * (-(my_ep / (float)P) * p.inv2sp2 + (my_eq / (float)P) * p.inv2sq2 + p.logdet);
     unsigned w = philox_word0((unsigned)b, (unsigned)r, (unsigned)(lane + 1), 0u, p.key0, p.key1);
     float u = word_uniform(w);
     logu = logf(u);

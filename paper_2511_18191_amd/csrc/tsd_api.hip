@@ -49,6 +49,9 @@ struct tsd_ctx {
   float *mean, *sdev, *pending, *prev, *forecast, *znorm;
   long long* stat;
   float *X, *mu_q, *mu_p, *ell, *logu;
+  float* diag;  // [3P + 1]: 1/(2 s_p^2), 1/(2 s_q^2), s_q, then the log-det scalar (diagonal surrogate)
+  bool diag_on = false;
+  float diag_min_sp = 0.f;
   float* x;   // residual stream, fp32
   char* xb;   // its bf16 shadow (GEMM A operand in bf16 mode)
   char *qbuf, *abuf, *hbuf;
@@ -214,6 +217,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
   size_t o_stat = cv.take((size_t)B * 5 * 8);
   size_t o_X = cv.take((size_t)B * K * P * 4), o_mq = cv.take((size_t)B * K * P * 4), o_mp = cv.take((size_t)B * (K + 1) * P * 4);
   size_t o_ell = cv.take((size_t)B * K * 4), o_logu = cv.take((size_t)B * K * 4);
+  size_t o_diag = cv.take((size_t)(3 * P + 1) * 4);
   const size_t Dm = std::max(c.target.d_model, c.draft.d_model), Fm = std::max(c.target.d_ff, c.draft.d_ff);
   const size_t rows = std::max((size_t)B * (K + 1), (size_t)c.max_tokens);
   size_t o_xb = cv.take(rows * Dm * es);
@@ -254,6 +258,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
     ctx->mu_p = (float*)at(o_mp);
     ctx->ell = (float*)at(o_ell);
     ctx->logu = (float*)at(o_logu);
+    ctx->diag = (float*)at(o_diag);
     ctx->x = (float*)at(o_x);
     ctx->xb = at(o_xb);
     ctx->qbuf = at(o_q);
@@ -584,6 +589,11 @@ int accept_commit_impl(tsd_ctx* ctx, const int32_t* forced, int K, hipStream_t s
   a.temper = (c.flags & TSD_FLAG_NO_TEMPERING) ? (float)c.patch : 1.0f;
   a.log_alpha_override = ctx->alpha_override > 0.f ? std::log(ctx->alpha_override) : 1.0f;
   a.fallback_r = K > 0 ? c.fallback_r : 0.f;  // the target-only step commits the target mean
+  if (ctx->diag_on) {
+    a.inv2sp2_vec = ctx->diag;
+    a.inv2sq2_vec = ctx->diag + c.patch;
+    a.logdet_dev = ctx->diag + 3 * c.patch;
+  }
   a.key0 = (unsigned)(c.seed & 0xFFFFFFFFull);
   a.key1 = (unsigned)(c.seed >> 32);
   HIP_TRY(ctx, timed_launch(ctx, TSD_K_ACCEPT, 4.0 * ctx->B * c.patch * (2.0 * K + 2), st, [&] { return launch_accept(a, st); }));
@@ -864,6 +874,7 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
     sp.P = P;
     sp.i = i;
     sp.sigma_q = c.sigma_q;
+    sp.sigma_q_vec = ctx->diag_on ? ctx->diag + 2 * P : nullptr;
     sp.key0 = (unsigned)(c.seed & 0xFFFFFFFFull);
     sp.key1 = (unsigned)(c.seed >> 32);
     HIP_TRY(ctx, launch_sample(sp, st));
@@ -1150,8 +1161,38 @@ int tsd_set_sigma(tsd_ctx* ctx, float sigma_p, float sigma_q) {
   if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
   if (!(sigma_p > 0.f) || !(sigma_q > 0.f) || !std::isfinite(sigma_p) || !std::isfinite(sigma_q))
     return fail(ctx, TSD_E_INVALID_ARG, "sigma_p and sigma_q must be positive and finite");
+  if (ctx->cfg.fallback_r > sigma_p) return fail(ctx, TSD_E_INVALID_ARG, "sigma_p must not fall below fallback_r");
   ctx->cfg.sigma_p = sigma_p;
   ctx->cfg.sigma_q = sigma_q;
+  ctx->diag_on = false;
+  drop_graphs(ctx);
+  return TSD_OK;
+}
+
+int tsd_set_sigma_diag(tsd_ctx* ctx, const float* sigma_p_dev, const float* sigma_q_dev, void* stream) {
+  if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
+  if (!sigma_p_dev || !sigma_q_dev) return fail(ctx, TSD_E_INVALID_ARG, "sigma_p_dev and sigma_q_dev are both required");
+  const int P = ctx->cfg.patch;
+  hipStream_t st = (hipStream_t)stream;
+  std::vector<float> sp(P), sq(P), pack(3 * (size_t)P + 1);
+  HIP_TRY(ctx, hipMemcpyAsync(sp.data(), sigma_p_dev, (size_t)P * 4, hipMemcpyDeviceToHost, st));
+  HIP_TRY(ctx, hipMemcpyAsync(sq.data(), sigma_q_dev, (size_t)P * 4, hipMemcpyDeviceToHost, st));
+  HIP_TRY(ctx, hipStreamSynchronize(st));
+  double logdet = 0.0;
+  float min_sp = INFINITY;
+  for (int e = 0; e < P; ++e) {
+    if (!(sp[e] > 0.f) || !(sq[e] > 0.f) || !std::isfinite(sp[e]) || !std::isfinite(sq[e]))
+      return fail(ctx, TSD_E_INVALID_ARG, "every per-dimension scale must be positive and finite");
+    pack[e] = (float)(1.0 / (2.0 * (double)sp[e] * sp[e]));
+    pack[P + e] = (float)(1.0 / (2.0 * (double)sq[e] * sq[e]));
+    pack[2 * P + e] = sq[e];
+    logdet += std::log((double)sq[e] * sq[e]) - std::log((double)sp[e] * sp[e]);
+    min_sp = std::min(min_sp, sp[e]);
+  }
+  if (ctx->cfg.fallback_r > min_sp) return fail(ctx, TSD_E_INVALID_ARG, "no target scale may fall below fallback_r");
+  pack[3 * (size_t)P] = (float)(logdet / (2.0 * P));
+  HIP_TRY(ctx, hipMemcpy(ctx->diag, pack.data(), pack.size() * 4, hipMemcpyHostToDevice));
+  ctx->diag_on = true;
   drop_graphs(ctx);
   return TSD_OK;
 }

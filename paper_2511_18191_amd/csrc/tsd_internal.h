@@ -151,6 +151,9 @@ struct AcceptP {
   float inv2sp2, inv2sq2, logdet, temper;  // temper = 1 (Eq. 5) or P (ablation without 1/d)
   float log_alpha_override;                // > 0 means "no override"
   float fallback_r;                        // noise scale of the corrected / bonus patch (0: target mean)
+  // diagonal-covariance surrogate (NULL: isotropic): 1 / (2 s_p[e]^2), 1 / (2 s_q[e]^2) per dimension and
+  // the scalar (1 / 2P) sum_e log(s_q[e]^2 / s_p[e]^2)
+  const float *inv2sp2_vec, *inv2sq2_vec, *logdet_dev;
   unsigned key0, key1;
 };
 hipError_t launch_accept(const AcceptP& p, hipStream_t st);
@@ -162,6 +165,7 @@ struct SampleP {  // X[b, i-1] = mu_q[b, i-1] + sigma_q * eps(b, round[b], i)
   const int* round;
   int n, K, P, i;
   float sigma_q;
+  const float* sigma_q_vec;  // per-dimension scales (NULL: sigma_q)
   unsigned key0, key1;
 };
 hipError_t launch_sample(const SampleP& p, hipStream_t st);

@@ -39,7 +39,7 @@ class Case(synth.Inputs):
 
 
 def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=True, tol=None, subset=None,
-             sample_proposals=False, fallback_r=0.0):
+             sample_proposals=False, fallback_r=0.0, sigma_p=None):
     """Run GPU and oracle round by round on the same histories.  The GPU evaluates its own
     acceptance test (recorded) but commits the oracle's accepted length, so the two histories
     stay aligned and every round's tensors can be compared.  Returns a report dict.
@@ -48,7 +48,8 @@ def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=Tru
     import torch
     c = case.cfg
     B, K, P, T = c.batch, c.K, c.patch, c.T
-    sq = sigma_q or c.sigma
+    sq = c.sigma if sigma_q is None else sigma_q      # scalars, or length-P vectors (diagonal surrogate)
+    sp = c.sigma if sigma_p is None else sigma_p
     sess.prefill(case.context, c.n_ctx, c.horizon)
     follow = list(range(B)) if subset is None else list(subset)
     hist = {b: case.oracle_hist(b)[0] for b in follow}
@@ -67,7 +68,7 @@ def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=Tru
         for b in follow:
             if Y[b].shape[0] >= T:
                 continue
-            recs[b] = orc.spec_round(case.Wt, c.target, case.Wd, c.draft, np.vstack([hist[b], Y[b]]), K, c.sigma, sq,
+            recs[b] = orc.spec_round(case.Wt, c.target, case.Wd, c.draft, np.vstack([hist[b], Y[b]]), K, sp, sq,
                                      (lambda i, b=b: orc.uniform(case.seed, b, rnd[b], i)),
                                      eps_fn=(lambda stream, i, b=b: orc.normal(case.seed, b, rnd[b], i, stream, P)),
                                      sample_proposals=sample_proposals, fallback_r=fallback_r)

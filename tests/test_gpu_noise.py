@@ -113,3 +113,64 @@ def test_sampled_acceptance_rate_follows_the_overlap_law_on_gpu():
         tested += B
     want = 2 * stats.norm.cdf(-Delta / 2)
     assert abs(acc / tested - want) < 4 * math.sqrt(want * (1 - want) / tested), (acc / tested, want)
+
+
+def test_diagonal_surrogate_statistic_on_injected_tensors():
+    # Remark "General covariances" on the kernel itself: per-dimension scales, proposals away from the
+    # draft mean, all K statistics against the oracle's float64 Mahalanobis form
+    case = Case("cfg1", B=64, K=4, sigma=0.5, horizon=16 * 40)
+    c = case.cfg
+    P, B, K = c.patch, c.batch, c.K
+    rng = np.random.default_rng(1)
+    sp, sq = rng.uniform(0.3, 1.2, P), rng.uniform(0.3, 1.2, P)
+    sess = case.session()
+    sess.prefill(case.context, c.n_ctx, c.horizon)
+    sess.set_sigma_diag(sp, sq)
+    mu_q = rng.standard_normal((B, K, P)).astype(np.float32)
+    X = (mu_q + 0.4 * rng.standard_normal((B, K, P))).astype(np.float32)
+    mu_p = (np.concatenate([mu_q, mu_q[:, :1]], axis=1) + 0.3 * rng.standard_normal((B, K + 1, P))).astype(np.float32)
+    sess.set_round_io(torch.from_numpy(X), torch.from_numpy(mu_q), torch.from_numpy(mu_p))
+    sess.accept_commit()
+    io = {k: v.cpu().numpy() for k, v in sess.get_round_io().items()}
+    mism = near = 0
+    for b in range(B):
+        n = 0
+        alive = True
+        for i in range(K):
+            ell = orc.log_ratio_diag(X[b, i], mu_p[b, i], mu_q[b, i], sp.astype(np.float32), sq.astype(np.float32))
+            logu = math.log(orc.uniform(case.seed, b, 0, i + 1))
+            if alive:
+                assert abs(io["ell"][b, i] - ell) < 2e-5 * max(1.0, abs(ell)), (b, i, io["ell"][b, i], ell)
+                near += abs(min(0.0, ell) - logu) < 1e-4
+                if logu <= min(0.0, ell):
+                    n += 1
+                else:
+                    alive = False
+        mism += int(io["n_acc"][b]) != n
+    assert mism <= near
+    # back to the isotropic surrogate
+    sess.set_sigma(0.5)
+    sess.set_round_io(torch.from_numpy(X), torch.from_numpy(mu_q), torch.from_numpy(mu_p))
+    sess.accept_commit()
+    ell1 = sess.get_round_io()["ell"].cpu().numpy()
+    assert abs(ell1[0, 0] - orc.log_ratio(X[0, 0], mu_p[0, 0], mu_q[0, 0], 0.5, 0.5)) < 2e-5
+    with pytest.raises(tsd.TsdError):
+        sess.set_sigma_diag(np.zeros(P), sq)
+
+
+@pytest.mark.parametrize("name", ["mini2_fp32", "mini2"])
+def test_round_lockstep_with_diagonal_scales_and_sampling(name):
+    case = Case(name, sigma=0.5)
+    c = case.cfg
+    P = c.patch
+    sp = np.linspace(0.35, 0.8, P).astype(np.float32).astype(np.float64)
+    sq = (0.5 + 0.25 * np.cos(np.arange(P))).astype(np.float32).astype(np.float64)
+    sess = case.session(flags=tsd.TSD_FLAG_SAMPLE_PROPOSALS, fallback_r=0.2)
+    sess.set_sigma_diag(sp, sq)
+    rep = lockstep(case, sess, sample_proposals=True, fallback_r=0.2, sigma_p=sp, sigma_q=sq)
+    print(f"\n{name} diag: rel X {rep['max_rel_X']:.2e} mu_p {rep['max_rel_mu_p']:.2e} mismatched {rep['mismatched']} "
+          f"near-ties {rep['near_ties']} accept {rep['accepted']}/{rep['tested']} d_ell {rep['max_abs_ell']:.1e}")
+    assert rep["max_rel_X"] <= TOL[c.dtype] and rep["max_rel_mu_p"] <= TOL[c.dtype]
+    if c.dtype == "fp32":
+        assert rep["mismatched"] <= rep["near_ties"] and rep["max_abs_ell"] < 2e-5
+    assert 0 < rep["accepted"] < rep["tested"]

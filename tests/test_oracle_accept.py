@@ -79,3 +79,34 @@ def test_fidelity_identity_monte_carlo():
         assert expect <= 2 * sigma ** 2 / math.e + 1e-15
         assert abs(err.mean() - expect) < 4 * delta2 * math.sqrt(0.25 / n)
     assert math.isclose(2 * sigma ** 2 * math.exp(-1), 2 * sigma ** 2 / math.e)
+
+
+def test_diagonal_covariance_statistic():
+    # Remark "General covariances": (1/d) log[p(x)/q(x)] for diagonal Gaussians, via scipy's log-pdf
+    rng = np.random.default_rng(3)
+    for d in (4, 32, 96):
+        x, mp, mq = rng.standard_normal((3, d))
+        sp, sq = rng.uniform(0.2, 1.5, d), rng.uniform(0.2, 1.5, d)
+        lp = stats.multivariate_normal(mean=mp, cov=np.diag(sp ** 2)).logpdf(x)
+        lq = stats.multivariate_normal(mean=mq, cov=np.diag(sq ** 2)).logpdf(x)
+        assert math.isclose(orc.log_ratio_diag(x, mp, mq, sp, sq), (lp - lq) / d, rel_tol=1e-10, abs_tol=1e-12)
+        # the isotropic case recovers Eq. 5, with scalars or constant vectors
+        assert math.isclose(orc.log_ratio_diag(x, mp, mq, 0.7, 0.4), orc.log_ratio(x, mp, mq, 0.7, 0.4), rel_tol=1e-12)
+        assert math.isclose(orc.log_ratio_diag(x, mp, mq, np.full(d, 0.7), np.full(d, 0.4)), orc.log_ratio(x, mp, mq, 0.7, 0.4),
+                            rel_tol=1e-12)
+    # a dimension the target is sure about (small s_p) dominates the energy: hand value
+    x, mp, mq = np.zeros(2), np.array([1.0, 1.0]), np.zeros(2)
+    sp, sq = np.array([0.5, 2.0]), np.array([1.0, 1.0])
+    want = (-0.5 * (1 / 0.25 + 1 / 4.0) + 0.0 + 0.5 * (0.0 - math.log(0.25) - math.log(4.0))) / 2
+    assert math.isclose(orc.log_ratio_diag(x, mp, mq, sp, sq), want, rel_tol=1e-12)
+
+
+def test_diagonal_log_determinant_is_load_bearing():
+    # a confident draft (s_q << s_p in every dimension) proposing its own mean: without the
+    # normalisation term the statistic is positive (always accept) however far the means are apart
+    d = 16
+    mq, mp = np.zeros(d), np.full(d, 0.3)
+    sp, sq = np.linspace(0.8, 1.2, d), np.linspace(0.05, 0.1, d)
+    with_term = orc.log_ratio_diag(mq, mp, mq, sp, sq)
+    logdet = (np.sum(np.log(sq ** 2)) - np.sum(np.log(sp ** 2))) / (2 * d)
+    assert with_term < -2.0 and with_term - logdet > -0.1

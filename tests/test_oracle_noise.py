@@ -191,3 +191,21 @@ def test_forecast_with_noise_uses_per_round_draws_and_keeps_length_law():
     # without noise the forecast differs (the knobs do something) and the default call is unchanged
     y0, _ = orc.forecast_spec(Wt, cfg.target, Wd, cfg.draft, series[1, : cfg.context], cfg.patch, cfg.horizon, cfg.K, 0.5, 0.5, seed=3, b=1)
     assert np.abs(y - y0).max() > 1e-3
+
+
+def test_round_with_diagonal_scales():
+    # per-dimension scales enter the statistic (Mahalanobis energies, log-det) and the proposal draw
+    cfg, Wt, Wd, h, _ = _setup()
+    P, K = cfg.patch, 3
+    sp, sq = np.linspace(0.3, 0.9, P), np.linspace(0.8, 0.2, P)
+    eps = lambda stream, i: orc.normal(6, 1, 0, i, stream, P)
+    rec = orc.spec_round(Wt, cfg.target, Wd, cfg.draft, h, K, sp, sq, lambda i: 1e-9, eps_fn=eps, sample_proposals=True)
+    assert rec["n"] == K                                    # u tiny: everything accepted, all K statistics recorded
+    for i in range(K):
+        np.testing.assert_allclose(rec["X"][i] - rec["mu_q"][i], sq * eps(orc.STREAM_PROPOSAL, i + 1), atol=1e-15)
+        assert rec["ell"][i] == orc.log_ratio_diag(rec["X"][i], rec["mu_p"][i], rec["mu_q"][i], sp, sq)
+    # constant vectors reproduce the isotropic round exactly
+    iso = orc.spec_round(Wt, cfg.target, Wd, cfg.draft, h, K, 0.4, 0.4, lambda i: 0.5)
+    vec = orc.spec_round(Wt, cfg.target, Wd, cfg.draft, h, K, np.full(P, 0.4), np.full(P, 0.4), lambda i: 0.5)
+    np.testing.assert_allclose(vec["ell"][: iso["n"] + 1], iso["ell"][: iso["n"] + 1], rtol=1e-12, atol=1e-15)
+    assert vec["n"] == iso["n"]
