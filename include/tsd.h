@@ -131,6 +131,18 @@ int tsd_load_weights(tsd_ctx* ctx, int which, const float* blob_dev, size_t n_fl
 int tsd_prefill(tsd_ctx* ctx, const float* series_dev, int32_t B, int32_t n_ctx_patches, int32_t horizon_steps,
                 void* stream);
 
+/* Continuous batching (the desynchronisation remedy the paper points to: a batch is as slow as
+ * its slowest series, so finished slots are handed to new series instead of idling).  Replaces the
+ * series in the `n` slots slots_host[0..n-1] (host array, distinct indices in 0..B-1) by new ones:
+ * series_dev is [n, n_ctx_patches * P] raw context steps with the n_ctx_patches and horizon of the
+ * running tsd_prefill.  Per slot: frozen statistics, normalisation, both models' KV entries of the
+ * context (the slot's pages are reused), cache length, committed count and the active flag start
+ * over; the slot's round counter keeps running, so the acceptance draws of successive series in
+ * one slot never repeat, and its statistics keep accumulating.  A slot that is still decoding
+ * loses its forecast.  Read finished forecasts (tsd_get_forecast) before refilling their slots,
+ * and call tsd_num_active afterwards.  Synchronises `stream` on entry. */
+int tsd_refill(tsd_ctx* ctx, const int32_t* slots_host, int32_t n, const float* series_dev, void* stream);
+
 /* Rewind to the state right after tsd_prefill (KV entries of the context are kept, everything
  * committed since is dropped, statistics zeroed).  Lets one prefill serve several decodes. */
 int tsd_reset_decode(tsd_ctx* ctx, void* stream);

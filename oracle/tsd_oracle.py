@@ -304,7 +304,7 @@ def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True
 
 def forecast_spec(Wt, mt, Wd, md, series_context, P, horizon, K, sigma_p, sigma_q, seed, b,
                   single_pass=True, alpha_override=None, u_fn=None, trace=None, sample_proposals=False,
-                  fallback_r=0.0):
+                  fallback_r=0.0, round0=0):
     """Speculative forecast of one series.  series_context: raw context steps (length N * P).
     Returns (forecast [horizon] in raw units, stats dict).  `trace`, if a list, receives each
     round's record."""
@@ -314,7 +314,7 @@ def forecast_spec(Wt, mt, Wd, md, series_context, P, horizon, K, sigma_p, sigma_
     T = -(-horizon // P)
     Y = np.empty((0, P))
     stats = dict(rounds=0, tested=0, accepted=0, committed=0, lengths=[])
-    r = 0
+    r = round0                                       # the draws' round counter (a reused batch slot keeps counting)
     while Y.shape[0] < T:
         draw = (lambda i, r=r: u_fn(b, r, i)) if u_fn is not None else (lambda i, r=r: uniform(seed, b, r, i))
         eps = lambda stream, i, r=r: normal(seed, b, r, i, stream, P)

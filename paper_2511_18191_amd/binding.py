@@ -44,6 +44,7 @@ SYMBOLS = {
     "tsd_destroy": ([C.c_void_p], C.c_int),
     "tsd_load_weights": ([C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
     "tsd_prefill": ([C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p], C.c_int),
+    "tsd_refill": ([C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_reset_decode": ([C.c_void_p, C.c_void_p], C.c_int),
     "tsd_draft_propose": ([C.c_void_p, C.c_void_p], C.c_int),
     "tsd_target_verify": ([C.c_void_p, C.c_void_p], C.c_int),
@@ -201,6 +202,14 @@ class Session:
         self.series = self._to_dev(series, self.torch.float32)
         self.B, self.H = self.series.shape[0], horizon_steps
         _check(lib().tsd_prefill(self.h, self.series.data_ptr(), self.B, n_ctx_patches, horizon_steps, self._stream()), self.h)
+
+    def refill(self, slots, series):
+        """New series (array [n, context steps]) into the listed slots of the running forecast."""
+        slots = [int(x) for x in slots]
+        arr = (C.c_int32 * len(slots))(*slots)
+        self._refill_series = self._to_dev(series, self.torch.float32)     # kept alive until the stream has used it
+        assert self._refill_series.shape[0] == len(slots)
+        _check(lib().tsd_refill(self.h, arr, len(slots), self._refill_series.data_ptr(), self._stream()), self.h)
 
     def reset_decode(self):
         _check(lib().tsd_reset_decode(self.h, self._stream()), self.h)

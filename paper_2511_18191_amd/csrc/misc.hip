@@ -58,8 +58,9 @@ __device__ __forceinline__ void init_state(const PrefillP& p, int b) {
 
 __global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillP p) {
   __shared__ double sh[4];
-  const int b = blockIdx.x, n = p.N * p.P;
-  const float* x = p.series + (long)b * n;
+  const int n = p.N * p.P;
+  const int b = p.slots ? p.slots[blockIdx.x] : (int)blockIdx.x;
+  const float* x = p.series + (long)blockIdx.x * n;
   double s = 0;
   for (int i = threadIdx.x; i < n; i += 256) s += x[i];
   const double mean = block_sum(s, sh) / n;
@@ -80,7 +81,13 @@ __global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillP p) {
   if (threadIdx.x == 0) {
     p.mean[b] = mf;
     p.sdev[b] = sf;
-    init_state(p, b);
+    if (p.keep_counters) {  // a new series in a used slot: its draws continue the slot's round counter
+      p.len[b] = p.N - 1;
+      p.committed[b] = 0;
+      p.active[b] = 1;
+    } else {
+      init_state(p, b);
+    }
   }
 }
 

@@ -77,6 +77,8 @@ struct tsd_ctx {
   // captured launch sequences of tsd_round / tsd_target_step (rebuilt when anything they bake in changes)
   hipGraphExec_t graph_round = nullptr, graph_step = nullptr;
   // measurement tap: event pairs around every launch of one kernel family
+  int* refill_list = nullptr;      // device copy of the slots of the last tsd_refill
+  std::vector<int> host_refill;
   int K_max = 0;  // K the handle was created with: buffers, pages and the skinny decision are sized for it
   int prof_class = -1;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
@@ -222,7 +224,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
   const size_t rows = std::max((size_t)B * (K + 1), (size_t)c.max_tokens);
   size_t o_xb = cv.take(rows * Dm * es);
   size_t o_x = cv.take(rows * Dm * 4), o_q = cv.take(rows * Dm * es), o_a = cv.take(rows * Dm * es), o_h = cv.take(rows * Fm * es);
-  size_t o_cnt = cv.take(256), o_so = cv.take(256), o_alist = cv.take((size_t)B * 4);
+  size_t o_cnt = cv.take(256), o_so = cv.take(256), o_alist = cv.take((size_t)B * 4), o_rlist = cv.take((size_t)B * 4);
   // routed FFN scratch: one slot per (token, chosen expert)
   const size_t topk = std::max(c.target.n_experts > 0 ? c.target.top_k : 0, c.draft.n_experts > 0 ? c.draft.top_k : 0);
   const size_t slots = rows * topk, nEmax = std::max(c.target.n_experts, c.draft.n_experts);
@@ -269,6 +271,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
     ctx->skinny = (c.dtype == TSD_BF16 && !(c.flags & TSD_FLAG_NO_SKINNY) && (size_t)B * (K + 1) <= 32) ? 1 : 0;
     ctx->count_out = (int*)at(o_cnt);
     ctx->act_list = (int*)at(o_alist);
+    ctx->refill_list = (int*)at(o_rlist);
     ctx->moe_ids = topk ? (int*)at(o_ids) : nullptr;
     ctx->moe_gates = (float*)at(o_gates);
     ctx->moe_src = (int*)at(o_src);
@@ -819,6 +822,49 @@ int tsd_prefill(tsd_ctx* ctx, const float* series_dev, int32_t B, int32_t n_ctx_
       if (rc) return rc;
     }
   ctx->prefilled = true;
+  return TSD_OK;
+}
+
+int tsd_refill(tsd_ctx* ctx, const int32_t* slots_host, int32_t n, const float* series_dev, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  if (!slots_host || !series_dev) return fail(ctx, TSD_E_INVALID_ARG, "slots_host and series_dev must not be NULL");
+  if (n < 1 || n > ctx->B) return fail(ctx, TSD_E_OUT_OF_RANGE, "n must be in 1..B of the running forecast");
+  std::vector<char> seen((size_t)ctx->B, 0);
+  for (int j = 0; j < n; ++j) {
+    const int b = slots_host[j];
+    if (b < 0 || b >= ctx->B) return fail(ctx, TSD_E_OUT_OF_RANGE, "slot index outside 0..B-1");
+    if (seen[(size_t)b]) return fail(ctx, TSD_E_INVALID_ARG, "a slot is listed twice");
+    seen[(size_t)b] = 1;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  const tsd_config& c = ctx->cfg;
+  const int N = ctx->N, P = c.patch;
+  HIP_TRY(ctx, hipStreamSynchronize(st));  // an earlier refill's list may still be in use
+  ctx->host_refill.assign(slots_host, slots_host + n);
+  HIP_TRY(ctx, hipMemcpyAsync(ctx->refill_list, ctx->host_refill.data(), (size_t)n * 4, hipMemcpyHostToDevice, st));
+  PrefillP pp{series_dev, ctx->znorm, ctx->mean, ctx->sdev, ctx->pending, ctx->prev, ctx->len, ctx->committed,
+              ctx->round, ctx->active, ctx->stat, n, N, P, ctx->refill_list, 1};
+  HIP_TRY(ctx, launch_prefill_stats(pp, st));
+  const int nq = N - 1;
+  const int chunk = std::max(1, ctx->rows_max / nq);
+  for (int which = 0; which < 2; ++which)
+    for (int s0 = 0; s0 < n; s0 += chunk) {
+      Pass ps;
+      std::memset(&ps, 0, sizeof(ps));
+      ps.which = which;
+      ps.B = std::min(chunk, n - s0);
+      ps.act = ctx->refill_list + s0;
+      ps.nq = nq;
+      ps.base_pos = nullptr;
+      ps.pos_off = 0;
+      ps.src0 = ctx->znorm;  // rows are gathered by slot
+      ps.stride0 = (long)N * P;
+      ps.n0 = nq;
+      ps.out = nullptr;
+      if ((rc = run_pass(ctx, ps, st))) return rc;
+    }
+  ctx->n_act = -1;  // the active list is stale until the next tsd_num_active
   return TSD_OK;
 }
 

@@ -126,6 +126,8 @@ struct PrefillP {
   int* active;
   long long* stat;      // [B][5]
   int B, N, P;
+  const int* slots;     // refill: row j of `series` goes to slot slots[j] (NULL: slot j)
+  int keep_counters;    // refill: the slot's round counter and statistics run on
 };
 hipError_t launch_prefill_stats(const PrefillP& p, hipStream_t st);
 hipError_t launch_reset(const PrefillP& p, hipStream_t st);

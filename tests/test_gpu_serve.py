@@ -1,0 +1,72 @@
+"""Continuous batching (tsd_refill) against the oracle: every series of a stream, whichever slot and
+round counter it started at, gets the forecast the oracle computes for that (slot, first round)."""
+import numpy as np
+import pytest
+
+import paper_2511_18191_amd as tsd
+from harness import TOL, Case
+from oracle import tsd_oracle as orc
+from paper_2511_18191_amd import serve
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_forecast(case, s, slot, round0, trace=None):
+    c = case.cfg
+    return orc.forecast_spec(case.Wt, c.target, case.Wd, c.draft, case.context[s], c.patch, c.horizon, c.K, c.sigma, c.sigma,
+                             case.seed, slot, round0=round0, trace=trace)
+
+
+@pytest.mark.parametrize("name,slots,sigma", [("mini2_fp32", 3, 0.5), ("cfg1", 4, 0.3)])
+def test_stream_through_refilled_slots_matches_oracle_fp32(name, slots, sigma):
+    case = Case(name, B=11, sigma=sigma)
+    c = case.cfg
+    sess = case.session(max_batch=slots)
+    out, placement = serve.run_stream(sess, case.context, c.n_ctx, c.horizon, track=True)
+    out = out.cpu().numpy()
+    assert sorted(p[0] for p in placement[:slots]) == list(range(slots)) and all(p is not None for p in placement)
+    assert any(p[1] > 0 for p in placement[slots:])           # later series started at a running round counter
+    checked = 0
+    for s in range(c.batch):
+        slot, r0 = placement[s]
+        trace = []
+        ref, st = _oracle_forecast(case, s, slot, r0, trace)
+        near = any(np.any(np.abs(np.minimum(0, r["ell"][: r["n"] + (r["n"] < c.K)]) - r["logu"][: r["n"] + (r["n"] < c.K)]) < 1e-4)
+                   for r in trace)
+        if not near:
+            np.testing.assert_allclose(out[s], ref, rtol=0, atol=1e-4 * np.abs(ref).max(), err_msg=f"series {s} in slot {slot} from round {r0}")
+            checked += 1
+    assert checked >= c.batch - 2
+    # the slot's counters kept running: rounds served per slot add up over its series
+    per = sess.get_series_stats().cpu().numpy()
+    assert per[:, 3].sum() == c.batch * c.T
+
+
+def test_stream_equals_batches_when_nothing_desynchronises():
+    # draft = target accepts everything: all series of a batch finish together, so the stream is just
+    # successive batches and (bf16 included) each series' forecast is bit-identical to the
+    # batch-synchronous one as long as it sits in the same slot
+    case = Case("mini2", B=10, sigma=0.5, draft_is_target=True)
+    c = case.cfg
+    sess = case.session(max_batch=5)
+    out, placement = serve.run_stream(sess, case.context, c.n_ctx, c.horizon, track=True)
+    ref = serve.run_batches(sess, case.context, c.n_ctx, c.horizon)
+    assert [p[0] for p in placement] == [0, 1, 2, 3, 4] * 2
+    np.testing.assert_array_equal(out[:5].cpu().numpy(), ref[:5].cpu().numpy())
+    # second batch: same slots, but the stream's draws continue the round counter (batches restart at 0);
+    # with every proposal accepted by a wide margin the forecasts still agree exactly
+    np.testing.assert_array_equal(out[5:].cpu().numpy(), ref[5:].cpu().numpy())
+
+
+def test_refill_argument_checks():
+    case = Case("mini2_fp32", B=4, sigma=0.5)
+    c = case.cfg
+    sess = case.session()
+    with pytest.raises(tsd.TsdError):
+        sess.refill([0], case.context[:1])                    # before prefill
+    sess.prefill(case.context, c.n_ctx, c.horizon)
+    for bad in ([4], [-1], [1, 1]):
+        with pytest.raises(tsd.TsdError):
+            sess.refill(bad, case.context[: len(bad)])
+    sess.refill([2], case.context[:1])                        # a running slot may be replaced
+    assert sess.num_active() == 4
