@@ -280,6 +280,14 @@ int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_de
  * (a multiple of 16).  Its known traffic calibrates the profiler's memory counters. */
 int tsd_bench_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
 
+/* Measurement tap: `blocks` workgroups of 256 lanes, workgroup w reading its own slice
+ * src_dev[w * bytes_per_block ...) `iters` times with 16-byte loads (the way a GEMM workgroup walks
+ * its operand panels); slices that fit L2 measure the cache-to-CU operand stream that bounds a
+ * tiled GEMM of a given tile shape.  src_dev holds blocks * bytes_per_block bytes; sink_dev is
+ * uint32 [blocks] (receives a checksum).  No handle needed. */
+int tsd_bench_stream(const void* src_dev, size_t bytes_per_block, int32_t blocks, int32_t iters, uint32_t* sink_dev,
+                     void* stream);
+
 const char* tsd_last_error(tsd_ctx* ctx);
 
 /* ABI version of this header (bumped on incompatible change). */

@@ -1184,6 +1184,15 @@ int tsd_bench_copy(void* dst_dev, const void* src_dev, size_t bytes, void* strea
   return TSD_OK;
 }
 
+int tsd_bench_stream(const void* src_dev, size_t bytes_per_block, int32_t blocks, int32_t iters, uint32_t* sink_dev,
+                     void* stream) {
+  if (!src_dev || !sink_dev) return fail(nullptr, TSD_E_INVALID_ARG, "device pointers must not be NULL");
+  if (bytes_per_block < 16 || (bytes_per_block % 16) || ((uintptr_t)src_dev % 16) || blocks < 1 || blocks > 65536 || iters < 1)
+    return fail(nullptr, TSD_E_INVALID_ARG, "need bytes_per_block a positive multiple of 16, 1..65536 blocks, iters >= 1");
+  HIP_TRY(nullptr, launch_stream(src_dev, bytes_per_block, blocks, iters, sink_dev, (hipStream_t)stream));
+  return TSD_OK;
+}
+
 int tsd_set_accept_override(tsd_ctx* ctx, float alpha) {
   if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
   if (alpha > 1.f || alpha == 0.f || std::isnan(alpha)) return fail(ctx, TSD_E_INVALID_ARG, "alpha must be in (0, 1], or negative to disable");

@@ -187,5 +187,6 @@ hipError_t launch_compact_active(const int* active, int B, int* list, int* count
 hipError_t launch_sum_stats(const long long* stat, int B, long long* out5, hipStream_t st);
 hipError_t launch_fill_nan(float* p, long n, hipStream_t st);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+hipError_t launch_stream(const void* src, size_t bytes_per_block, int blocks, int iters, unsigned* sink, hipStream_t st);
 
 }  // namespace tsd
