@@ -25,6 +25,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--sigma", type=float, default=None)
+    ap.add_argument("--sample-proposals", action="store_true", help="ablation: x_i = mu_q + sigma_q eps")
+    ap.add_argument("--fallback-r", type=float, default=0.0, help="ablation: fallback / bonus noise scale")
+    ap.add_argument("--naive-verify", action="store_true", help="ablation: one target pass per prefix")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-series", type=int, default=64, help="series in the oracle's bounded sample (~10-20 s of CPU work at cfg2)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -106,7 +109,7 @@ def kernel_rooflines(sess, dtype, steps, workload):
     return out
 
 
-def cpu_baseline(case, n_series):
+def cpu_baseline(case, n_series, **oracle_kw):
     """The oracle, as it stands, on a bounded sample: n_series series, whole horizon,
     single-pass mode, one process (numpy's BLAS threads).  The only place the oracle is used."""
     from oracle import tsd_oracle as orc
@@ -115,7 +118,7 @@ def cpu_baseline(case, n_series):
     t0 = time.perf_counter()
     for b in range(n_series):
         orc.forecast_spec(Wt, c.target, Wd, c.draft, case.context[b], c.patch, c.horizon, c.K, c.sigma,
-                          c.sigma, case.seed, b)
+                          c.sigma, case.seed, b, **oracle_kw)
     dt = time.perf_counter() - t0
     try:
         from threadpoolctl import threadpool_info
@@ -147,7 +150,8 @@ def main():
 
     case = synth.Inputs(a.config, sigma=a.sigma)
     c = case.cfg
-    sess = tsd.session_for(case)
+    flags = (tsd.TSD_FLAG_SAMPLE_PROPOSALS if a.sample_proposals else 0) | (tsd.TSD_FLAG_NAIVE_VERIFY if a.naive_verify else 0)
+    sess = tsd.session_for(case, flags=flags, fallback_r=a.fallback_r)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     sess.prefill(case.context, c.n_ctx, c.horizon)
@@ -181,7 +185,8 @@ def main():
         "dtype": c.dtype, "data": "synthetic",
         "config": {"workload": f"{c.name}: B={c.batch} P={c.patch} N={c.n_ctx} H={c.horizon} K={c.K} sigma={c.sigma} "
                                f"target {c.target.n_layers}L/d{c.target.d_model} draft {c.draft.n_layers}L/d{c.draft.d_model}",
-                   "step": "reset to post-prefill state + speculative rounds until all series reach the horizon"},
+                   "step": "reset to post-prefill state + speculative rounds until all series reach the horizon",
+                   "ablation": {"sample_proposals": a.sample_proposals, "fallback_r": a.fallback_r, "naive_verify": a.naive_verify}},
         "speedup_vs_target_only": t_base / t_spec,
         "target_only_steps_per_s": c.batch * c.horizon / t_base,
         "target_only_ms": t_base * 1e3,
@@ -198,7 +203,8 @@ def main():
         "kernel_families": fam,
     }
     if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(case, min(a.cpu_series, c.batch))
+        out["cpu_baseline"] = cpu_baseline(case, min(a.cpu_series, c.batch), sample_proposals=a.sample_proposals,
+                                           fallback_r=a.fallback_r, single_pass=not a.naive_verify)
     print(json.dumps(out))
 
 

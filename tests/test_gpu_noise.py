@@ -174,3 +174,24 @@ def test_round_lockstep_with_diagonal_scales_and_sampling(name):
     if c.dtype == "fp32":
         assert rep["mismatched"] <= rep["near_ties"] and rep["max_abs_ell"] < 2e-5
     assert 0 < rep["accepted"] < rep["tested"]
+
+
+def test_benchmark_size_with_all_knobs():
+    # the benchmark configuration at full size with sampled proposals, fallback noise and the diagonal
+    # surrogate together; the oracle follows three sampled series for two rounds, then the decode
+    # finishes free-running (graph replay) and the books must balance
+    case = Case("cfg2")
+    c = case.cfg
+    P = c.patch
+    sp = np.linspace(0.8, 1.2, P).astype(np.float32).astype(np.float64)
+    sq = (1.0 + 0.2 * np.sin(np.arange(P))).astype(np.float32).astype(np.float64)
+    sess = case.session(flags=tsd.TSD_FLAG_SAMPLE_PROPOSALS, fallback_r=0.5)
+    sess.set_sigma_diag(sp, sq)
+    rep = lockstep(case, sess, max_rounds=2, subset=[0, 128, 255], sample_proposals=True, fallback_r=0.5, sigma_p=sp, sigma_q=sq)
+    print(f"\ncfg2 full size, all knobs: per-pass q {rep['pass_rel_q']:.2e} p {rep['pass_rel_p']:.2e}; chained X {rep['max_rel_X']:.2e} "
+          f"mu_p {rep['max_rel_mu_p']:.2e}; accept {rep['accepted']}/{rep['tested']}")
+    assert rep["max_rel_X"] <= TOL[c.dtype] and rep["max_rel_mu_p"] <= TOL[c.dtype]
+    while sess.num_active() > 0:
+        sess.round()
+    st = sess.get_stats()
+    assert st["committed"] == c.batch * c.T and torch.isfinite(sess.get_forecast()).all()

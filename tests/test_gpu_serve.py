@@ -70,3 +70,27 @@ def test_refill_argument_checks():
             sess.refill(bad, case.context[: len(bad)])
     sess.refill([2], case.context[:1])                        # a running slot may be replaced
     assert sess.num_active() == 4
+
+
+def test_refill_on_a_small_batch_handle_and_with_a_routed_target():
+    # the weight-streaming GEMM path (B (K+1) <= 32) and the routed FFN both prefill refilled slots
+    # through slot lists; fp32 twin of the routed configuration for an exact comparison
+    for name, slots in (("mini2", 2), ("mini5_fp32", 3)):
+        case = Case(name, B=7, sigma=0.6)
+        c = case.cfg
+        sess = case.session(max_batch=slots)
+        out, placement = serve.run_stream(sess, case.context, c.n_ctx, c.horizon, track=True)
+        out = out.cpu().numpy()
+        assert np.isfinite(out).all()
+        worst = 0.0
+        for s in range(c.batch):
+            slot, r0 = placement[s]
+            trace = []
+            ref, _ = _oracle_forecast(case, s, slot, r0, trace)
+            near = any(np.any(np.abs(np.minimum(0, r["ell"][: r["n"] + (r["n"] < c.K)]) - r["logu"][: r["n"] + (r["n"] < c.K)]) < 2e-2)
+                       for r in trace)
+            if not near:      # far from any tie the accepted lengths agree, so the forecasts do (to the dtype's tolerance)
+                err = np.abs(out[s] - ref).max() / np.abs(ref).max()
+                worst = max(worst, err)
+        print(f"\n{name}: worst relative forecast error over streamed series {worst:.2e}")
+        assert worst <= (5e-2 if c.dtype == "bf16" else 1e-4)
