@@ -156,7 +156,9 @@ int tsd_reset_decode(tsd_ctx* ctx, void* stream);
  * proposals and 2 for the fallback patch: the block's four words give lattice uniforms u0..u3
  * (as for the acceptance uniform) and the Box-Muller pairs sqrt(-2 ln u0) (cos, sin)(2 pi u1),
  * sqrt(-2 ln u2) (cos, sin)(2 pi u3); element e takes number e mod 4.
- * Fills the internal X [B,K,P] (and mu_q [B,K,P] when sampling). */
+ * Fills the internal X [B,K,P] (and mu_q [B,K,P] when sampling).  Once tsd_num_active has
+ * reported that no active series needs K more patches, only min(K, largest need) steps run and
+ * the later rows of X keep stale values (no series tests them). */
 int tsd_draft_propose(tsd_ctx* ctx, void* stream);
 
 /* Single-pass verification (Sec. "Single-Pass Verification"): one causal target pass over the
@@ -172,8 +174,10 @@ int tsd_target_verify(tsd_ctx* ctx, void* stream);
  *           + (1/2) log(sigma_q^2 / sigma_p^2),     ||u||_d^2 = ||u||^2 / P;
  *   u_i = Philox4x32-10(counter = (series, round of that series, i, 0), key = seed), word 0,
  *         u = ((w >> 9) + 0.5) * 2^-23;   accept iff log u_i <= min(0, ell_i), left to right;
- *   n = number of leading accepts; commit x_1..x_n then mu_p^(n+1) (fallback if n < K, bonus
- *   if n = K), truncated at T = ceil(H/P) patches; both KV caches keep exactly the entries of
+ *   a series with r = T - committed patches left (T = ceil(H/P)) tests only positions
+ *   1..K_b, K_b = min(K, r): nothing is proposed for patches that could never be committed;
+ *   n = number of leading accepts; commit x_1..x_n then mu_p^(n+1) (fallback if n < K_b, bonus
+ *   if n = K_b), truncated at T patches (which drops a bonus patch at T + 1); both KV caches keep exactly the entries of
  *   the committed history; mu_p^(n+1) becomes the pending token; a series with T patches
  *   becomes inactive.  With fallback_r = r > 0 the corrected / bonus patch is the draw
  *   mu_p^(n+1) + r eps (stream 2, position n+1; Sec. "Bonus Patch on Full Acceptance").

@@ -19,8 +19,10 @@ What the paper fixes and what it leaves open
     tanh-GELU, no biases, softmax-router top-2 MoE with renormalised gates), instance
     normalisation (mean / population std with eps 1e-5 under the root), the uniform draw
     (Philox4x32-10 keyed by seed, counter = (series, round, position, 0), 23-bit mid-point
-    lattice), "u <= alpha" evaluated as log u <= min(0, ell), truncation of commits at
-    T = ceil(H / P).
+    lattice), "u <= alpha" evaluated as log u <= min(0, ell), the horizon: T = ceil(H / P)
+    patches, a round of a series with r patches left proposes and tests min(K, r) positions
+    (nothing is proposed for patches that could never be committed) and a bonus patch beyond T
+    is dropped.
 
 Pins (tests/test_oracle_*.py): Philox known-answer vectors; closed forms of Eq. 5 / Eq. 6 and
 of the fidelity identity (Eq. 9); the model collapsing to a two-matmul closed form when the
@@ -318,17 +320,18 @@ def forecast_spec(Wt, mt, Wd, md, series_context, P, horizon, K, sigma_p, sigma_
     while Y.shape[0] < T:
         draw = (lambda i, r=r: u_fn(b, r, i)) if u_fn is not None else (lambda i, r=r: uniform(seed, b, r, i))
         eps = lambda stream, i, r=r: normal(seed, b, r, i, stream, P)
-        rec = spec_round(Wt, mt, Wd, md, np.vstack([hist, Y]), K, sigma_p, sigma_q, draw,
+        K_r = min(K, T - Y.shape[0])                 # no proposals for patches past the horizon
+        rec = spec_round(Wt, mt, Wd, md, np.vstack([hist, Y]), K_r, sigma_p, sigma_q, draw,
                          single_pass=single_pass, alpha_override=alpha_override, eps_fn=eps,
                          sample_proposals=sample_proposals, fallback_r=fallback_r)
         if trace is not None:
             trace.append(rec)
         n = rec["n"]
         stats["rounds"] += 1
-        stats["tested"] += n + (1 if n < K else 0)
+        stats["tested"] += n + (1 if n < K_r else 0)
         stats["accepted"] += n
         stats["lengths"].append(n + 1)
-        Y = np.vstack([Y, rec["commits"]])[:T]       # whole patches, never more than T
+        Y = np.vstack([Y, rec["commits"]])[:T]       # whole patches, never more than T (drops a bonus patch at T + 1)
         r += 1
     stats["committed"] = Y.shape[0]
     return (Y.reshape(-1) * s + m)[:horizon], stats

@@ -191,11 +191,15 @@ __global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
     return;
   }
   const int r = p.round[b];
+  const int c0 = p.committed[b];
+  // a series with fewer than K patches left proposes and tests only as many positions as it
+  // still needs: later ones could never be committed
+  const int Kb = min(K, p.T - c0);
   const float* X = p.X + (long)b * K * P;
   const float* MQ = p.mu_q + (long)b * K * P;
   const float* MP = p.mu_p + (long)b * (K + 1) * P;
   float my_ep = 0.f, my_eq = 0.f;
-  for (int i = 0; i < K; ++i) {
+  for (int i = 0; i < Kb; ++i) {
     float ep = 0.f, eq = 0.f;
     for (int e = lane; e < P; e += 64) {
       float x = X[i * P + e];
@@ -220,7 +224,7 @@ __global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
   }
   bool reject = false;
   float ell = NAN, logu = NAN, thr = 0.f;
-  if (lane < K) {
+  if (lane < Kb) {
     // Eq. 5 with per-dimension energies ||.||^2 / P
     if (p.inv2sp2_vec)
       ell = p.temper * (-(my_ep / (float)P) + (my_eq / (float)P) + p.logdet_dev[0]);
@@ -233,8 +237,8 @@ __global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
     reject = !(logu <= thr);
   }
   const unsigned long long rej = __ballot(reject);
-  const int n_free = rej ? (int)__builtin_ctzll(rej) : K;  // leading accepts
-  const int tested = n_free + (n_free < K ? 1 : 0);
+  const int n_free = rej ? (int)__builtin_ctzll(rej) : Kb;  // leading accepts
+  const int tested = n_free + (n_free < Kb ? 1 : 0);
   const bool is_tested = lane < tested;
   const unsigned long long near = __ballot(is_tested && fabsf(thr - logu) < 1e-4f);
   if (lane < K) {
@@ -244,9 +248,8 @@ __global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
   int n = n_free;
   if (p.forced) {
     int f = p.forced[b];
-    if (f >= 0 && f <= K) n = f;
+    if (f >= 0 && f <= Kb) n = f;
   }
-  const int c0 = p.committed[b];
   const int L = n + 1;
   const int Lc = min(L, p.T - c0);
   float* fc = p.forecast + ((long)b * p.T + c0) * P;
@@ -297,11 +300,17 @@ hipError_t launch_forecast_out(const float* forecast, const float* mean, const f
 }
 
 // One block: stable compaction of the active series (ascending series index) and their count.
-__global__ __launch_bounds__(1024) void compact_active_kernel(const int* active, int B, int* list, int* count) {
+// count[0] = number of active series, count[1] = the largest number of patches any of them still
+// needs (T - committed).
+__global__ __launch_bounds__(1024) void compact_active_kernel(const int* active, const int* committed, int T, int B,
+                                                              int* list, int* count) {
   __shared__ int wave_cnt[16];
-  __shared__ int base_s;
+  __shared__ int base_s, max_rem;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  if (threadIdx.x == 0) base_s = 0;
+  if (threadIdx.x == 0) {
+    base_s = 0;
+    max_rem = 0;
+  }
   __syncthreads();
   for (int b0 = 0; b0 < B; b0 += 1024) {
     const int b = b0 + threadIdx.x;
@@ -311,7 +320,10 @@ __global__ __launch_bounds__(1024) void compact_active_kernel(const int* active,
     __syncthreads();
     int off = base_s;
     for (int i = 0; i < w; ++i) off += wave_cnt[i];
-    if (on) list[off + __popcll(m & ((1ull << lane) - 1ull))] = b;
+    if (on) {
+      list[off + __popcll(m & ((1ull << lane) - 1ull))] = b;
+      atomicMax(&max_rem, T - committed[b]);
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
       int t = 0;
@@ -320,10 +332,14 @@ __global__ __launch_bounds__(1024) void compact_active_kernel(const int* active,
     }
     __syncthreads();
   }
-  if (threadIdx.x == 0) *count = base_s;
+  if (threadIdx.x == 0) {
+    count[0] = base_s;
+    count[1] = max_rem;
+  }
 }
-hipError_t launch_compact_active(const int* active, int B, int* list, int* count, hipStream_t st) {
-  hipLaunchKernelGGL(compact_active_kernel, dim3(1), dim3(1024), 0, st, active, B, list, count);
+hipError_t launch_compact_active(const int* active, const int* committed, int T, int B, int* list, int* count,
+                                 hipStream_t st) {
+  hipLaunchKernelGGL(compact_active_kernel, dim3(1), dim3(1024), 0, st, active, committed, T, B, list, count);
   return hipGetLastError();
 }
 

@@ -75,7 +75,8 @@ struct tsd_ctx {
   float alpha_override;
   std::vector<int> host_pt;
   // captured launch sequences of tsd_round / tsd_target_step (rebuilt when anything they bake in changes)
-  hipGraphExec_t graph_round = nullptr, graph_step = nullptr;
+  hipGraphExec_t graph_round[17] = {}, graph_step = nullptr;  // one round graph per number of positions
+  int k_round = 0;  // positions the next round proposes: min(K, most patches any active series still needs)
   // measurement tap: event pairs around every launch of one kernel family
   int* refill_list = nullptr;      // device copy of the slots of the last tsd_refill
   std::vector<int> host_refill;
@@ -513,11 +514,15 @@ Cover cover(const tsd_ctx* ctx) {
 }
 
 void drop_graphs(tsd_ctx* ctx) {
-  for (hipGraphExec_t* g : {&ctx->graph_round, &ctx->graph_step})
-    if (*g) {
-      (void)hipGraphExecDestroy(*g);
-      *g = nullptr;
+  for (hipGraphExec_t& g : ctx->graph_round)
+    if (g) {
+      (void)hipGraphExecDestroy(g);
+      g = nullptr;
     }
+  if (ctx->graph_step) {
+    (void)hipGraphExecDestroy(ctx->graph_step);
+    ctx->graph_step = nullptr;
+  }
 }
 
 // Runs `body` (a sequence of kernel launches on `st`) through a HIP graph: captured on first use,
@@ -548,6 +553,14 @@ int run_graphed(tsd_ctx* ctx, hipGraphExec_t* slot, hipStream_t st, F body) {
   }
   HIP_TRY(ctx, hipGraphLaunch(*slot, st));
   return TSD_OK;
+}
+
+// Positions the next round proposes and verifies.  A series with r patches left tests min(K, r)
+// positions (the acceptance kernel applies that per series); when tsd_num_active has reported
+// that no active series needs K more patches, the passes themselves shrink to the largest need.
+int round_positions(const tsd_ctx* ctx) {
+  const int K = ctx->cfg.K;
+  return (ctx->k_round >= 1 && ctx->k_round < K) ? ctx->k_round : K;
 }
 
 int require_ready(tsd_ctx* ctx, bool need_prefill) {
@@ -777,6 +790,7 @@ int tsd_prefill(tsd_ctx* ctx, const float* series_dev, int32_t B, int32_t n_ctx_
   hipStream_t st = (hipStream_t)stream;
   ctx->prefilled = false;
   ctx->n_act = -1;
+  ctx->k_round = 0;
   drop_graphs(ctx);  // batch size, context length and horizon are baked into the captured launches
   // page table: every series reserves the pages its whole forecast can touch
   const int need = (N + T + ctx->K_max + c.page_tokens - 1) / c.page_tokens;
@@ -865,6 +879,7 @@ int tsd_refill(tsd_ctx* ctx, const int32_t* slots_host, int32_t n, const float* 
       if ((rc = run_pass(ctx, ps, st))) return rc;
     }
   ctx->n_act = -1;  // the active list is stale until the next tsd_num_active
+  ctx->k_round = 0;
   return TSD_OK;
 }
 
@@ -875,6 +890,7 @@ int tsd_reset_decode(tsd_ctx* ctx, void* stream) {
               ctx->round, ctx->active, ctx->stat, ctx->B, ctx->N, ctx->cfg.patch};
   HIP_TRY(ctx, launch_reset(pp, (hipStream_t)stream));
   ctx->n_act = -1;  // every series is active again
+  ctx->k_round = 0;
   return TSD_OK;
 }
 
@@ -882,7 +898,8 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
   int rc = require_ready(ctx, true);
   if (rc) return rc;
   const tsd_config& c = ctx->cfg;
-  const int P = c.patch, K = c.K;
+  const int P = c.patch, K = c.K;      // K: layout of the round tensors
+  const int Kr = round_positions(ctx);  // positions proposed this round
   hipStream_t st = (hipStream_t)stream;
   ctx->injected = false;
   // Step 1 ingests two tokens per series: the token just before the pending one and the pending
@@ -931,7 +948,7 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
   ps.t_skip = 1;
   if ((rc = run_pass(ctx, ps, st))) return rc;
   if ((rc = draw(1))) return rc;
-  for (int i = 2; i <= K; ++i) {  // step i consumes x_{i-1} at position len + i - 1, emits x_i
+  for (int i = 2; i <= Kr; ++i) {  // step i consumes x_{i-1} at position len + i - 1, emits x_i
     std::memset(&ps, 0, sizeof(ps));
     ps.which = TSD_DRAFT;
     ps.B = cv.n;
@@ -956,6 +973,7 @@ int tsd_target_verify(tsd_ctx* ctx, void* stream) {
   if (rc) return rc;
   const tsd_config& c = ctx->cfg;
   const int P = c.patch, K = c.K;
+  const int Kr = round_positions(ctx);  // boundaries beyond Kr + 1 belong to patches no active series can commit
   const Cover cv = cover(ctx);
   if (cv.n == 0) return TSD_OK;
   Pass ps;
@@ -963,7 +981,7 @@ int tsd_target_verify(tsd_ctx* ctx, void* stream) {
   ps.which = TSD_TARGET;
   ps.B = cv.n;
   ps.act = cv.act;
-  ps.nq = K + 1;
+  ps.nq = Kr + 1;
   ps.base_pos = ctx->len;
   ps.pos_off = 0;
   ps.src0 = ctx->pending;
@@ -978,7 +996,7 @@ int tsd_target_verify(tsd_ctx* ctx, void* stream) {
     // Ablation "w/o single-pass verification": every prefix [pending, x_1..x_{i-1}] is encoded by
     // a pass of its own and only its last boundary is read, so a round costs (K+1)(K+2)/2 target
     // tokens instead of K+1.  (Each pass rewrites the same KV entries with the same values.)
-    for (int i = 1; i <= K + 1; ++i) {
+    for (int i = 1; i <= Kr + 1; ++i) {
       ps.nq = i;
       ps.t_skip = i - 1;
       ps.out = ctx->mu_p + (size_t)(i - 1) * P;
@@ -998,7 +1016,7 @@ int tsd_accept_commit(tsd_ctx* ctx, const int32_t* forced_len_dev, void* stream)
 int tsd_round(tsd_ctx* ctx, void* stream) {
   int rc = require_ready(ctx, true);
   if (rc) return rc;
-  return run_graphed(ctx, &ctx->graph_round, (hipStream_t)stream, [&]() {
+  return run_graphed(ctx, &ctx->graph_round[round_positions(ctx)], (hipStream_t)stream, [&]() {
     int r;
     if ((r = tsd_draft_propose(ctx, stream))) return r;
     if ((r = tsd_target_verify(ctx, stream))) return r;
@@ -1038,10 +1056,15 @@ int tsd_num_active(tsd_ctx* ctx, int32_t* out_host, void* stream) {
   if (rc) return rc;
   if (!out_host) return fail(ctx, TSD_E_INVALID_ARG, "out_host is NULL");
   hipStream_t st = (hipStream_t)stream;
-  HIP_TRY(ctx, launch_compact_active(ctx->active, ctx->B, ctx->act_list, ctx->count_out, st));
-  HIP_TRY(ctx, hipMemcpyAsync(out_host, ctx->count_out, 4, hipMemcpyDeviceToHost, st));
+  int32_t both[2] = {0, 0};
+  HIP_TRY(ctx, launch_compact_active(ctx->active, ctx->committed, ctx->T, ctx->B, ctx->act_list, ctx->count_out, st));
+  HIP_TRY(ctx, hipMemcpyAsync(both, ctx->count_out, 8, hipMemcpyDeviceToHost, st));
   HIP_TRY(ctx, hipStreamSynchronize(st));
-  if (!(ctx->cfg.flags & TSD_FLAG_NO_COMPACT)) ctx->n_act = *out_host;  // later passes cover only these series
+  *out_host = both[0];
+  if (!(ctx->cfg.flags & TSD_FLAG_NO_COMPACT)) {
+    ctx->n_act = both[0];    // later passes cover only these series ...
+    ctx->k_round = both[1];  // ... and only the positions one of them can still commit
+  }
   return TSD_OK;
 }
 
@@ -1206,6 +1229,7 @@ int tsd_set_block_size(tsd_ctx* ctx, int32_t K) {
   if (K < 1 || K > ctx->K_max) return fail(ctx, TSD_E_OUT_OF_RANGE, "K must be in 1..K of tsd_create");
   if (K != ctx->cfg.K) {
     ctx->cfg.K = K;
+    ctx->k_round = 0;
     ctx->injected = false;  // injected round tensors were laid out for the old K
     drop_graphs(ctx);
   }

@@ -182,8 +182,9 @@ hipError_t launch_combine(int dtype, const float* Y, const int* slot_of, const f
 
 hipError_t launch_forecast_out(const float* forecast, const float* mean, const float* sdev, const int* committed,
                                float* out, int B, int P, int T, int H, hipStream_t st);
-// stable list of the series with active != 0 and their count
-hipError_t launch_compact_active(const int* active, int B, int* list, int* count, hipStream_t st);
+// stable list of the series with active != 0; count[0] = how many, count[1] = max over them of T - committed
+hipError_t launch_compact_active(const int* active, const int* committed, int T, int B, int* list, int* count,
+                                 hipStream_t st);
 hipError_t launch_sum_stats(const long long* stat, int B, long long* out5, hipStream_t st);
 hipError_t launch_fill_nan(float* p, long n, hipStream_t st);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);

@@ -64,11 +64,12 @@ def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=Tru
         sess.draft_propose()
         sess.target_verify()
         forced = np.full(B, -1, np.int32)
-        recs = {}
+        recs, Kb = {}, {}
         for b in follow:
             if Y[b].shape[0] >= T:
                 continue
-            recs[b] = orc.spec_round(case.Wt, c.target, case.Wd, c.draft, np.vstack([hist[b], Y[b]]), K, sp, sq,
+            Kb[b] = min(K, T - Y[b].shape[0])       # a series proposes no more positions than it has patches left
+            recs[b] = orc.spec_round(case.Wt, c.target, case.Wd, c.draft, np.vstack([hist[b], Y[b]]), Kb[b], sp, sq,
                                      (lambda i, b=b: orc.uniform(case.seed, b, rnd[b], i)),
                                      eps_fn=(lambda stream, i, b=b: orc.normal(case.seed, b, rnd[b], i, stream, P)),
                                      sample_proposals=sample_proposals, fallback_r=fallback_r)
@@ -76,10 +77,11 @@ def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=Tru
         sess.accept_commit(torch.from_numpy(forced))
         io = {k: v.cpu().numpy() for k, v in sess.get_round_io().items()}
         for b, rec in recs.items():
-            n = rec["n"]
+            n, Kc = rec["n"], Kb[b]
+            io_b = {"X": io["X"][b][:Kc], "mu_q": io["mu_q"][b][:Kc], "mu_p": io["mu_p"][b][:Kc + 1]}
             # compare what both sides computed from (nearly) identical histories
-            rx = max(rel_err(io["X"][b], rec["X"]).max(), rel_err(io["mu_q"][b], rec["mu_q"]).max())
-            rp = rel_err(io["mu_p"][b], rec["mu_p"]).max()
+            rx = max(rel_err(io_b["X"], rec["X"]).max(), rel_err(io_b["mu_q"], rec["mu_q"]).max())
+            rp = rel_err(io_b["mu_p"], rec["mu_p"]).max()
             rep["max_rel_X"] = max(rep["max_rel_X"], rx)
             rep["max_rel_mu_p"] = max(rep["max_rel_mu_p"], rp)
             if check:
@@ -87,20 +89,20 @@ def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=Tru
                 assert rp <= tol, f"series {b} round {rnd[b]}: target means differ, rel {rp:.3e}"
             if per_pass:
                 hg = np.vstack([hist[b], Yg[b]])
-                Xg, n0 = io["X"][b].astype(np.float64), hg.shape[0]
-                for i in range(K):
+                Xg, n0 = io_b["X"].astype(np.float64), hg.shape[0]
+                for i in range(Kc):
                     q_ref = orc.forward(case.Wd, c.draft, np.vstack([hg, Xg[:i]]))[-1]
-                    rep["pass_rel_q"] = max(rep["pass_rel_q"], rel_err(io["mu_q"][b][i], q_ref))
+                    rep["pass_rel_q"] = max(rep["pass_rel_q"], rel_err(io_b["mu_q"][i], q_ref))
                 p_ref = orc.forward(case.Wt, c.target, np.vstack([hg, Xg]))[n0 - 1:]
-                rep["pass_rel_p"] = max(rep["pass_rel_p"], rel_err(io["mu_p"][b], p_ref).max())
+                rep["pass_rel_p"] = max(rep["pass_rel_p"], rel_err(io_b["mu_p"], p_ref).max())
                 if check:
                     assert rep["pass_rel_q"] <= PASS_TOL[c.dtype] and rep["pass_rel_p"] <= PASS_TOL[c.dtype], \
                         f"series {b} round {rnd[b]}: per-pass error {rep['pass_rel_q']:.3e} / {rep['pass_rel_p']:.3e}"
-                t_g = io["mu_p"][b][n].astype(np.float64)
+                t_g = io_b["mu_p"][n].astype(np.float64)
                 if fallback_r > 0.0:    # what the GPU committed, up to the rounding of its own draw
                     t_g = t_g + fallback_r * orc.normal(case.seed, b, rnd[b], n + 1, orc.STREAM_FALLBACK, P)
                 Yg[b] = np.vstack([Yg[b], Xg[:n], t_g[None, :]])[:T]
-            tested = n + (1 if n < K else 0)
+            tested = n + (1 if n < Kc else 0)
             gap = np.abs(np.minimum(0.0, rec["ell"][:tested]) - rec["logu"][:tested])
             near = bool(np.any(gap < 1e-4))
             rep["near_ties"] += int(near)

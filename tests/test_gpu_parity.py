@@ -77,7 +77,7 @@ def test_free_running_fp32_matches_oracle(name, sigma):
         ref, s = orc.forecast_spec(case.Wt, c.target, case.Wd, c.draft, case.context[b], c.patch, c.horizon, c.K,
                                    c.sigma, c.sigma, case.seed, b, trace=trace)
         for r in trace:
-            t = r["n"] + (r["n"] < c.K)
+            t = r["n"] + (r["n"] < r["X"].shape[0])      # positions of that round (fewer near the horizon)
             near += int(np.any(np.abs(np.minimum(0, r["ell"][:t]) - r["logu"][:t]) < 1e-4))
         tested, accepted, rounds = tested + s["tested"], accepted + s["accepted"], rounds + s["rounds"]
         if near == 0:
@@ -200,7 +200,7 @@ def test_block_length_law_on_gpu():
 def test_accept_kernel_bit_exact_against_oracle_rule():
     # kernel-level parity of Eq. 5 in its general form (x != mu_q, sigma_p != sigma_q) on
     # injected tensors, at the batch of the large configuration (1024 series, K = 6, P = 96)
-    case = Case("mini3", B=1024, sigma=0.5)
+    case = Case("mini3", B=1024, sigma=0.5, horizon=96 * 8)      # T = 8 >= K = 6: every position is tested
     c = case.cfg
     sq = 0.35
     sess = case.session(sigma_q=sq)
@@ -423,3 +423,51 @@ def test_handle_reuse_and_error_paths():
     assert torch.equal(a1[0], f1[0]) and a1[1] == f1[1]
     assert torch.equal(a2[0], f2[0]) and a2[1] == f2[1]
     assert torch.equal(a3[0], a1[0]) and a3[1] == a1[1]
+
+
+def test_no_positions_past_the_horizon():
+    # a series with r patches left tests min(K, r) positions; once tsd_num_active has seen that no
+    # series needs K more, the passes shrink too, and the forecast is bit-identical to the one
+    # obtained with full-size passes (TSD_FLAG_NO_COMPACT keeps them full)
+    import paper_2511_18191_amd as tsd
+    case = Case("mini3", sigma=0.6, horizon=96 * 7)               # T = 7, K = 6
+    c = case.cfg
+    out = []
+    for flags in (0, tsd.TSD_FLAG_NO_COMPACT):
+        sess = case.session(flags=flags | tsd.TSD_FLAG_NO_SKINNY)
+        sess.prefill(case.context, c.n_ctx, c.horizon)
+        tested_cap_ok = True
+        while sess.num_active() > 0:
+            before = sess.get_state()["committed"].cpu().numpy()
+            sess.round()
+            io = sess.get_round_io()
+            ell = io["ell"].cpu().numpy()
+            for b in range(c.batch):
+                left = c.T - before[b]
+                if left > 0:
+                    kb = min(c.K, left)
+                    tested_cap_ok &= bool(np.all(np.isnan(ell[b, kb:])))      # nothing tested past the horizon
+        assert tested_cap_ok
+        out.append((sess.get_forecast().cpu().numpy(), sess.get_stats()))
+    np.testing.assert_array_equal(out[0][0], out[1][0])
+    assert out[0][1] == out[1][1]
+    # and the oracle agrees on the counters in fp32
+    case32 = Case("mini2_fp32", sigma=0.5, horizon=96 * 2 + 10, K=4)   # T = 3 < K
+    c = case32.cfg
+    sess = case32.session()
+    sess.prefill(case32.context, c.n_ctx, c.horizon)
+    while sess.num_active() > 0:
+        sess.round()
+    st = sess.get_stats()
+    tested = accepted = near = 0
+    for b in range(c.batch):
+        trace = []
+        _, s = orc.forecast_spec(case32.Wt, c.target, case32.Wd, c.draft, case32.context[b], c.patch, c.horizon, c.K,
+                                 c.sigma, c.sigma, case32.seed, b, trace=trace)
+        tested, accepted = tested + s["tested"], accepted + s["accepted"]
+        for r in trace:
+            t = r["n"] + (r["n"] < r["X"].shape[0])
+            near += int(np.any(np.abs(np.minimum(0, r["ell"][:t]) - r["logu"][:t]) < 1e-4))
+            assert r["X"].shape[0] <= 3
+    if near == 0:
+        assert (st["tested"], st["accepted"]) == (tested, accepted)

@@ -31,7 +31,7 @@ def test_stream_through_refilled_slots_matches_oracle_fp32(name, slots, sigma):
         slot, r0 = placement[s]
         trace = []
         ref, st = _oracle_forecast(case, s, slot, r0, trace)
-        near = any(np.any(np.abs(np.minimum(0, r["ell"][: r["n"] + (r["n"] < c.K)]) - r["logu"][: r["n"] + (r["n"] < c.K)]) < 1e-4)
+        near = any(np.any(np.abs(np.minimum(0, r["ell"][: r["n"] + (r["n"] < r["X"].shape[0])]) - r["logu"][: r["n"] + (r["n"] < r["X"].shape[0])]) < 1e-4)
                    for r in trace)
         if not near:
             np.testing.assert_allclose(out[s], ref, rtol=0, atol=1e-4 * np.abs(ref).max(), err_msg=f"series {s} in slot {slot} from round {r0}")
@@ -87,7 +87,7 @@ def test_refill_on_a_small_batch_handle_and_with_a_routed_target():
             slot, r0 = placement[s]
             trace = []
             ref, _ = _oracle_forecast(case, s, slot, r0, trace)
-            near = any(np.any(np.abs(np.minimum(0, r["ell"][: r["n"] + (r["n"] < c.K)]) - r["logu"][: r["n"] + (r["n"] < c.K)]) < 2e-2)
+            near = any(np.any(np.abs(np.minimum(0, r["ell"][: r["n"] + (r["n"] < r["X"].shape[0])]) - r["logu"][: r["n"] + (r["n"] < r["X"].shape[0])]) < 2e-2)
                        for r in trace)
             if not near:      # far from any tie the accepted lengths agree, so the forecasts do (to the dtype's tolerance)
                 err = np.abs(out[s] - ref).max() / np.abs(ref).max()

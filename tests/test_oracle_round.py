@@ -79,8 +79,13 @@ def test_draft_equal_to_target_accepts_everything():
                                   1e-3, 1e-3, seed=1, b=b)
         ref = orc.forecast_target_only(Wt, cfg.target, ctx, cfg.patch, cfg.horizon)
         np.testing.assert_allclose(f, ref, rtol=1e-9, atol=1e-12)
-        assert st["accepted"] == st["rounds"] * cfg.K and st["tested"] == st["accepted"]
-        assert st["lengths"] == [cfg.K + 1] * st["rounds"] and st["rounds"] == math.ceil(cfg.T / (cfg.K + 1))
+        # every round of a series with r patches left proposes min(K, r) and commits them all plus the bonus
+        want, rem = [], cfg.T
+        while rem > 0:
+            want.append(min(cfg.K, rem) + 1)
+            rem -= want[-1]
+        assert st["lengths"] == want and st["rounds"] == math.ceil(cfg.T / (cfg.K + 1))
+        assert st["accepted"] == sum(L - 1 for L in want) and st["tested"] == st["accepted"]
 
 
 def test_sigma_to_zero_recovers_target_only():
@@ -107,7 +112,12 @@ def test_forecast_bookkeeping_and_truncation():
         assert all(1 <= L <= cfg.K + 1 for L in st["lengths"])
         assert sum(st["lengths"][:-1]) < T <= sum(st["lengths"])
         assert st["accepted"] == sum(L - 1 for L in st["lengths"])
-        assert st["tested"] == sum(r["n"] + (r["n"] < cfg.K) for r in trace)
+        assert st["tested"] == sum(r["n"] + (r["n"] < r["X"].shape[0]) for r in trace)
+        # no round proposes more than the patches the series still needs
+        left = T
+        for r in trace:
+            assert r["X"].shape[0] == min(cfg.K, left)
+            left -= min(r["n"] + 1, left)
         # each round's history is the context plus everything committed before it
         m, s = orc.context_stats(series[2, : cfg.context].astype(np.float64))
         y = np.vstack([r["commits"] for r in trace])[:T].reshape(-1) * s + m
@@ -136,3 +146,27 @@ def test_block_length_law_under_injected_rate():
         assert abs(Ls.mean() - EL) < 4 * Ls.std() / math.sqrt(n)
     assert math.isclose(orc.expected_block_length(0.9, 3), 3.439, rel_tol=1e-12)
     assert math.isclose(orc.expected_block_length(0.75, 6), (1 - 0.75 ** 7) / 0.25, rel_tol=1e-12)
+
+
+def test_not_proposing_past_the_horizon_changes_no_forecast():
+    # a round of a series with r < K patches left proposes r positions; running the full K and
+    # truncating the commits at T (the other possible reading) gives the same patches: positions
+    # past the horizon can only produce commits that are dropped
+    cfg, Wt, Wd, series = _setup(B=2)
+    P, K = cfg.patch, cfg.K
+    for H, sigma in ((96, 0.3), (90, 1.0), (40, 2.0)):
+        T = -(-H // P)
+        ctx = series[1, : cfg.context].astype(np.float64)
+        m, s = orc.context_stats(ctx)
+        hist = ((ctx - m) / s).reshape(-1, P)
+        Y = np.empty((0, P))
+        r = 0
+        while Y.shape[0] < T:                                   # the full-K reading, written out
+            rec = orc.spec_round(Wt, cfg.target, Wd, cfg.draft, np.vstack([hist, Y]), K, sigma, sigma,
+                                 lambda i, r=r: orc.uniform(9, 1, r, i))
+            Y = np.vstack([Y, rec["commits"]])[:T]
+            r += 1
+        want = (Y.reshape(-1) * s + m)[:H]
+        got, st = orc.forecast_spec(Wt, cfg.target, Wd, cfg.draft, ctx, P, H, K, sigma, sigma, seed=9, b=1)
+        np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-12)
+        assert st["rounds"] == r
