@@ -59,6 +59,7 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
 
   const int lane = threadIdx.x;
   const int bl = blockIdx.x / p.Hh, h = blockIdx.x % p.Hh;
+  if (p.n_dev && bl >= *p.n_dev) return;  // replayed launch: this series slot is past the active list
   const int b = p.act ? p.act[bl] : p.s0 + bl;
   const int PT = p.PT, Hh = p.Hh, pts = p.pt_shift;
   const T* q = reinterpret_cast<const T*>(p.q);
@@ -219,6 +220,7 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
 __global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnP p) {
   const int lane = threadIdx.x;
   const int bl = blockIdx.x / p.Hh, h = blockIdx.x % p.Hh;
+  if (p.n_dev && bl >= *p.n_dev) return;  // replayed launch: this series slot is past the active list
   const int b = p.act ? p.act[bl] : p.s0 + bl;
   const bf16* q = reinterpret_cast<const bf16*>(p.q);
   bf16* out = reinterpret_cast<bf16*>(p.out);

@@ -58,7 +58,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   int* row_page = row_pos + BM;                                   // [BM] EP_QKV: its physical KV page
 
   const int tid = threadIdx.x;
-  const int M = p.M, N = p.N, K = p.K;
+  // rows of the product: fixed at launch, or capped by a device-side series count when the launch
+  // is replayed from a graph while series finish
+  const int M = p.n_dev ? min(p.M, *p.n_dev * p.nq) : p.M;
+  const int N = p.N, K = p.K;
   // Tile order.  Workgroups go round-robin to the 8 XCDs (each with its own L2), so workgroup
   // w lands on XCD w % 8.  Give every XCD one contiguous run of the tile list, and order the
   // list in groups of 8 tile columns walked row by row: the ~32 tiles an XCD runs at a time then
@@ -66,6 +69,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   const int tiles_m = p.tile_map ? p.n_mtiles : (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const int n_tiles = tiles_m * tiles_n;
   const int per_xcd = (n_tiles + 7) >> 3;
+  // (a replayed launch may be larger than the tile list: workgroups past an XCD's run must not
+  // wander into the next XCD's)
+  if ((int)(blockIdx.x >> 3) >= per_xcd) return;
   const int lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (lin >= n_tiles) return;
   constexpr int GW = 8;

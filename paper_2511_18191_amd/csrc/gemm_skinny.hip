@@ -52,7 +52,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const GemmP p) {
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int li = lane & 15, lg = lane >> 4;
-  const int M = p.M, N = p.N, K = p.K;
+  const int M = p.n_dev ? min(p.M, *p.n_dev * p.nq) : p.M;
+  const int N = p.N, K = p.K;
+  if (M <= 0) return;  // uniform: every series of a replayed launch has finished
 
   // ---- the 16 columns of this workgroup ----
   int col_of[2];  // first global column of LDS columns 0..7 and 8..15

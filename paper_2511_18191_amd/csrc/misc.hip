@@ -48,12 +48,24 @@ __device__ __forceinline__ double block_sum(double v, double* sh) {
   return t;
 }
 
+// Every series decodes again: the active list is the identity, its count the batch, and the
+// largest number of patches still needed is T.
+__device__ __forceinline__ void reset_active_list(const PrefillP& p, int b) {
+  if (!p.act_list) return;
+  p.act_list[b] = b;
+  if (b == 0) {
+    p.act_count[0] = p.batch;
+    p.act_count[1] = p.T;
+  }
+}
+
 __device__ __forceinline__ void init_state(const PrefillP& p, int b) {
   p.len[b] = p.N - 1;  // context patches 0..N-2 are cached; patch N-1 is pending at position N-1
   p.committed[b] = 0;
   p.round[b] = 0;
   p.active[b] = 1;
   for (int i = 0; i < 5; ++i) p.stat[(long)b * 5 + i] = 0;
+  reset_active_list(p, b);
 }
 
 __global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillP p) {
@@ -161,6 +173,7 @@ __device__ __forceinline__ float normal_draw(unsigned b, unsigned r, unsigned i,
 // Sampled proposals: X[b, i-1, :] = mu_q[b, i-1, :] + sigma_q * eps for the covered series, with
 // each series' own round counter.  One 64-thread block per series.
 __global__ __launch_bounds__(64) void sample_kernel(const SampleP p) {
+  if (p.n_dev && (int)blockIdx.x >= *p.n_dev) return;
   const int b = p.act ? p.act[blockIdx.x] : (int)blockIdx.x;
   const unsigned r = (unsigned)p.round[b];
   const long off = ((long)b * p.K + (p.i - 1)) * p.P;
@@ -179,6 +192,7 @@ hipError_t launch_sample(const SampleP& p, hipStream_t st) {
 // tokens and the cache lengths (rollback is metadata only: speculative KV entries past the
 // accepted length are simply overwritten by the next round).
 __global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
+  if (p.n_dev && (int)blockIdx.x >= *p.n_dev) return;
   const int b = p.act ? p.act[blockIdx.x] : (int)blockIdx.x, lane = threadIdx.x;
   const int K = p.K, P = p.P;
   const int KE = K > 0 ? K : 1;
@@ -353,6 +367,19 @@ __global__ void sum_stats_kernel(const long long* stat, int B, long long* out5) 
     if (threadIdx.x == 0) out5[j] = c[j];
   }
 }
+__global__ void identity_list_kernel(int* list, int* count, int B, int T) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) list[b] = b;
+  if (b == 0) {
+    count[0] = B;
+    count[1] = T;
+  }
+}
+hipError_t launch_identity_list(int* list, int* count, int B, int T, hipStream_t st) {
+  hipLaunchKernelGGL(identity_list_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, st, list, count, B, T);
+  return hipGetLastError();
+}
+
 hipError_t launch_sum_stats(const long long* stat, int B, long long* out5, hipStream_t st) {
   hipLaunchKernelGGL(sum_stats_kernel, dim3(1), dim3(64), 0, st, stat, B, out5);
   return hipGetLastError();

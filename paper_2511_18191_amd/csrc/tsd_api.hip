@@ -76,6 +76,7 @@ struct tsd_ctx {
   std::vector<int> host_pt;
   // captured launch sequences of tsd_round / tsd_target_step (rebuilt when anything they bake in changes)
   hipGraphExec_t graph_round[17] = {}, graph_step = nullptr;  // one round graph per number of positions
+  bool capturing = false;  // a graph capture of this handle's launches is in progress
   int k_round = 0;  // positions the next round proposes: min(K, most patches any active series still needs)
   // measurement tap: event pairs around every launch of one kernel family
   int* refill_list = nullptr;      // device copy of the slots of the last tsd_refill
@@ -316,6 +317,7 @@ struct Pass {
   int which;
   int B, s0, nq;
   const int* act;  // compacted pass over B listed series (NULL: series s0 .. s0+B-1)
+  const int* n_dev;  // device-side count of listed series (NULL: B)
   const int* base_pos;
   int pos_off;
   const float *src0, *src1;
@@ -346,6 +348,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
   g.stride1 = ps.stride1;
   g.n0 = ps.n0;
   g.act = ps.act;
+  g.n_dev = ps.n_dev;
   g.W = md.W_e;
   g.Cf = ctx->x;
   g.Cb = ctx->xb;
@@ -370,6 +373,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     q.pos_off = ps.pos_off;
     q.s0 = ps.s0;
     q.act = ps.act;
+    q.n_dev = ps.n_dev;
     q.rope_cos = md.rope_cos;
     q.rope_sin = md.rope_sin;
     q.D = D;
@@ -390,6 +394,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     a.pos_off = ps.pos_off;
     a.s0 = ps.s0;
     a.act = ps.act;
+    a.n_dev = ps.n_dev;
     a.nq = ps.nq;
     a.B = ps.B;
     a.Hh = md.c.n_heads;
@@ -407,6 +412,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     o.allow_skinny = ctx->skinny;
     o.M = M;
     o.nq = ps.nq;
+    o.n_dev = ps.n_dev;
     o.N = D;
     o.K = D;
     o.A = ctx->abuf;
@@ -464,6 +470,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     f1.allow_skinny = ctx->skinny;
     f1.M = M;
     f1.nq = ps.nq;
+    f1.n_dev = ps.n_dev;
     f1.N = F;
     f1.K = D;
     f1.A = xin;
@@ -475,6 +482,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     f2.allow_skinny = ctx->skinny;
     f2.M = M;
     f2.nq = ps.nq;
+    f2.n_dev = ps.n_dev;
     f2.N = D;
     f2.K = F;
     f2.A = ctx->hbuf;
@@ -497,6 +505,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     h.out_stride_b = ps.out_stride_b;
     h.t_skip = ps.t_skip;
     h.act = ps.act;
+    h.n_dev = ps.n_dev;
     HIP_TRY(ctx, timed_launch(ctx, TSD_K_HEAD, 2.0 * M * D * P, st, [&] { return launch_gemm(c.dtype, A_NORM32, EP_HEAD, h, st); }));
   }
   return TSD_OK;
@@ -507,10 +516,18 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
 struct Cover {
   const int* act;
   int n;
+  const int* n_dev;  // launches being captured into a graph: the count is read on the device at replay
 };
+// Dense models can replay one graph however many series are still active: the launches are sized
+// for the whole batch and every kernel caps its work by the device-side count that
+// tsd_num_active maintains (the routed FFN sizes its expert runs on the host, so it cannot).
+bool device_counts(const tsd_ctx* ctx) {
+  return !(ctx->cfg.flags & TSD_FLAG_NO_COMPACT) && ctx->cfg.target.n_experts == 0 && ctx->cfg.draft.n_experts == 0;
+}
 Cover cover(const tsd_ctx* ctx) {
-  if (ctx->n_act >= 0 && ctx->n_act < ctx->B) return Cover{ctx->act_list, ctx->n_act};
-  return Cover{nullptr, ctx->B};
+  if (ctx->capturing && device_counts(ctx)) return Cover{ctx->act_list, ctx->B, ctx->count_out};
+  if (ctx->n_act >= 0 && ctx->n_act < ctx->B) return Cover{ctx->act_list, ctx->n_act, nullptr};
+  return Cover{nullptr, ctx->B, nullptr};
 }
 
 void drop_graphs(tsd_ctx* ctx) {
@@ -530,13 +547,16 @@ void drop_graphs(tsd_ctx* ctx) {
 // itself capturing `st`, or when graphs are switched off.
 template <typename F>
 int run_graphed(tsd_ctx* ctx, hipGraphExec_t* slot, hipStream_t st, F body) {
-  if ((ctx->cfg.flags & TSD_FLAG_NO_GRAPH) || st == nullptr || ctx->prof_class >= 0 || cover(ctx).act) return body();
+  if ((ctx->cfg.flags & TSD_FLAG_NO_GRAPH) || st == nullptr || ctx->prof_class >= 0) return body();
+  if (cover(ctx).act && !device_counts(ctx)) return body();  // host-sized compacted passes cannot be replayed
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
   HIP_TRY(ctx, hipStreamIsCapturing(st, &cs));
   if (cs != hipStreamCaptureStatusNone) return body();
   if (!*slot) {
     HIP_TRY(ctx, hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+    ctx->capturing = true;
     int rc = body();
+    ctx->capturing = false;
     hipGraph_t graph = nullptr;
     hipError_t e = hipStreamEndCapture(st, &graph);
     if (rc) {
@@ -596,6 +616,7 @@ int accept_commit_impl(tsd_ctx* ctx, const int32_t* forced, int K, hipStream_t s
   if (cv.n == 0) return TSD_OK;
   a.B = cv.n;
   a.act = cv.act;
+  a.n_dev = cv.n_dev;
   a.K = K;
   a.P = c.patch;
   a.T = ctx->T;
@@ -809,7 +830,7 @@ int tsd_prefill(tsd_ctx* ctx, const float* series_dev, int32_t B, int32_t n_ctx_
     }
   HIP_TRY(ctx, hipMemcpyAsync(ctx->page_table, ctx->host_pt.data(), ctx->host_pt.size() * 4, hipMemcpyHostToDevice, st));
   PrefillP pp{series_dev, ctx->znorm, ctx->mean, ctx->sdev, ctx->pending, ctx->prev, ctx->len, ctx->committed,
-              ctx->round, ctx->active, ctx->stat, B, N, P};
+              ctx->round, ctx->active, ctx->stat, B, N, P, nullptr, 0, ctx->act_list, ctx->count_out, B, T};
   HIP_TRY(ctx, launch_prefill_stats(pp, st));
   ctx->B = B;
   ctx->N = N;
@@ -858,8 +879,10 @@ int tsd_refill(tsd_ctx* ctx, const int32_t* slots_host, int32_t n, const float* 
   ctx->host_refill.assign(slots_host, slots_host + n);
   HIP_TRY(ctx, hipMemcpyAsync(ctx->refill_list, ctx->host_refill.data(), (size_t)n * 4, hipMemcpyHostToDevice, st));
   PrefillP pp{series_dev, ctx->znorm, ctx->mean, ctx->sdev, ctx->pending, ctx->prev, ctx->len, ctx->committed,
-              ctx->round, ctx->active, ctx->stat, n, N, P, ctx->refill_list, 1};
+              ctx->round, ctx->active, ctx->stat, n, N, P, ctx->refill_list, 1, nullptr, nullptr, 0, 0};
   HIP_TRY(ctx, launch_prefill_stats(pp, st));
+  // every slot may be active again: identity list until the next tsd_num_active
+  HIP_TRY(ctx, launch_identity_list(ctx->act_list, ctx->count_out, ctx->B, ctx->T, st));
   const int nq = N - 1;
   const int chunk = std::max(1, ctx->rows_max / nq);
   for (int which = 0; which < 2; ++which)
@@ -887,7 +910,8 @@ int tsd_reset_decode(tsd_ctx* ctx, void* stream) {
   int rc = require_ready(ctx, true);
   if (rc) return rc;
   PrefillP pp{nullptr, ctx->znorm, ctx->mean, ctx->sdev, ctx->pending, ctx->prev, ctx->len, ctx->committed,
-              ctx->round, ctx->active, ctx->stat, ctx->B, ctx->N, ctx->cfg.patch};
+              ctx->round, ctx->active, ctx->stat, ctx->B, ctx->N, ctx->cfg.patch, nullptr, 0, ctx->act_list,
+              ctx->count_out, ctx->B, ctx->T};
   HIP_TRY(ctx, launch_reset(pp, (hipStream_t)stream));
   ctx->n_act = -1;  // every series is active again
   ctx->k_round = 0;
@@ -912,6 +936,7 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
   ps.which = TSD_DRAFT;
   ps.B = cv.n;
   ps.act = cv.act;
+  ps.n_dev = cv.n_dev;
   ps.nq = 2;
   ps.base_pos = ctx->len;
   ps.pos_off = -1;
@@ -931,6 +956,7 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
     sp.mu_q = ctx->mu_q;
     sp.X = ctx->X;
     sp.act = cv.act;
+    sp.n_dev = cv.n_dev;
     sp.round = ctx->round;
     sp.n = cv.n;
     sp.K = K;
@@ -953,6 +979,7 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
     ps.which = TSD_DRAFT;
     ps.B = cv.n;
     ps.act = cv.act;
+    ps.n_dev = cv.n_dev;
     ps.nq = 1;
     ps.base_pos = ctx->len;
     ps.pos_off = i - 1;
@@ -981,6 +1008,7 @@ int tsd_target_verify(tsd_ctx* ctx, void* stream) {
   ps.which = TSD_TARGET;
   ps.B = cv.n;
   ps.act = cv.act;
+  ps.n_dev = cv.n_dev;
   ps.nq = Kr + 1;
   ps.base_pos = ctx->len;
   ps.pos_off = 0;
@@ -1036,6 +1064,7 @@ int tsd_target_step(tsd_ctx* ctx, void* stream) {
     ps.which = TSD_TARGET;
     ps.B = cv.n;
     ps.act = cv.act;
+    ps.n_dev = cv.n_dev;
     ps.nq = 1;
     ps.base_pos = ctx->len;
     ps.pos_off = 0;

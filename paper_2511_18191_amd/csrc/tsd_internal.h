@@ -57,7 +57,9 @@ struct GemmP {
   const int* base_pos;  // per-series position of token 0 minus pos_off (NULL = 0)
   int pos_off;
   int s0;  // first series of this pass (chunked prefill)
-  const int* act;  // compacted pass: row block i belongs to series act[i] (NULL: series s0 + i)
+  const int* act;
+  // compacted pass: row block i belongs to series act[i] (NULL: series s0 + i)
+  const int* n_dev;  // device-side series count for launches replayed from a graph: rows = min(M, *n_dev * nq) (NULL: M)
   const float* rope_cos;
   const float* rope_sin;  // [max_tokens][hd/2]
   int D, Hh, hd, PT;
@@ -86,6 +88,7 @@ struct AttnP {
   int pos_off;
   int s0;
   const int* act;  // compacted pass: block i handles series act[i] (NULL: series s0 + i)
+  const int* n_dev;  // device-side series count (NULL: B): blocks of series >= *n_dev exit
   int nq, B, Hh, hd, D, PT;
   int pt_shift;  // log2(PT)
   int v_transposed;  // V block of a page is [head][dim][token] (bf16 head_dim-64 MFMA attention)
@@ -128,6 +131,9 @@ struct PrefillP {
   int B, N, P;
   const int* slots;     // refill: row j of `series` goes to slot slots[j] (NULL: slot j)
   int keep_counters;    // refill: the slot's round counter and statistics run on
+  int* act_list;        // prefill / reset: the active list becomes the identity ...
+  int* act_count;       // ... with count[0] = batch, count[1] = T (NULL: leave both alone)
+  int batch, T;
 };
 hipError_t launch_prefill_stats(const PrefillP& p, hipStream_t st);
 hipError_t launch_reset(const PrefillP& p, hipStream_t st);
@@ -138,6 +144,7 @@ struct AcceptP {
   const float* mu_p;  // [B][K+1][P]
   const int* forced;  // nullable
   const int* act;     // compacted round: block i handles series act[i] (NULL: series i)
+  const int* n_dev;   // device-side series count (NULL: B)
   float* pending;
   float* prev;
   float* forecast;    // [B][T*P] normalised
@@ -164,6 +171,7 @@ struct SampleP {  // X[b, i-1] = mu_q[b, i-1] + sigma_q * eps(b, round[b], i)
   const float* mu_q;
   float* X;
   const int* act;    // block j handles series act[j] (NULL: series j)
+  const int* n_dev;  // device-side series count (NULL: n)
   const int* round;
   int n, K, P, i;
   float sigma_q;
@@ -185,6 +193,8 @@ hipError_t launch_forecast_out(const float* forecast, const float* mean, const f
 // stable list of the series with active != 0; count[0] = how many, count[1] = max over them of T - committed
 hipError_t launch_compact_active(const int* active, const int* committed, int T, int B, int* list, int* count,
                                  hipStream_t st);
+// active list = identity, count[0] = B, count[1] = T
+hipError_t launch_identity_list(int* list, int* count, int B, int T, hipStream_t st);
 hipError_t launch_sum_stats(const long long* stat, int B, long long* out5, hipStream_t st);
 hipError_t launch_fill_nan(float* p, long n, hipStream_t st);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
