@@ -59,8 +59,7 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
 
   const int lane = threadIdx.x;
   const int bl = blockIdx.x / p.Hh, h = blockIdx.x % p.Hh;
-  if (p.n_dev && bl >= *p.n_dev) return;  // replayed launch: this series slot is past the active list
-  const int b = p.act ? p.act[bl] : p.s0 + bl;
+  const int b = p.act ? p.act[bl] : p.s0 + bl;  // (entries past the active count are stale but valid series)
   const int PT = p.PT, Hh = p.Hh, pts = p.pt_shift;
   const T* q = reinterpret_cast<const T*>(p.q);
   T* out = reinterpret_cast<T*>(p.out);
@@ -69,6 +68,7 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
   // base position, and the first chunk's queries.
   const int my_page = p.page_table[(long)b * p.pt_stride + min(lane, p.pt_stride - 1)];
   const int base = (p.base_pos ? p.base_pos[b] : 0) + p.pos_off;
+  if (p.n_dev && bl >= *p.n_dev) return;  // replayed launch: this slot is past the active list
   constexpr int QR = QC * HD / 64;
   float qreg[QR];
   {
@@ -220,13 +220,13 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
 __global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnP p) {
   const int lane = threadIdx.x;
   const int bl = blockIdx.x / p.Hh, h = blockIdx.x % p.Hh;
-  if (p.n_dev && bl >= *p.n_dev) return;  // replayed launch: this series slot is past the active list
-  const int b = p.act ? p.act[bl] : p.s0 + bl;
+  const int b = p.act ? p.act[bl] : p.s0 + bl;  // (entries past the active count are stale but valid series)
   const bf16* q = reinterpret_cast<const bf16*>(p.q);
   bf16* out = reinterpret_cast<bf16*>(p.out);
   const bf16* pool = reinterpret_cast<const bf16*>(p.kv_pool);
   const int my_page = p.page_table[(long)b * p.pt_stride + min(lane, p.pt_stride - 1)];
   const int base = (p.base_pos ? p.base_pos[b] : 0) + p.pos_off;
+  if (p.n_dev && bl >= *p.n_dev) return;  // replayed launch: this slot is past the active list
   for (int q0 = 0; q0 < p.nq; q0 += 16) {
     const int nqt = min(16, p.nq - q0);
     const bf16* qt = q + ((long)bl * p.nq + q0) * p.D + h * 64;

@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
 
   const int tid = threadIdx.x;
   // rows of the product: fixed at launch, or capped by a device-side series count when the launch
-  // is replayed from a graph while series finish
+  // is replayed from a graph while series finish (workgroups past the cap leave at once)
   const int M = p.n_dev ? min(p.M, *p.n_dev * p.nq) : p.M;
   const int N = p.N, K = p.K;
   // Tile order.  Workgroups go round-robin to the 8 XCDs (each with its own L2), so workgroup

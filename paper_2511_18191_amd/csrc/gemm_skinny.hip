@@ -52,9 +52,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const GemmP p) {
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int li = lane & 15, lg = lane >> 4;
-  const int M = p.n_dev ? min(p.M, *p.n_dev * p.nq) : p.M;
-  const int N = p.N, K = p.K;
-  if (M <= 0) return;  // uniform: every series of a replayed launch has finished
+  const int M = p.M, N = p.N, K = p.K;
 
   // ---- the 16 columns of this workgroup ----
   int col_of[2];  // first global column of LDS columns 0..7 and 8..15
@@ -192,7 +190,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const GemmP p) {
   // ---- reduce over wavefronts in a fixed order, then the epilogue: one thread per (row, 4 columns) ----
   if (tid >= kRowsMax * 4) return;
   const int row = tid >> 2, c4 = (tid & 3) * 4;
-  if (row >= M) return;
+  // a launch replayed from a graph stores only the rows of series that are still active
+  if (row >= (p.n_dev ? min(M, *p.n_dev * p.nq) : M)) return;
   const int gm = row;
   const int gn = col_of[c4 >> 3] + (c4 & 7);
   if (gn >= N) return;

@@ -522,7 +522,8 @@ struct Cover {
 // for the whole batch and every kernel caps its work by the device-side count that
 // tsd_num_active maintains (the routed FFN sizes its expert runs on the host, so it cannot).
 bool device_counts(const tsd_ctx* ctx) {
-  return !(ctx->cfg.flags & TSD_FLAG_NO_COMPACT) && ctx->cfg.target.n_experts == 0 && ctx->cfg.draft.n_experts == 0;
+  return !(ctx->cfg.flags & TSD_FLAG_NO_COMPACT) && ctx->cfg.target.n_experts == 0 && ctx->cfg.draft.n_experts == 0 &&
+         ctx->B > 1;
 }
 Cover cover(const tsd_ctx* ctx) {
   if (ctx->capturing && device_counts(ctx)) return Cover{ctx->act_list, ctx->B, ctx->count_out};
@@ -546,15 +547,15 @@ void drop_graphs(tsd_ctx* ctx) {
 // replayed afterwards.  Falls back to plain launches on the NULL stream, when the caller is
 // itself capturing `st`, or when graphs are switched off.
 template <typename F>
-int run_graphed(tsd_ctx* ctx, hipGraphExec_t* slot, hipStream_t st, F body) {
+int run_graphed(tsd_ctx* ctx, hipGraphExec_t* slot, hipStream_t st, F body, bool counts = true) {
   if ((ctx->cfg.flags & TSD_FLAG_NO_GRAPH) || st == nullptr || ctx->prof_class >= 0) return body();
-  if (cover(ctx).act && !device_counts(ctx)) return body();  // host-sized compacted passes cannot be replayed
+  if (cover(ctx).act && !(counts && device_counts(ctx))) return body();  // host-sized compacted passes cannot be replayed
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
   HIP_TRY(ctx, hipStreamIsCapturing(st, &cs));
   if (cs != hipStreamCaptureStatusNone) return body();
   if (!*slot) {
     HIP_TRY(ctx, hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
-    ctx->capturing = true;
+    ctx->capturing = counts;
     int rc = body();
     ctx->capturing = false;
     hipGraph_t graph = nullptr;
@@ -1077,7 +1078,7 @@ int tsd_target_step(tsd_ctx* ctx, void* stream) {
     int r = run_pass(ctx, ps, (hipStream_t)stream);
     if (r) return r;
     return accept_commit_impl(ctx, nullptr, 0, (hipStream_t)stream);  // K = 0: commit the target's mean
-  });
+  }, /*counts=*/false);  // target-only decoding finishes every series in the same step: nothing to compact
 }
 
 int tsd_num_active(tsd_ctx* ctx, int32_t* out_host, void* stream) {
