@@ -14,11 +14,6 @@
 
 namespace tsd {
 
-__device__ __forceinline__ float gelu_tanh(float z) {
-  const float c = 0.7978845608028654f;  // sqrt(2/pi)
-  return 0.5f * z * (1.0f + tanhf(c * (z + 0.044715f * z * z * z)));
-}
-
 template <typename T>
 __device__ __forceinline__ void store4(T* dst, float4 v);
 template <>

@@ -17,11 +17,6 @@ namespace tsd {
 
 namespace {
 
-__device__ __forceinline__ float gelu_tanh_s(float z) {
-  const float c = 0.7978845608028654f;  // sqrt(2/pi)
-  return 0.5f * z * (1.0f + tanhf(c * (z + 0.044715f * z * z * z)));
-}
-
 __device__ __forceinline__ void store4_bf16(bf16* dst, float4 v) {
   bf16x4 o;
   o[0] = (bf16)v.x;
@@ -233,10 +228,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const GemmP p) {
     *dst = o;
     if (p.Cb) store4_bf16(reinterpret_cast<bf16*>(p.Cb) + (long)gm * N + gn, o);
   } else if constexpr (EP == EP_GELU) {
-    v.x = gelu_tanh_s(v.x);
-    v.y = gelu_tanh_s(v.y);
-    v.z = gelu_tanh_s(v.z);
-    v.w = gelu_tanh_s(v.w);
+    v.x = gelu_tanh(v.x);
+    v.y = gelu_tanh(v.y);
+    v.z = gelu_tanh(v.z);
+    v.w = gelu_tanh(v.w);
     store4_bf16(reinterpret_cast<bf16*>(p.Ct) + (long)gm * N + gn, v);
   } else if constexpr (EP == EP_HEAD) {
     const int bl = gm / p.nq, t = gm % p.nq;
