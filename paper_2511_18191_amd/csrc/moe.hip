@@ -10,7 +10,6 @@ namespace tsd {
 
 constexpr int kMaxExperts = 16;
 constexpr int kMaxTopK = 4;
-constexpr size_t kPermuteLdsMax = 150 * 1024;  // expert ids of one pass staged in LDS
 
 // One wavefront per token.  x: fp32 residual rows [M][D]; Wr: fp32 [E][D] with the norm gain folded.
 __global__ __launch_bounds__(64) void router_kernel(const float* x, const float* Wr, int M, int D, int E, int topk,
@@ -81,44 +80,82 @@ __global__ __launch_bounds__(64) void router_kernel(const float* x, const float*
   }
 }
 
-// One block, one wavefront per expert.  Assignment a = token * topk + choice.  The expert ids are
-// first copied into LDS with every load in flight; the two scans (count, then place) run from LDS.
+// One block of 1024 lanes: a stable counting sort of the assignments a = token * topk + choice by
+// expert.  Lane t owns the contiguous run of assignments [t * per, (t + 1) * per), so "earlier lane,
+// then earlier position" is assignment order and the sort is stable.  Per expert: counts per lane,
+// an exclusive scan over the lanes of a wavefront (shuffles) and over the wavefronts (LDS), then
+// every lane places its own run.  The tile map of the grouped GEMMs (one entry per BM-row tile of
+// an expert's run of slots) is written by one lane per tile.
 __global__ __launch_bounds__(1024) void permute_kernel(const int* ids, int n_assign, int topk, int E, int BM, int n_mtiles,
                                                        int* src_row, int* slot_of, int4* tile_map) {
-  extern __shared__ int lds_ids[];  // [n_assign]
-  __shared__ int cnt[kMaxExperts], beg[kMaxExperts + 1];
-  for (int a = threadIdx.x; a < n_assign; a += blockDim.x) lds_ids[a] = ids[a];
-  __syncthreads();
-  const int e = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  int c = 0;
-  for (int a0 = 0; a0 < n_assign; a0 += 64) {
-    const int a = a0 + lane;
-    c += __popcll(__ballot(a < n_assign && lds_ids[a] == e));
+  __shared__ int wave_tot[16][kMaxExperts];  // assignments of expert e in wavefront w
+  __shared__ int beg[kMaxExperts + 1];       // first slot of expert e
+  __shared__ int tile_beg[kMaxExperts + 1];  // first tile of expert e
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int per = (n_assign + 1023) / 1024;
+  const int a0 = min(t * per, n_assign), a1 = min(a0 + per, n_assign);
+  int cnt[kMaxExperts];
+#pragma unroll
+  for (int e = 0; e < kMaxExperts; ++e) cnt[e] = 0;
+  for (int a = a0; a < a1; ++a) {
+    const int id = ids[a];
+#pragma unroll
+    for (int e = 0; e < kMaxExperts; ++e) cnt[e] += (id == e) ? 1 : 0;
   }
-  if (lane == 0) cnt[e] = c;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int run = 0, t = 0;
-    for (int i = 0; i < E; ++i) {
-      beg[i] = run;
-      for (int r0 = 0; r0 < cnt[i]; r0 += BM) tile_map[t++] = make_int4(i, run + r0, run + cnt[i], 0);
-      run += cnt[i];
+  // exclusive prefix of cnt[e] over the lanes of this wavefront, and the wavefront's total
+  int start[kMaxExperts];
+#pragma unroll
+  for (int e = 0; e < kMaxExperts; ++e) {
+    int incl = cnt[e];
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
     }
-    beg[E] = run;
-    for (; t < n_mtiles; ++t) tile_map[t] = make_int4(-1, 0, 0, 0);
+    start[e] = incl - cnt[e];
+    if (lane == 63) wave_tot[w][e] = incl;
   }
   __syncthreads();
-  int pos = beg[e];
-  for (int a0 = 0; a0 < n_assign; a0 += 64) {
-    const int a = a0 + lane;
-    const bool mine = a < n_assign && lds_ids[a] == e;
-    const unsigned long long m = __ballot(mine);
-    if (mine) {
-      const int slot = pos + __popcll(m & ((1ull << lane) - 1ull));
-      src_row[slot] = a / topk;
-      slot_of[a] = slot;
+  if (t == 0) {
+    int run = 0, tiles = 0;
+    for (int e = 0; e < kMaxExperts; ++e) {
+      int c = 0;
+      for (int i = 0; i < 16; ++i) c += wave_tot[i][e];
+      beg[e] = run;
+      tile_beg[e] = tiles;
+      run += c;
+      tiles += (c + BM - 1) / BM;
     }
-    pos += __popcll(m);
+    beg[kMaxExperts] = run;
+    tile_beg[kMaxExperts] = tiles;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < kMaxExperts; ++e) {
+    int base = beg[e];
+    for (int i = 0; i < w; ++i) base += wave_tot[i][e];
+    start[e] += base;
+  }
+  for (int a = a0; a < a1; ++a) {
+    const int id = ids[a];
+    int slot = 0;
+#pragma unroll
+    for (int e = 0; e < kMaxExperts; ++e)
+      if (id == e) {
+        slot = start[e];
+        start[e] += 1;
+      }
+    src_row[slot] = a / topk;
+    slot_of[a] = slot;
+  }
+  // tile map: tile j belongs to the expert e with tile_beg[e] <= j < tile_beg[e + 1]
+  for (int j = t; j < n_mtiles; j += 1024) {
+    int4 entry = make_int4(-1, 0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < kMaxExperts; ++e)
+      if (e < E && j >= tile_beg[e] && j < tile_beg[e + 1])
+        entry = make_int4(e, beg[e] + (j - tile_beg[e]) * BM, beg[e + 1], 0);
+    tile_map[j] = entry;
   }
 }
 
@@ -146,11 +183,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* Y, const int*
   }
 }
 
-// More than 64 KB of dynamic LDS needs a one-time opt-in (done at handle creation).
-hipError_t prepare_moe() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&permute_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)kPermuteLdsMax);
-}
+hipError_t prepare_moe() { return hipSuccess; }  // (nothing to opt into any more)
 
 hipError_t launch_router(const float* x, const float* Wr, int M, int D, int E, int topk, int* ids, float* gates,
                          hipStream_t st) {
@@ -161,8 +194,8 @@ hipError_t launch_router(const float* x, const float* Wr, int M, int D, int E, i
 
 hipError_t launch_permute(const int* ids, int n_assign, int topk, int E, int BM, int n_mtiles, int* src_row,
                           int* slot_of, void* tile_map, hipStream_t st) {
-  if (E > kMaxExperts || (size_t)n_assign * 4 > kPermuteLdsMax) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(64 * E), (size_t)n_assign * 4, st, ids, n_assign, topk, E, BM, n_mtiles, src_row, slot_of,
+  if (E > kMaxExperts || n_assign < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(1024), 0, st, ids, n_assign, topk, E, BM, n_mtiles, src_row, slot_of,
                      reinterpret_cast<int4*>(tile_map));
   return hipGetLastError();
 }
