@@ -84,21 +84,35 @@ __global__ __launch_bounds__(64) void router_kernel(const float* x, const float*
 // expert.  Lane t owns the contiguous run of assignments [t * per, (t + 1) * per), so "earlier lane,
 // then earlier position" is assignment order and the sort is stable.  Per expert: counts per lane,
 // an exclusive scan over the lanes of a wavefront (shuffles) and over the wavefronts (LDS), then
-// every lane places its own run.  The tile map of the grouped GEMMs (one entry per BM-row tile of
-// an expert's run of slots) is written by one lane per tile.
+// every lane places its own run.  The expert ids are first staged in LDS (one byte each) by
+// coalesced loads, eight in flight per lane: read straight from memory, a lane's run would be a
+// chain of dependent-latency loads.  The tile map of the grouped GEMMs (one entry per BM-row tile
+// of an expert's run of slots) is written by one lane per tile.
 __global__ __launch_bounds__(1024) void permute_kernel(const int* ids, int n_assign, int topk, int E, int BM, int n_mtiles,
                                                        int* src_row, int* slot_of, int4* tile_map) {
-  __shared__ int wave_tot[16][kMaxExperts];  // assignments of expert e in wavefront w
+  extern __shared__ unsigned char lds_id[];   // [n_assign]
+  __shared__ int wave_tot[16][kMaxExperts];   // assignments of expert e in wavefront w
+  __shared__ int wave_base[16][kMaxExperts];  // ... in the wavefronts before w
+  __shared__ int tot[kMaxExperts];
   __shared__ int beg[kMaxExperts + 1];       // first slot of expert e
   __shared__ int tile_beg[kMaxExperts + 1];  // first tile of expert e
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  for (int a = t; a < n_assign; a += 8 * 1024) {
+    int v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = ids[min(a + u * 1024, n_assign - 1)];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (a + u * 1024 < n_assign) lds_id[a + u * 1024] = (unsigned char)v[u];
+  }
+  __syncthreads();
   const int per = (n_assign + 1023) / 1024;
   const int a0 = min(t * per, n_assign), a1 = min(a0 + per, n_assign);
   int cnt[kMaxExperts];
 #pragma unroll
   for (int e = 0; e < kMaxExperts; ++e) cnt[e] = 0;
   for (int a = a0; a < a1; ++a) {
-    const int id = ids[a];
+    const int id = lds_id[a];
 #pragma unroll
     for (int e = 0; e < kMaxExperts; ++e) cnt[e] += (id == e) ? 1 : 0;
   }
@@ -116,28 +130,47 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int* ids, int n_ass
     if (lane == 63) wave_tot[w][e] = incl;
   }
   __syncthreads();
-  if (t == 0) {
-    int run = 0, tiles = 0;
-    for (int e = 0; e < kMaxExperts; ++e) {
-      int c = 0;
-      for (int i = 0; i < 16; ++i) c += wave_tot[i][e];
-      beg[e] = run;
-      tile_beg[e] = tiles;
-      run += c;
-      tiles += (c + BM - 1) / BM;
+  // Scans over the 16 wavefronts (per expert) and over the 16 experts, by lanes rather than by one
+  // lane walking LDS: 256 lanes hold (expert, wavefront) pairs, 16 consecutive lanes per expert.
+  if (t < 256) {
+    const int e = t >> 4, i = t & 15;
+    const int v = wave_tot[i][e];
+    int incl = v;
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) {
+      const int up = __shfl_up(incl, o, 16);
+      if (i >= o) incl += up;
     }
-    beg[kMaxExperts] = run;
-    tile_beg[kMaxExperts] = tiles;
+    wave_base[i][e] = incl - v;
+    if (i == 15) tot[e] = incl;
+  }
+  __syncthreads();
+  if (t < 64) {
+    const int c = t < kMaxExperts ? tot[t] : 0;
+    const int tl = (c + BM - 1) / BM;
+    int ic = c, it = tl;
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) {
+      const int uc = __shfl_up(ic, o, 16), ut = __shfl_up(it, o, 16);
+      if ((t & 15) >= o) {
+        ic += uc;
+        it += ut;
+      }
+    }
+    if (t < kMaxExperts) {
+      beg[t] = ic - c;
+      tile_beg[t] = it - tl;
+      if (t == kMaxExperts - 1) {
+        beg[kMaxExperts] = ic;
+        tile_beg[kMaxExperts] = it;
+      }
+    }
   }
   __syncthreads();
 #pragma unroll
-  for (int e = 0; e < kMaxExperts; ++e) {
-    int base = beg[e];
-    for (int i = 0; i < w; ++i) base += wave_tot[i][e];
-    start[e] += base;
-  }
+  for (int e = 0; e < kMaxExperts; ++e) start[e] += beg[e] + wave_base[w][e];
   for (int a = a0; a < a1; ++a) {
-    const int id = ids[a];
+    const int id = lds_id[a];
     int slot = 0;
 #pragma unroll
     for (int e = 0; e < kMaxExperts; ++e)
@@ -183,7 +216,12 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* Y, const int*
   }
 }
 
-hipError_t prepare_moe() { return hipSuccess; }  // (nothing to opt into any more)
+constexpr size_t kPermuteLdsMax = 144 * 1024;  // one byte per assignment
+// More than 64 KB of dynamic LDS needs a one-time opt-in (done at handle creation).
+hipError_t prepare_moe() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&permute_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)kPermuteLdsMax);
+}
 
 hipError_t launch_router(const float* x, const float* Wr, int M, int D, int E, int topk, int* ids, float* gates,
                          hipStream_t st) {
@@ -194,8 +232,8 @@ hipError_t launch_router(const float* x, const float* Wr, int M, int D, int E, i
 
 hipError_t launch_permute(const int* ids, int n_assign, int topk, int E, int BM, int n_mtiles, int* src_row,
                           int* slot_of, void* tile_map, hipStream_t st) {
-  if (E > kMaxExperts || n_assign < 1) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(1024), 0, st, ids, n_assign, topk, E, BM, n_mtiles, src_row, slot_of,
+  if (E > kMaxExperts || n_assign < 1 || (size_t)n_assign > kPermuteLdsMax) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(1024), (size_t)((n_assign + 15) & ~15), st, ids, n_assign, topk, E, BM, n_mtiles, src_row, slot_of,
                      reinterpret_cast<int4*>(tile_map));
   return hipGetLastError();
 }

@@ -152,6 +152,9 @@ int check_config(const tsd_config* c, std::string& why) {
   if ((c->max_tokens + c->page_tokens - 1) / c->page_tokens > 64)
     return bad("max_tokens / page_tokens must not exceed 64 pages per series");
   for (const tsd_model_cfg* m : {&c->target, &c->draft})
+    if (m->n_experts > 0 && (size_t)std::max((long)c->max_batch * (c->K + 1), (long)c->max_tokens) * m->top_k > 144 * 1024)
+      return bad("max_batch * (K + 1) * top_k too large for the expert sort (one byte per assignment in 144 KB of LDS)");
+  for (const tsd_model_cfg* m : {&c->target, &c->draft})
     if (attention_lds_bytes(c->dtype, m->d_model / m->n_heads, c->max_tokens, c->page_tokens) > 160 * 1024)
       return bad("max_tokens too large: one head's K and V rows must fit the 160 KB of LDS");
   return TSD_OK;
