@@ -30,8 +30,9 @@ __device__ __forceinline__ void store4<bf16>(bf16* dst, float4 v) {
   *reinterpret_cast<bf16x4*>(dst) = o;
 }
 
-template <typename T, int AM, int EP, int BM, int BN, int BK>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
+template <typename T, int AM, int EP, int BM, int BN, int BK, int G = 1>
+__global__ __launch_bounds__(256 * G) void gemm_kernel(const GemmP p) {
+  constexpr int NT = 256 * G;
   constexpr bool kBf = !std::is_same<T, float>::value;
   constexpr bool kNorm = (AM == A_NORM || AM == A_NORM32);  // RMSNorm fused as a row scale
   // fp32 A rows in bf16 mode (patches, and the residual feeding the output head) are split into
@@ -41,18 +42,21 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   constexpr int NAS = kSplit ? 2 : 1;  // A tiles kept in LDS per buffer
   constexpr int LDT = BK + (kBf ? 8 : 1);  // padded LDS row, in elements
   constexpr int LDC = BN + 4;
-  constexpr int AB_BYTES = 2 * (NAS * BM + BN) * LDT * (int)sizeof(T);
-  constexpr int C_BYTES = 64 * LDC * 4;
+  static_assert(G == 1 || (kBf && BM == 64 && !kNorm), "split workgroups: bf16, 64-row tiles, no fused norm");
+  constexpr int GROUP_ELEMS = 2 * (NAS * BM + BN) * LDT;  // one group's pair of tile buffers
+  constexpr int AB_BYTES = G * GROUP_ELEMS * (int)sizeof(T);
+  constexpr int C_BYTES = G * 64 * LDC * 4;
   constexpr int SMEM = AB_BYTES > C_BYTES ? AB_BYTES : C_BYTES;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // SMEM + BM * 12 bytes
-  T* As = reinterpret_cast<T*>(smem);  // [2][NAS][BM][LDT]
+  const int tid = threadIdx.x;
+  const int grp = G > 1 ? tid >> 8 : 0, gt = tid & 255;  // group of 4 wavefronts, lane index inside it
+  T* As = reinterpret_cast<T*>(smem) + grp * GROUP_ELEMS;  // [2][NAS][BM][LDT] per group
   T* Bs = As + 2 * NAS * BM * LDT;     // [2][BN][LDT]
-  float* Cs = reinterpret_cast<float*>(smem);  // [64][LDC], reuses the tile buffers
+  float* Cs = reinterpret_cast<float*>(smem);  // [G][64][LDC], reuses the tile buffers
   float* row_scale = reinterpret_cast<float*>(smem + SMEM);  // [BM]
   int* row_pos = reinterpret_cast<int*>(smem + SMEM + BM * 4);   // [BM] EP_QKV: absolute position of the row's token
   int* row_page = row_pos + BM;                                   // [BM] EP_QKV: its physical KV page
 
-  const int tid = threadIdx.x;
   // rows of the product: fixed at launch, or capped by a device-side series count when the launch
   // is replayed from a graph while series finish (workgroups past the cap leave at once)
   const int M = p.n_dev ? min(p.M, *p.n_dev * p.nq) : p.M;
@@ -95,7 +99,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   float ss[NA];
 #pragma unroll
   for (int i = 0; i < NA; ++i) {
-    int id = tid + i * 256;
+    int id = gt + i * 256;
     a_r[i] = id / CPRA;
     a_kc[i] = id % CPRA;
     ss[i] = 0.f;
@@ -126,7 +130,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   int b_r[NB], b_kc[NB];
 #pragma unroll
   for (int i = 0; i < NB; ++i) {
-    int id = tid + i * 256;
+    int id = gt + i * 256;
     b_r[i] = id / CPRB;
     b_kc[i] = id % CPRB;
     int gn = min(n0 + b_r[i], N - 1);  // clamped like the rows of A
@@ -201,7 +205,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   };
 
   // ---- accumulators -------------------------------------------------------------------------
-  const int lane = tid & 63, wid = tid >> 6;
+  const int lane = tid & 63, wid = (tid >> 6) & 3;
   const int wm = wid >> 1, wn = wid & 1;
   constexpr int WTM = BM / 2, WTN = BN / 2;            // wave tile (bf16 path)
   constexpr int TM = kBf ? WTM / 32 : 1, TN = kBf ? WTN / 32 : 1;
@@ -221,7 +225,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) accf[i][j] = 0.f;
   }
-  const int ty = tid >> 4, tx = tid & 15;  // fp32 path: 4x4 micro-tile at (ty*4, tx*4)
+  const int ty = gt >> 4, tx = gt & 15;  // fp32 path: 4x4 micro-tile at (ty*4, tx*4)
 
   // ---- main loop ----------------------------------------------------------------------------
   auto compute = [&](int buf) {
@@ -264,8 +268,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
     }
   };
   const int nk = (K + BK - 1) / BK;
-  load_global(0, ra0, rb0);
-  load_global(min(1, nk - 1), ra1, rb1);
+  // Split workgroup: group g walks the g-th run of ceil(nk / G) k-steps with its own tile buffers and
+  // accumulators (steps past K multiply zeros, so every group meets the same barriers); the epilogue
+  // adds the G partial products in group order.
+  const int nkl = G > 1 ? (nk + G - 1) / G : nk;  // k-steps this group walks
+  const int kt0 = G > 1 ? grp * nkl : 0;
+  load_global(kt0, ra0, rb0);
+  load_global(kt0 + 1, ra1, rb1);
   // Epilogue inputs that do not depend on the product are requested now, so their latency hides
   // behind the main loop: the KV position/page of each row (QKV), the old residual values (RESID).
   int my_pos = 0, my_page = 0;
@@ -278,37 +287,37 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
     }
   }
   constexpr bool kPrefetchC = (EP == EP_RESID) && BM == 64;
-  constexpr int NPRE = kPrefetchC ? 64 * (BN / 4) / 256 : 1;
+  constexpr int NPRE = kPrefetchC ? 64 * (BN / 4) / NT : 1;
   float4 oldc[NPRE];
   if constexpr (kPrefetchC) {
 #pragma unroll
     for (int it = 0; it < NPRE; ++it) {
-      const int g = tid + it * 256;
+      const int g = tid + it * NT;
       const int gm = min(m0 + g / (BN / 4), m_lim - 1), gn = min(n0 + (g % (BN / 4)) * 4, N - 4);
       oldc[it] = *reinterpret_cast<const float4*>(p.Cf + (long)gm * N + gn);
     }
   }
-  store_lds(0, 0, ra0, rb0);
+  store_lds(kt0, 0, ra0, rb0);
   __syncthreads();
-  int kt = 0;
+  int kt = 0;  // k-steps done, counted from kt0
   // Steady state, two tiles per trip and no branches inside: tile kt sits in LDS buffer 0, register
   // set 1 holds tile kt+1 (in flight), set 0 is free.  The scheduling barriers keep each prefetch
   // ahead of the MFMA work it is meant to overlap.
-  for (; kt + 2 < nk; kt += 2) {
-    load_global(kt + 2, ra0, rb0);
+  for (; kt + 2 < nkl; kt += 2) {
+    load_global(kt0 + kt + 2, ra0, rb0);
     __builtin_amdgcn_sched_barrier(0);
     compute(0);
-    store_lds(kt + 1, 1, ra1, rb1);
+    store_lds(kt0 + kt + 1, 1, ra1, rb1);
     __syncthreads();
-    load_global(min(kt + 3, nk - 1), ra1, rb1);
+    load_global(kt0 + kt + 3, ra1, rb1);
     __builtin_amdgcn_sched_barrier(0);
     compute(1);
-    store_lds(kt + 2, 0, ra0, rb0);
+    store_lds(kt0 + kt + 2, 0, ra0, rb0);
     __syncthreads();
   }
   compute(0);
-  if (kt + 1 < nk) {
-    store_lds(kt + 1, 1, ra1, rb1);
+  if (kt + 1 < nkl) {
+    store_lds(kt0 + kt + 1, 1, ra1, rb1);
     __syncthreads();
     compute(1);
   }
@@ -331,6 +340,24 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   }
 
   // ---- epilogue, 64 rows at a time through LDS ----------------------------------------------
+  auto read_c1 = [&](int row, int col) {  // one element / four consecutive elements of the product
+    float v = Cs[row * LDC + col];
+#pragma unroll
+    for (int g = 1; g < G; ++g) v += Cs[(g * 64 + row) * LDC + col];
+    return v;
+  };
+  auto read_c4 = [&](int row, int col) {
+    float4 v = *reinterpret_cast<const float4*>(Cs + row * LDC + col);
+#pragma unroll
+    for (int g = 1; g < G; ++g) {
+      const float4 w = *reinterpret_cast<const float4*>(Cs + (g * 64 + row) * LDC + col);
+      v.x += w.x;
+      v.y += w.y;
+      v.z += w.z;
+      v.w += w.w;
+    }
+    return v;
+  };
   for (int pass = 0; pass < BM / 64; ++pass) {
     __syncthreads();  // tile buffers (or the previous pass's Cs) are no longer read
     if constexpr (kBf) {
@@ -345,7 +372,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
             for (int r = 0; r < 16; ++r) {
               int row = rbase + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
               int col = wn * WTN + j * 32 + (lane & 31);
-              Cs[row * LDC + col] = acc[i][j][r];
+              Cs[(grp * 64 + row) * LDC + col] = acc[i][j][r];
             }
       }
     } else {
@@ -362,7 +389,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
       // 128-byte line of the block, so a store instruction touches a handful of lines instead of
       // sixteen (the cache sees ~5x fewer write requests than with 4-dim groups per lane).
       if (p.v_transposed && n0 >= 2 * p.D) {
-        const int w16 = (tid >> 6) * 16 + (tid & 15);  // this lane's row of the 64-row pass
+        const int w16 = ((tid >> 6) & 3) * 16 + (tid & 15);  // this lane's row of the 64-row pass
         const int rs_row = pass * 64 + w16;
         const int gm = m0 + rs_row;
         if (gm < m_lim) {
@@ -370,12 +397,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
           const int pos = row_pos[rs_row], page = row_page[rs_row];
           T* blk = reinterpret_cast<T*>(p.kv_pool) + ((long)page * 2 + 1) * p.Hh * p.PT * 64 + (pos & (p.PT - 1));
 #pragma unroll 4
-          for (int it = 0; it < BN / 4; ++it) {
+          for (int it = grp * (BN / 4 / G); it < (grp + 1) * (BN / 4 / G); ++it) {
             const int col = it * 4 + ((tid >> 4) & 3);
             const int gn = n0 + col;
             if (gn >= N) continue;
             const int c = gn - 2 * p.D;  // column inside V: head c / 64, dim c % 64
-            blk[(long)(c >> 6) * p.PT * 64 + (long)(c & 63) * p.PT] = (T)(Cs[w16 * LDC + col] * rs);
+            blk[(long)(c >> 6) * p.PT * 64 + (long)(c & 63) * p.PT] = (T)(read_c1(w16, col) * rs);
           }
         }
         continue;
@@ -383,12 +410,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
     }
     constexpr int GPR = BN / 4;  // 4-column groups per row
 #pragma unroll
-    for (int it = 0; it < 64 * GPR / 256; ++it) {
-      const int g = tid + it * 256;
+    for (int it = 0; it < 64 * GPR / NT; ++it) {
+      const int g = tid + it * NT;
       const int row = g / GPR, col = (g % GPR) * 4;
       const int gm = m0 + pass * 64 + row, gn = n0 + col;
       if (gm >= m_lim || gn >= N) continue;
-      float4 v = *reinterpret_cast<const float4*>(Cs + row * LDC + col);
+      float4 v = read_c4(row, col);
       float rs = 1.f;
       if constexpr (kNorm) {
         rs = row_scale[pass * 64 + row];
@@ -428,7 +455,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
         if (which < 2) {
           const bool lo = d < half;
           const int pcol = lo ? col + half : col - half;
-          float4 pv = *reinterpret_cast<const float4*>(Cs + row * LDC + pcol);
+          float4 pv = read_c4(row, pcol);
           const int f = lo ? d : d - half;
           const float4 cs = *reinterpret_cast<const float4*>(p.rope_cos + (long)pos * half + f);
           const float4 sn = *reinterpret_cast<const float4*>(p.rope_sin + (long)pos * half + f);
@@ -460,21 +487,21 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   }
 }
 
-template <typename T, int AM, int BM, int BN, int BK>
+template <typename T, int AM, int BM, int BN, int BK, int G = 1>
 constexpr size_t gemm_smem_bytes() {
   constexpr bool kBf = !std::is_same<T, float>::value;
   constexpr int LDT = BK + (kBf ? 8 : 1);
   constexpr int nas = (kBf && (AM == A_TOK || AM == A_NORM32)) ? 2 : 1;
-  constexpr size_t ab = 2 * (nas * BM + BN) * LDT * sizeof(T), c = 64 * (BN + 4) * 4;
+  constexpr size_t ab = (size_t)G * 2 * (nas * BM + BN) * LDT * sizeof(T), c = (size_t)G * 64 * (BN + 4) * 4;
   return (ab > c ? ab : c) + BM * 12;
 }
 
-template <typename T, int AM, int EP, int BM, int BN, int BK>
+template <typename T, int AM, int EP, int BM, int BN, int BK, int G = 1>
 static hipError_t launch_tile(const GemmP& p, hipStream_t st) {
-  constexpr size_t smem = gemm_smem_bytes<T, AM, BM, BN, BK>();
+  constexpr size_t smem = gemm_smem_bytes<T, AM, BM, BN, BK, G>();
   const long tiles = (long)(p.tile_map ? p.n_mtiles : (p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
   const unsigned grid = (unsigned)(((tiles + 7) / 8) * 8);  // padded so that every XCD gets a full run
-  hipLaunchKernelGGL((gemm_kernel<T, AM, EP, BM, BN, BK>), dim3(grid), dim3(256), smem, st, p);
+  hipLaunchKernelGGL((gemm_kernel<T, AM, EP, BM, BN, BK, G>), dim3(grid), dim3(256 * G), smem, st, p);
   return hipGetLastError();
 }
 
@@ -486,11 +513,25 @@ int gemm_row_tile(int dtype, int M, int N, int force_bm) {
   return t128 >= 192 ? 128 : 64;
 }
 
+// A long contraction with too few 64 x 64 tiles to cover the chip is bound by how fast the few busy
+// compute units can pull their operand panels: such a product runs with 1024-lane workgroups whose
+// four groups of wavefronts each stream a quarter of K (four times the loads in flight per unit, a
+// quarter of the serial k-steps).  The partial sums are added in a fixed order, so the result does
+// not depend on timing; it differs in the last bits from the single-group kernel's, which is why
+// the choice depends on the shape of the product alone.
+static bool gemm_split(const GemmP& p) {
+  const long t64 = (long)(p.tile_map ? p.n_mtiles : (p.M + 63) / 64) * ((p.N + 63) / 64);
+  return p.K >= 1024 && t64 <= 192;
+}
+
 template <typename T, int AM, int EP>
 static hipError_t launch_cfg(const GemmP& p, hipStream_t st) {
   constexpr bool kBf = !std::is_same<T, float>::value;
   if constexpr (kBf) {
     if (gemm_row_tile(TSD_BF16, p.M, p.N, p.force_bm) == 128) return launch_tile<T, AM, EP, 128, 128, 64>(p, st);
+    if constexpr (AM == A_ACT) {
+      if (gemm_split(p)) return launch_tile<T, AM, EP, 64, 64, 64, 4>(p, st);
+    }
     return launch_tile<T, AM, EP, 64, 64, 64>(p, st);
   } else {
     return launch_tile<T, AM, EP, 64, 64, 16>(p, st);
@@ -500,6 +541,11 @@ static hipError_t launch_cfg(const GemmP& p, hipStream_t st) {
 template <typename T, int AM, int EP>
 static hipError_t raise_cfg() {
   if constexpr (!std::is_same<T, float>::value) {
+    if constexpr (AM == A_ACT) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, AM, EP, 64, 64, 64, 4>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_smem_bytes<T, AM, 64, 64, 64, 4>());
+      if (e != hipSuccess) return e;
+    }
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, AM, EP, 128, 128, 64>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_smem_bytes<T, AM, 128, 128, 64>());
   }
