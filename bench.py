@@ -82,8 +82,8 @@ def phase_times(torch, sess, reps=20):
 
 # HBM bytes per launch of each kernel family from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by the
 # copy-kernel calibration (profiles/traffic_cfg2_bench.md has the commands, raw values and factors)
-TRAFFIC = {"cfg2": {"resid": 7927537, "qkv": 8140259, "gelu": 6174597, "attn": 11248708, "head": 1098586,
-                    "embed": 1238448, "accept": 813759}}
+TRAFFIC = {"cfg2": {"resid": 8360400, "qkv": 8588061, "gelu": 6448329, "attn": 11916056, "head": 1221537,
+                    "embed": 1361866, "accept": 797552}}
 PEAK = {"bf16": 2500.0, "fp32": 157.3}   # dense MFMA bf16 / vector fp32, TFLOP/s
 HBM_PEAK = 8000.0                        # GB/s
 
