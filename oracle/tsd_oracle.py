@@ -30,7 +30,10 @@ mixing matrices are zero; causality; single pass == K+1 passes; brute force over
 patterns; draft == target; sigma -> 0; the capped-geometric block-length law (Eq. 7); for the
 sampled variants a Kolmogorov-Smirnov test of the normal draws, the equal-covariance closed form
 2 Phi(-Delta/2) of the unscaled stochastic rule, a quadrature of the tempered rule's mean
-acceptance, and the fallback-noise energy r^2.
+acceptance, and the fallback-noise energy r^2; for the threshold rule its equivalence to the
+ratio rule under the constant draw u = exp(-1/2) and a hand-built boundary case; for the
+batch-synchronised loop the reduction to the unsynchronised one at batch 1 and on identical series,
+and the per-round minimum recomputed from each series' own record.
 The full transformer forward has no external reference value to compare against: beyond
 those structural pins it is "parity unpinned".
 """
@@ -252,8 +255,18 @@ def log_ratio_diag(x, mu_p, mu_q, s_p, s_q):
     return -0.5 * maha_p + 0.5 * maha_q + logdet / (2.0 * d)
 
 
+def within_threshold(x, mu_p, sigma_p):
+    """Deterministic acceptance of the standalone TiRex-style variant (Table "TiRex configuration",
+    row "Acceptance draw"): a proposal passes iff its scaled squared distance from the target's
+    prediction, ||x - mu_p||_d^2 = ||x - mu_p||^2 / d, is at most sigma^2 (per-dimension scales:
+    the scaled Mahalanobis distance is at most 1)."""
+    if np.ndim(sigma_p):
+        return energy((x - mu_p) / np.asarray(sigma_p, dtype=np.float64)) <= 1.0
+    return energy(x - mu_p) <= sigma_p * sigma_p
+
+
 def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True, alpha_override=None,
-               eps_fn=None, sample_proposals=False, fallback_r=0.0):
+               eps_fn=None, sample_proposals=False, fallback_r=0.0, rule="ratio"):
     """One speculative round for one series.
 
     hist: [n, P] normalised history (context patches then committed patches).
@@ -267,9 +280,15 @@ def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True
     deployed mean-propagating scheme (x_i = mu_q^(i), t = mu_p^(n+1)).
     sigma_p / sigma_q may be length-P vectors: the diagonal-covariance surrogate (Remark "General
     covariances"); scalars are the isotropic surrogate of Eq. 4.
+    rule: "ratio" is the likelihood-ratio test of Eq. 5 against a uniform draw; "threshold" is the
+    deterministic test of `within_threshold` (no draw is used).  For the threshold rule the record
+    carries the same decision in log form, ell = -||x - mu_p||_d^2 / (2 sigma_p^2) against the
+    constant log u = -1/2, so that callers can see how close to the boundary a decision was.
     Returns a dict with X, mu_q [K, P], mu_p [K+1, P], ell, logu [K] (nan where untested),
     n (accepted count) and commits [n + 1, P].
     """
+    if rule not in ("ratio", "threshold"):
+        raise ValueError("rule must be 'ratio' or 'threshold'")
     hist = np.asarray(hist, dtype=np.float64)
     P = hist.shape[1]
     X = np.empty((K, P))
@@ -289,6 +308,16 @@ def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True
     logu = np.full(K, np.nan)
     n = 0
     for i in range(K):                               # left to right, stop at the first rejection
+        if rule == "threshold":
+            if np.ndim(sigma_p):
+                ell[i] = -0.5 * energy((X[i] - mu_p[i]) / np.asarray(sigma_p, dtype=np.float64))
+            else:
+                ell[i] = -energy(X[i] - mu_p[i]) / (2.0 * sigma_p * sigma_p)
+            logu[i] = -0.5
+            if within_threshold(X[i], mu_p[i], sigma_p):
+                n += 1
+                continue
+            break
         if np.ndim(sigma_p) or np.ndim(sigma_q):
             ell[i] = log_ratio_diag(X[i], mu_p[i], mu_q[i], sigma_p, sigma_q)
         else:
@@ -306,7 +335,7 @@ def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True
 
 def forecast_spec(Wt, mt, Wd, md, series_context, P, horizon, K, sigma_p, sigma_q, seed, b,
                   single_pass=True, alpha_override=None, u_fn=None, trace=None, sample_proposals=False,
-                  fallback_r=0.0, round0=0):
+                  fallback_r=0.0, round0=0, rule="ratio"):
     """Speculative forecast of one series.  series_context: raw context steps (length N * P).
     Returns (forecast [horizon] in raw units, stats dict).  `trace`, if a list, receives each
     round's record."""
@@ -323,7 +352,7 @@ def forecast_spec(Wt, mt, Wd, md, series_context, P, horizon, K, sigma_p, sigma_
         K_r = min(K, T - Y.shape[0])                 # no proposals for patches past the horizon
         rec = spec_round(Wt, mt, Wd, md, np.vstack([hist, Y]), K_r, sigma_p, sigma_q, draw,
                          single_pass=single_pass, alpha_override=alpha_override, eps_fn=eps,
-                         sample_proposals=sample_proposals, fallback_r=fallback_r)
+                         sample_proposals=sample_proposals, fallback_r=fallback_r, rule=rule)
         if trace is not None:
             trace.append(rec)
         n = rec["n"]
@@ -335,6 +364,60 @@ def forecast_spec(Wt, mt, Wd, md, series_context, P, horizon, K, sigma_p, sigma_
         r += 1
     stats["committed"] = Y.shape[0]
     return (Y.reshape(-1) * s + m)[:horizon], stats
+
+
+def commit_block(rec, n, fallback_r=0.0, eps_fn=None):
+    """The patches a round commits when it keeps n of its proposals: x_1..x_n, then the target's
+    prediction at position n + 1 (plus r eps when fallback noise is on)."""
+    t = rec["mu_p"][n] + fallback_r * eps_fn(STREAM_FALLBACK, n + 1) if fallback_r > 0.0 else rec["mu_p"][n]
+    return np.vstack([rec["X"][:n], t[None, :]])
+
+
+def forecast_spec_sync(Wt, mt, Wd, md, contexts, P, horizon, K, sigma_p, sigma_q, seed, rule="ratio",
+                       single_pass=True, sample_proposals=False, fallback_r=0.0, trace=None):
+    """Batch-synchronised speculative forecast (Table "TiRex configuration": acceptance
+    "batch-synchronized"): every round each series runs its own tests, and the whole batch then
+    keeps the smallest accepted count among them, so that all series stay at the same length: each
+    commits its first n_min proposals and its target's prediction at position n_min + 1.
+    contexts: [B, N * P] raw context steps.  Returns (forecasts [B, horizon], list of per-series
+    stats).  tested / accepted count each series' own tests (what it tried before its own first
+    rejection); committed follows the synchronised length.  `trace`, if a list, receives per round
+    the list of the series' records, each with the extra key n_sync."""
+    contexts = np.asarray(contexts, dtype=np.float64)
+    B = contexts.shape[0]
+    T = -(-horizon // P)
+    norm = [context_stats(contexts[b]) for b in range(B)]
+    hist = [((contexts[b] - norm[b][0]) / norm[b][1]).reshape(-1, P) for b in range(B)]
+    Y = [np.empty((0, P)) for _ in range(B)]
+    stats = [dict(rounds=0, tested=0, accepted=0, committed=0, lengths=[]) for _ in range(B)]
+    r = 0
+    while Y[0].shape[0] < T:                         # all series have the same length
+        K_r = min(K, T - Y[0].shape[0])
+        recs = []
+        for b in range(B):
+            draw = lambda i, b=b: uniform(seed, b, r, i)
+            eps = lambda stream, i, b=b: normal(seed, b, r, i, stream, P)
+            recs.append(spec_round(Wt, mt, Wd, md, np.vstack([hist[b], Y[b]]), K_r, sigma_p, sigma_q, draw,
+                                   single_pass=single_pass, eps_fn=eps, sample_proposals=sample_proposals,
+                                   fallback_r=fallback_r, rule=rule))
+        n_sync = min(rec["n"] for rec in recs)
+        for b in range(B):
+            rec = recs[b]
+            rec["n_sync"] = n_sync
+            eps = lambda stream, i, b=b: normal(seed, b, r, i, stream, P)
+            stats[b]["rounds"] += 1
+            stats[b]["tested"] += rec["n"] + (1 if rec["n"] < K_r else 0)
+            stats[b]["accepted"] += rec["n"]
+            stats[b]["lengths"].append(n_sync + 1)
+            Y[b] = np.vstack([Y[b], commit_block(rec, n_sync, fallback_r, eps)])[:T]
+        if trace is not None:
+            trace.append(recs)
+        r += 1
+    out = np.empty((B, horizon))
+    for b in range(B):
+        stats[b]["committed"] = Y[b].shape[0]
+        out[b] = (Y[b].reshape(-1) * norm[b][1] + norm[b][0])[:horizon]
+    return out, stats
 
 
 def forecast_target_only(Wt, mt, series_context, P, horizon):
