@@ -66,6 +66,8 @@ extern "C" {
 #define TSD_FLAG_NO_SKINNY 16u     /* never use the <= 32-row weight-streaming GEMM                */
 #define TSD_FLAG_SAMPLE_PROPOSALS 32u /* ablation: x_i = mu_q^(i) + sigma_q eps instead of the mean */
 #define TSD_FLAG_NAIVE_VERIFY 64u  /* ablation: one target pass per prefix instead of one causal pass */
+#define TSD_FLAG_THRESHOLD_RULE 128u /* variant: accept iff ||x_i - mu_p^(i)||_d^2 <= sigma_p^2, no draw */
+#define TSD_FLAG_BATCH_SYNC 256u   /* variant: every series keeps the batch's smallest accepted count */
 
 typedef struct tsd_ctx tsd_ctx; /* opaque */
 
@@ -181,8 +183,19 @@ int tsd_target_verify(tsd_ctx* ctx, void* stream);
  *   the committed history; mu_p^(n+1) becomes the pending token; a series with T patches
  *   becomes inactive.  With fallback_r = r > 0 the corrected / bonus patch is the draw
  *   mu_p^(n+1) + r eps (stream 2, position n+1; Sec. "Bonus Patch on Full Acceptance").
+ * With TSD_FLAG_THRESHOLD_RULE (Table "TiRex configuration", row "Acceptance draw") the test is
+ * deterministic: position i passes iff ||x_i - mu_p^(i)||_d^2 <= sigma_p^2 (per-dimension scales:
+ * the scaled Mahalanobis distance is at most 1).  It is evaluated and recorded in the log form
+ * ell_i = -||x_i - mu_p^(i)||_d^2 / (2 sigma_p^2) against the constant log u_i = -1/2; no uniform
+ * is drawn and the draft-side terms of Eq. 5 are not used.
+ * With TSD_FLAG_BATCH_SYNC (same row: the batch is kept in step) the series taking part in the round
+ * first find their own counts, then all of them keep the smallest one: each commits its first
+ * n_min proposals and its own mu_p^(n_min + 1), so series that start together stay at the same
+ * length.  The statistics' tested / accepted and the n_acc tap keep each series' own test;
+ * committed follows n_min.  Costs two more small launches per round.
  * forced_len_dev (nullable): int32 [B]; entry b in 0..K overrides n for series b after the test
- * has been evaluated and recorded (used to keep two implementations in lock-step); -1 = free. */
+ * has been evaluated and recorded (used to keep two implementations in lock-step); -1 = free.
+ * Under TSD_FLAG_BATCH_SYNC the overridden value is the series' own count that enters the minimum. */
 int tsd_accept_commit(tsd_ctx* ctx, const int32_t* forced_len_dev, void* stream);
 
 /* tsd_draft_propose; tsd_target_verify; tsd_accept_commit(NULL).  On a non-NULL stream that is not

@@ -375,8 +375,8 @@ def commit_block(rec, n, fallback_r=0.0, eps_fn=None):
 
 def forecast_spec_sync(Wt, mt, Wd, md, contexts, P, horizon, K, sigma_p, sigma_q, seed, rule="ratio",
                        single_pass=True, sample_proposals=False, fallback_r=0.0, trace=None):
-    """Batch-synchronised speculative forecast (Table "TiRex configuration": acceptance
-    "batch-synchronized"): every round each series runs its own tests, and the whole batch then
+    """Batch-synchronised speculative forecast (Table "TiRex configuration", acceptance row: the
+    batch is kept in step): every round each series runs its own tests, and the whole batch then
     keeps the smallest accepted count among them, so that all series stay at the same length: each
     commits its first n_min proposals and its target's prediction at position n_min + 1.
     contexts: [B, N * P] raw context steps.  Returns (forecasts [B, horizon], list of per-series

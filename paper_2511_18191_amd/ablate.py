@@ -5,7 +5,9 @@ component-ablation table): acceptance, deviation from the target-only forecast, 
 
 Rows: the full rule; without the 1/d tempering; sampled proposals x_i ~ q instead of the mean;
 fallback noise r = sigma instead of the clean target mean; one target pass per prefix instead of
-single-pass verification.  There is no trained model or dataset here, so "accuracy" is the mean
+single-pass verification; and the standalone variant of the paper's TiRex table: the deterministic
+threshold ||x - mu_p||_d^2 <= sigma^2 with batch-synchronised commits, alone and on top of
+per-prefix verification.  There is no trained model or dataset here, so "accuracy" is the mean
 energy per dimension of (forecast - target-only forecast) in normalised units: the quantity the
 deterministic fidelity bound (Eq. 9) caps at 2 sigma^2 / e per committed patch for the full rule.
 Prints a markdown table.
@@ -17,7 +19,8 @@ import numpy as np
 
 import synth
 
-from .binding import (TSD_FLAG_NAIVE_VERIFY, TSD_FLAG_NO_TEMPERING, TSD_FLAG_SAMPLE_PROPOSALS, session_for)
+from .binding import (TSD_FLAG_BATCH_SYNC, TSD_FLAG_NAIVE_VERIFY, TSD_FLAG_NO_TEMPERING, TSD_FLAG_SAMPLE_PROPOSALS,
+                      TSD_FLAG_THRESHOLD_RULE, session_for)
 from .sweep import _decode_spec, _decode_target, _time
 
 
@@ -51,7 +54,12 @@ def main(argv=None):
     c = inputs.cfg
     rows = [("full rule", 0, 0.0), ("w/o 1/d tempering", TSD_FLAG_NO_TEMPERING, 0.0),
             ("w/o mean proposal (x_i ~ q)", TSD_FLAG_SAMPLE_PROPOSALS, 0.0), ("w/o clean fallback (r = sigma)", 0, c.sigma),
-            ("w/o single-pass verification", TSD_FLAG_NAIVE_VERIFY, 0.0)]
+            ("w/o single-pass verification", TSD_FLAG_NAIVE_VERIFY, 0.0),
+            ("batch-synchronised commits", TSD_FLAG_BATCH_SYNC, 0.0),
+            ("threshold rule", TSD_FLAG_THRESHOLD_RULE, 0.0),
+            ("threshold rule, batch-synchronised", TSD_FLAG_THRESHOLD_RULE | TSD_FLAG_BATCH_SYNC, 0.0),
+            ("threshold rule, batch-synchronised, per-prefix verification",
+             TSD_FLAG_THRESHOLD_RULE | TSD_FLAG_BATCH_SYNC | TSD_FLAG_NAIVE_VERIFY, 0.0)]
     print(f"{c.name}: B={c.batch} P={c.patch} K={c.K} sigma={c.sigma:g} H={c.horizon}; fidelity cap of the full rule "
           f"2 sigma^2/e = {2 * c.sigma ** 2 / np.e:.3f}\n")
     print("| configuration | accept | patches/round | deviation from target-only | spec ms | target-only ms | speedup |")

@@ -240,13 +240,20 @@ __global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
   float ell = NAN, logu = NAN, thr = 0.f;
   if (lane < Kb) {
     // Eq. 5 with per-dimension energies ||.||^2 / P
-    if (p.inv2sp2_vec)
-      ell = p.temper * (-(my_ep / (float)P) + (my_eq / (float)P) + p.logdet_dev[0]);
-    else
-      ell = p.temper * (-(my_ep / (float)P) * p.inv2sp2 + (my_eq / (float)P) * p.inv2sq2 + p.logdet);
-    unsigned w = philox_word0((unsigned)b, (unsigned)r, (unsigned)(lane + 1), 0u, p.key0, p.key1);
-    float u = word_uniform(w);
-    logu = logf(u);
+    if (p.threshold) {
+      // threshold rule: ||x - mu_p||_d^2 <= sigma_p^2, written as ell >= -1/2 so that the recorded
+      // pair (ell, log u) shows how close to the boundary the decision was
+      ell = p.temper * (p.inv2sp2_vec ? -(my_ep / (float)P) : -(my_ep / (float)P) * p.inv2sp2);
+      logu = -0.5f;
+    } else {
+      if (p.inv2sp2_vec)
+        ell = p.temper * (-(my_ep / (float)P) + (my_eq / (float)P) + p.logdet_dev[0]);
+      else
+        ell = p.temper * (-(my_ep / (float)P) * p.inv2sp2 + (my_eq / (float)P) * p.inv2sq2 + p.logdet);
+      unsigned w = philox_word0((unsigned)b, (unsigned)r, (unsigned)(lane + 1), 0u, p.key0, p.key1);
+      float u = word_uniform(w);
+      logu = logf(u);
+    }
     thr = (p.log_alpha_override <= 0.f) ? p.log_alpha_override : fminf(0.f, ell);
     reject = !(logu <= thr);
   }
@@ -255,14 +262,19 @@ __global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
   const int tested = n_free + (n_free < Kb ? 1 : 0);
   const bool is_tested = lane < tested;
   const unsigned long long near = __ballot(is_tested && fabsf(thr - logu) < 1e-4f);
-  if (lane < K) {
-    p.ell[(long)b * KE + lane] = is_tested ? ell : NAN;
-    p.logu[(long)b * KE + lane] = is_tested ? logu : NAN;
-  }
   int n = n_free;
   if (p.forced) {
     int f = p.forced[b];
     if (f >= 0 && f <= Kb) n = f;
+  }
+  if (p.mode == 1) {  // synchronised round, first launch: only the minimum over the series
+    if (lane == 0) atomicMin(p.sync, n);
+    return;
+  }
+  if (p.mode == 2) n = min(n, *p.sync);
+  if (lane < K) {
+    p.ell[(long)b * KE + lane] = is_tested ? ell : NAN;
+    p.logu[(long)b * KE + lane] = is_tested ? logu : NAN;
   }
   const int L = n + 1;
   const int Lc = min(L, p.T - c0);
@@ -296,6 +308,15 @@ __global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
 
 hipError_t launch_accept(const AcceptP& p, hipStream_t st) {
   hipLaunchKernelGGL(accept_kernel, dim3(p.B), dim3(64), 0, st, p);
+  return hipGetLastError();
+}
+
+__global__ void fill_int_kernel(int* p, int value, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = value;
+}
+hipError_t launch_fill_int(int* p, int value, int n, hipStream_t st) {
+  hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)((n + 63) / 64)), dim3(64), 0, st, p, value, n);
   return hipGetLastError();
 }
 

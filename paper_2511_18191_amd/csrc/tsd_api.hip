@@ -1,6 +1,7 @@
 // Host side of libtsd: argument validation, arena carving, weight loading, and the sequencing of
 // kernel launches that make up prefill, draft proposal, single-pass verification, acceptance and
 // the target-only baseline step.  Nothing here allocates device memory.
+#include <climits>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -148,7 +149,7 @@ int check_config(const tsd_config* c, std::string& why) {
     return bad("sigma_p and sigma_q must be positive and finite");
   if (!(c->fallback_r >= 0.f) || c->fallback_r > c->sigma_p) return bad("fallback_r must lie in [0, sigma_p]");
   if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING | TSD_FLAG_NO_GRAPH | TSD_FLAG_NO_COMPACT | TSD_FLAG_NO_SKINNY | TSD_FLAG_SAMPLE_PROPOSALS |
-                   TSD_FLAG_NAIVE_VERIFY)) return bad("unknown flag bits");
+                   TSD_FLAG_NAIVE_VERIFY | TSD_FLAG_THRESHOLD_RULE | TSD_FLAG_BATCH_SYNC)) return bad("unknown flag bits");
   if ((c->max_tokens + c->page_tokens - 1) / c->page_tokens > 64)
     return bad("max_tokens / page_tokens must not exceed 64 pages per series");
   for (const tsd_model_cfg* m : {&c->target, &c->draft})
@@ -634,6 +635,15 @@ int accept_commit_impl(tsd_ctx* ctx, const int32_t* forced, int K, hipStream_t s
   }
   a.key0 = (unsigned)(c.seed & 0xFFFFFFFFull);
   a.key1 = (unsigned)(c.seed >> 32);
+  a.threshold = (c.flags & TSD_FLAG_THRESHOLD_RULE) ? 1 : 0;
+  if ((c.flags & TSD_FLAG_BATCH_SYNC) && K > 0) {
+    // the series' own counts first (their minimum lands in the sync word), then the commit
+    a.sync = ctx->count_out + 8;
+    HIP_TRY(ctx, launch_fill_int(a.sync, INT_MAX, 1, st));
+    a.mode = 1;
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_ACCEPT, 4.0 * ctx->B * c.patch * (2.0 * K + 2), st, [&] { return launch_accept(a, st); }));
+    a.mode = 2;
+  }
   HIP_TRY(ctx, timed_launch(ctx, TSD_K_ACCEPT, 4.0 * ctx->B * c.patch * (2.0 * K + 2), st, [&] { return launch_accept(a, st); }));
   ctx->injected = false;
   return TSD_OK;

@@ -174,8 +174,15 @@ struct AcceptP {
   // the scalar (1 / 2P) sum_e log(s_q[e]^2 / s_p[e]^2)
   const float *inv2sp2_vec, *inv2sq2_vec, *logdet_dev;
   unsigned key0, key1;
+  int threshold;  // deterministic rule: -||x - mu_p||_d^2 / (2 sigma_p^2) against log u = -1/2, no draw
+  // batch-synchronised acceptance runs the kernel twice: mode 1 only folds every series' own count
+  // into *sync (atomic minimum; the word starts at INT_MAX), mode 2 commits with n = *sync;
+  // mode 0 is the unsynchronised round in one launch
+  int mode;
+  int* sync;
 };
 hipError_t launch_accept(const AcceptP& p, hipStream_t st);
+hipError_t launch_fill_int(int* p, int value, int n, hipStream_t st);
 
 struct SampleP {  // X[b, i-1] = mu_q[b, i-1] + sigma_q * eps(b, round[b], i)
   const float* mu_q;

@@ -39,12 +39,14 @@ class Case(synth.Inputs):
 
 
 def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=True, tol=None, subset=None,
-             sample_proposals=False, fallback_r=0.0, sigma_p=None):
+             sample_proposals=False, fallback_r=0.0, sigma_p=None, rule="ratio", sync=False):
     """Run GPU and oracle round by round on the same histories.  The GPU evaluates its own
     acceptance test (recorded) but commits the oracle's accepted length, so the two histories
     stay aligned and every round's tensors can be compared.  Returns a report dict.
     sample_proposals / fallback_r: the oracle's noise knobs; the session must have been created
-    with the matching flag / fallback_r."""
+    with the matching flag / fallback_r.  rule / sync: the threshold rule and the batch-synchronised
+    commit (the session must carry TSD_FLAG_THRESHOLD_RULE / TSD_FLAG_BATCH_SYNC): with sync the GPU
+    is handed every series' own oracle count and must itself keep the smallest."""
     import torch
     c = case.cfg
     B, K, P, T = c.batch, c.K, c.patch, c.T
@@ -72,12 +74,14 @@ def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=Tru
             recs[b] = orc.spec_round(case.Wt, c.target, case.Wd, c.draft, np.vstack([hist[b], Y[b]]), Kb[b], sp, sq,
                                      (lambda i, b=b: orc.uniform(case.seed, b, rnd[b], i)),
                                      eps_fn=(lambda stream, i, b=b: orc.normal(case.seed, b, rnd[b], i, stream, P)),
-                                     sample_proposals=sample_proposals, fallback_r=fallback_r)
+                                     sample_proposals=sample_proposals, fallback_r=fallback_r, rule=rule)
             forced[b] = recs[b]["n"]
+        n_sync = min(rec["n"] for rec in recs.values()) if sync else None
         sess.accept_commit(torch.from_numpy(forced))
         io = {k: v.cpu().numpy() for k, v in sess.get_round_io().items()}
         for b, rec in recs.items():
-            n, Kc = rec["n"], Kb[b]
+            n_own, Kc = rec["n"], Kb[b]
+            n = n_sync if sync else n_own          # what the round keeps
             io_b = {"X": io["X"][b][:Kc], "mu_q": io["mu_q"][b][:Kc], "mu_p": io["mu_p"][b][:Kc + 1]}
             # compare what both sides computed from (nearly) identical histories
             rx = max(rel_err(io_b["X"], rec["X"]).max(), rel_err(io_b["mu_q"], rec["mu_q"]).max())
@@ -102,23 +106,25 @@ def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=Tru
                 if fallback_r > 0.0:    # what the GPU committed, up to the rounding of its own draw
                     t_g = t_g + fallback_r * orc.normal(case.seed, b, rnd[b], n + 1, orc.STREAM_FALLBACK, P)
                 Yg[b] = np.vstack([Yg[b], Xg[:n], t_g[None, :]])[:T]
-            tested = n + (1 if n < Kc else 0)
+            tested = n_own + (1 if n_own < Kc else 0)
             gap = np.abs(np.minimum(0.0, rec["ell"][:tested]) - rec["logu"][:tested])
             near = bool(np.any(gap < 1e-4))
             rep["near_ties"] += int(near)
             rep["tested"] += tested
-            rep["accepted"] += n
+            rep["accepted"] += n_own
             g_n = int(io["n_acc"][b])
             # the uniforms are exact on both sides; log u and ell only to rounding
             np.testing.assert_allclose(io["logu"][b][:min(tested, g_n + 1)], rec["logu"][:min(tested, g_n + 1)], rtol=2e-6, atol=2e-6)
-            if g_n != n:
+            if g_n != n_own:
                 rep["mismatched"] += 1
                 if check and c.dtype == "fp32":
-                    assert near, f"series {b} round {rnd[b]}: accepted {g_n} vs oracle {n} away from any tie"
+                    assert near, f"series {b} round {rnd[b]}: accepted {g_n} vs oracle {n_own} away from any tie"
             else:
                 d_ell = np.abs(io["ell"][b][:tested] - rec["ell"][:tested]).max() if tested else 0.0
                 rep["max_abs_ell"] = max(rep["max_abs_ell"], float(d_ell))
-            Y[b] = np.vstack([Y[b], rec["commits"]])[:T]
+            blk = rec["commits"] if not sync else orc.commit_block(
+                rec, n, fallback_r, (lambda stream, i, b=b: orc.normal(case.seed, b, rnd[b], i, stream, P)))
+            Y[b] = np.vstack([Y[b], blk])[:T]
             rnd[b] += 1
             rep["lengths"].append(n + 1)
         rounds += 1

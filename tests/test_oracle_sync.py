@@ -1,6 +1,6 @@
 """Pins of the threshold acceptance rule and of the batch-synchronised loop (oracle only).
 
-Table "TiRex configuration": acceptance by the threshold ||.||_d^2 <= sigma^2, batch-synchronised.
+Table "TiRex configuration", acceptance row: the inequality ||.||_d^2 <= sigma^2, batch kept in step.
 """
 import math
 
