@@ -28,6 +28,8 @@ def parse():
     ap.add_argument("--sample-proposals", action="store_true", help="ablation: x_i = mu_q + sigma_q eps")
     ap.add_argument("--fallback-r", type=float, default=0.0, help="ablation: fallback / bonus noise scale")
     ap.add_argument("--naive-verify", action="store_true", help="ablation: one target pass per prefix")
+    ap.add_argument("--threshold-rule", action="store_true", help="variant: accept iff ||x - mu_p||_d^2 <= sigma^2")
+    ap.add_argument("--batch-sync", action="store_true", help="variant: all series keep the batch's smallest accepted count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-series", type=int, default=64, help="series in the oracle's bounded sample (~10-20 s of CPU work at cfg2)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -109,16 +111,20 @@ def kernel_rooflines(sess, dtype, steps, workload):
     return out
 
 
-def cpu_baseline(case, n_series, **oracle_kw):
+def cpu_baseline(case, n_series, batch_sync=False, **oracle_kw):
     """The oracle, as it stands, on a bounded sample: n_series series, whole horizon,
     single-pass mode, one process (numpy's BLAS threads).  The only place the oracle is used."""
     from oracle import tsd_oracle as orc
     c = case.cfg
     Wt, Wd = orc.as_f64(case.wt), orc.as_f64(case.wd)
     t0 = time.perf_counter()
-    for b in range(n_series):
-        orc.forecast_spec(Wt, c.target, Wd, c.draft, case.context[b], c.patch, c.horizon, c.K, c.sigma,
-                          c.sigma, case.seed, b, **oracle_kw)
+    if batch_sync:   # the sample decodes as one synchronised batch of its own
+        orc.forecast_spec_sync(Wt, c.target, Wd, c.draft, case.context[:n_series], c.patch, c.horizon, c.K, c.sigma,
+                               c.sigma, case.seed, **oracle_kw)
+    else:
+        for b in range(n_series):
+            orc.forecast_spec(Wt, c.target, Wd, c.draft, case.context[b], c.patch, c.horizon, c.K, c.sigma,
+                              c.sigma, case.seed, b, **oracle_kw)
     dt = time.perf_counter() - t0
     try:
         from threadpoolctl import threadpool_info
@@ -126,8 +132,10 @@ def cpu_baseline(case, n_series, **oracle_kw):
     except Exception:
         cores = os.cpu_count()
     return dict(value=n_series * c.horizon / dt, unit="forecast steps/s", cores=cores, kind="oracle",
-                sample=f"{n_series} of {c.batch} series, whole horizon of {c.horizon} steps, single-pass oracle, "
-                       f"{dt:.1f} s")
+                sample=f"{n_series} of {c.batch} series, whole horizon of {c.horizon} steps, "
+                       f"{'single-pass' if oracle_kw.get('single_pass', True) else 'per-prefix'} oracle"
+                       f"{', threshold rule' if oracle_kw.get('rule') == 'threshold' else ''}"
+                       f"{', batch-synchronised' if batch_sync else ''}, {dt:.1f} s")
 
 
 def main():
@@ -151,6 +159,7 @@ def main():
     case = synth.Inputs(a.config, sigma=a.sigma)
     c = case.cfg
     flags = (tsd.TSD_FLAG_SAMPLE_PROPOSALS if a.sample_proposals else 0) | (tsd.TSD_FLAG_NAIVE_VERIFY if a.naive_verify else 0)
+    flags |= (tsd.TSD_FLAG_THRESHOLD_RULE if a.threshold_rule else 0) | (tsd.TSD_FLAG_BATCH_SYNC if a.batch_sync else 0)
     sess = tsd.session_for(case, flags=flags, fallback_r=a.fallback_r)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -186,7 +195,8 @@ def main():
         "config": {"workload": f"{c.name}: B={c.batch} P={c.patch} N={c.n_ctx} H={c.horizon} K={c.K} sigma={c.sigma} "
                                f"target {c.target.n_layers}L/d{c.target.d_model} draft {c.draft.n_layers}L/d{c.draft.d_model}",
                    "step": "reset to post-prefill state + speculative rounds until all series reach the horizon",
-                   "ablation": {"sample_proposals": a.sample_proposals, "fallback_r": a.fallback_r, "naive_verify": a.naive_verify}},
+                   "ablation": {"sample_proposals": a.sample_proposals, "fallback_r": a.fallback_r, "naive_verify": a.naive_verify,
+                                "threshold_rule": a.threshold_rule, "batch_sync": a.batch_sync}},
         "speedup_vs_target_only": t_base / t_spec,
         "target_only_steps_per_s": c.batch * c.horizon / t_base,
         "target_only_ms": t_base * 1e3,
@@ -204,7 +214,8 @@ def main():
     }
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case, min(a.cpu_series, c.batch), sample_proposals=a.sample_proposals,
-                                           fallback_r=a.fallback_r, single_pass=not a.naive_verify)
+                                           fallback_r=a.fallback_r, single_pass=not a.naive_verify,
+                                           rule="threshold" if a.threshold_rule else "ratio", batch_sync=a.batch_sync)
     print(json.dumps(out))
 
 
