@@ -91,3 +91,33 @@ def test_plan_follows_the_law_and_the_measured_optimum():
         t = costs[K]
         rate[K] = st["committed"] / st["rounds"] / (t["draft"] + t["verify"] + t["accept"])
     assert rate[p["k_table"]] >= 0.85 * max(rate.values()), (p["k_table"], rate)
+
+
+def test_calibrated_temperature_hits_the_rate_and_the_oracle_agrees():
+    # sigma found by bisection on GPU decodes; at that sigma the oracle, decoding the same series, tests and
+    # accepts the same numbers of proposals (fp32, outside near ties)
+    from paper_2511_18191_amd import sweep
+    from oracle import tsd_oracle as orc
+    from harness import Case
+    case = Case("cfg1")
+    c = case.cfg
+    for target in (0.5, 0.8):
+        sigma, rate = sweep.calibrate_sigma(case, target, tol=0.03)
+        assert abs(rate - target) <= 0.03 and 0.0 < sigma < 16.0
+        sess = case.session()
+        sess.set_sigma(sigma)
+        sess.prefill(case.context, c.n_ctx, c.horizon)
+        while sess.num_active() > 0:
+            sess.round()
+        st = sess.get_stats()
+        tested = accepted = 0
+        for b in range(c.batch):
+            _, s = orc.forecast_spec(case.Wt, c.target, case.Wd, c.draft, case.context[b], c.patch, c.horizon, c.K,
+                                     sigma, sigma, case.seed, b)
+            tested += s["tested"]
+            accepted += s["accepted"]
+        print(f"\ntarget {target}: sigma {sigma:.4f}, GPU {st['accepted']}/{st['tested']}, oracle {accepted}/{tested}, "
+              f"near ties {st['near_ties']}")
+        if st["near_ties"] == 0:
+            assert (st["tested"], st["accepted"]) == (tested, accepted)
+        assert abs(accepted / tested - target) <= 0.06
