@@ -111,6 +111,31 @@ def kernel_rooflines(sess, dtype, steps, workload):
     return out
 
 
+def measured_peaks(torch, tsd):
+    """What this machine delivers to the simplest possible kernels: the library's register-only MFMA
+    loop (bf16 32x32x16, every wavefront slot of every CU busy) and its plain 256 MiB copy kernel.
+    Reported beside the published peaks the roofline fractions are quoted against."""
+    def ms(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    blocks, iters = 256 * 8, 20000
+    sink = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    t = ms(lambda: tsd.bench_mfma(blocks, iters, sink), 3)
+    mfma = blocks * 4 * iters * 4 * 2.0 * 32 * 32 * 16 / (t * 1e-3) / 1e12
+    src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")      # 256 MiB
+    dst = torch.empty_like(src)
+    t = ms(lambda: tsd.bench_copy(dst, src), 5)
+    copy = 2.0 * src.numel() * 4 / (t * 1e-3) / 1e9
+    return {"mfma_bf16_tflops": mfma, "hbm_copy_gbs": copy}
+
+
 def cpu_baseline(case, n_series, batch_sync=False, **oracle_kw):
     """The oracle, as it stands, on a bounded sample: n_series series, whole horizon,
     single-pass mode, one process (numpy's BLAS threads).  The only place the oracle is used."""
@@ -179,6 +204,7 @@ def main():
 
     fam = kernel_rooflines(sess, c.dtype, max(2, a.steps // 4), c.name if a.sigma is None else None)
     dominant = max(fam, key=lambda k: fam[k]["total_ms"])
+    peaks = measured_peaks(torch, tsd)
 
     alpha = st["accepted"] / max(1, st["tested"])
     mean_L = st["committed"] / max(1, st["rounds"])
@@ -211,6 +237,7 @@ def main():
         "roofline": dict({k: v for k, v in fam[dominant].items() if k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},
                          kernel=dominant, avg_us=fam[dominant]["avg_us"], launches=fam[dominant]["launches"]),
         "kernel_families": fam,
+        "measured_peaks": peaks,
     }
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case, min(a.cpu_series, c.batch), sample_proposals=a.sample_proposals,

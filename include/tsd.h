@@ -297,6 +297,13 @@ int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_de
  * (a multiple of 16).  Its known traffic calibrates the profiler's memory counters. */
 int tsd_bench_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
 
+/* Measurement tap: `blocks` workgroups of 256 lanes, every wavefront issuing `iters` rounds of four
+ * independent v_mfma_f32_32x32x16_bf16 chains on register operands (no memory traffic inside the
+ * loop): 2 * 32 * 32 * 16 * 4 * iters flop per wavefront.  The rate it reaches is the matrix-core
+ * ceiling this library's GEMM instruction can be priced against on the machine at hand, next to the
+ * published peak.  sink_dev: float [blocks * 256], written once at the end (keeps the chains live). */
+int tsd_bench_mfma(int32_t blocks, int32_t iters, float* sink_dev, void* stream);
+
 /* Measurement tap: `blocks` workgroups of 256 lanes, workgroup w reading its own slice
  * src_dev[w * bytes_per_block ...) `iters` times with 16-byte loads (the way a GEMM workgroup walks
  * its operand panels); slices that fit L2 measure the cache-to-CU operand stream that bounds a

@@ -62,6 +62,7 @@ SYMBOLS = {
     "tsd_profile_end": ([C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p], C.c_int),
     "tsd_bench_gemm": ([C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_bench_copy": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
+    "tsd_bench_mfma": ([C.c_int32, C.c_int32, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_bench_stream": ([C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_set_accept_override": ([C.c_void_p, C.c_float], C.c_int),
     "tsd_get_series_stats": ([C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
@@ -133,6 +134,13 @@ def bench_copy(dst, src):
     n = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == n
     _check(lib().tsd_bench_copy(dst.data_ptr(), src.data_ptr(), n, torch.cuda.current_stream(src.device).cuda_stream))
+
+
+def bench_mfma(blocks, iters, sink):
+    """Matrix-core tap (see tsd_bench_mfma) on torch's current stream; sink: float32 GPU tensor [blocks * 256]."""
+    import torch
+    assert sink.dtype == torch.float32 and sink.numel() >= blocks * 256
+    _check(lib().tsd_bench_mfma(blocks, iters, sink.data_ptr(), torch.cuda.current_stream(sink.device).cuda_stream))
 
 
 def bench_stream(src, bytes_per_block, blocks, iters, sink):

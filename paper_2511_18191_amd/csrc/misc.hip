@@ -416,6 +416,34 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
   return hipGetLastError();
 }
 
+// Matrix-core tap: four independent accumulation chains per wavefront keep the MFMA pipe full; the
+// operands stay in registers, so nothing but the matrix cores is measured.
+__global__ __launch_bounds__(256) void mfma_peak_kernel(int iters, float* sink) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    a[e] = (bf16)(0.015625f * (float)(1 + ((threadIdx.x + e) & 3)));
+    b[e] = (bf16)(0.015625f * (float)(1 + ((threadIdx.x >> 2) & 3)));
+  }
+  f32x16 c0, c1, c2, c3;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) c0[r] = c1[r] = c2[r] = c3[r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+    c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+    c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+    c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+    c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) s += c0[r] + c1[r] + c2[r] + c3[r];
+  sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+hipError_t launch_mfma_peak(int blocks, int iters, float* sink, hipStream_t st) {
+  hipLaunchKernelGGL(mfma_peak_kernel, dim3(blocks), dim3(256), 0, st, iters, sink);
+  return hipGetLastError();
+}
+
 // Operand-stream tap: workgroup w reads its own `bytes_per_block` slice of `src` `iters` times with
 // 16-byte loads (eight in flight per lane), i.e. the access pattern of a GEMM workgroup walking its
 // A/B panels out of L2.  The XOR of everything read goes to sink[w] so the loads cannot be dropped.

@@ -1256,6 +1256,14 @@ int tsd_bench_stream(const void* src_dev, size_t bytes_per_block, int32_t blocks
   return TSD_OK;
 }
 
+int tsd_bench_mfma(int32_t blocks, int32_t iters, float* sink_dev, void* stream) {
+  if (!sink_dev) return fail(nullptr, TSD_E_INVALID_ARG, "sink_dev must not be NULL");
+  if (blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 24))
+    return fail(nullptr, TSD_E_INVALID_ARG, "need 1..65536 blocks and 1..2^24 iters");
+  HIP_TRY(nullptr, launch_mfma_peak(blocks, iters, sink_dev, (hipStream_t)stream));
+  return TSD_OK;
+}
+
 int tsd_set_accept_override(tsd_ctx* ctx, float alpha) {
   if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
   if (alpha > 1.f || alpha == 0.f || std::isnan(alpha)) return fail(ctx, TSD_E_INVALID_ARG, "alpha must be in (0, 1], or negative to disable");

@@ -215,6 +215,7 @@ hipError_t launch_identity_list(int* list, int* count, int B, int T, hipStream_t
 hipError_t launch_sum_stats(const long long* stat, int B, long long* out5, hipStream_t st);
 hipError_t launch_fill_nan(float* p, long n, hipStream_t st);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+hipError_t launch_mfma_peak(int blocks, int iters, float* sink, hipStream_t st);
 hipError_t launch_stream(const void* src, size_t bytes_per_block, int blocks, int iters, unsigned* sink, hipStream_t st);
 
 }  // namespace tsd
