@@ -108,6 +108,10 @@ def kernel_rooflines(sess, dtype, steps, workload):
         out[name] = dict(bound="hbm" if hbm else "mfma", achieved=achieved, peak=peak, unit="GB/s" if hbm else "TFLOP/s",
                          frac=achieved / peak, launches=n, avg_us=ms * 1e3 / n, total_ms=ms,
                          traffic=TRAFFIC.get(workload, {}).get(name))
+        # the GEMMs of this size sit near the ridge (intensity ~ 300 flop per HBM byte): besides the
+        # MFMA fraction, the measured HBM bytes per launch against the memory peak
+        if out[name]["traffic"]:
+            out[name]["hbm_frac_of_traffic"] = out[name]["traffic"] / (ms * 1e-3 / n) / 1e9 / HBM_PEAK
     return out
 
 
@@ -234,7 +238,8 @@ def main():
         "near_ties": st["near_ties"],
         # committed patches per unit time against one patch per target step (what Eq. 8 predicts)
         "patch_rate_speedup": mean_L * ph["target_step"] / (ph["draft"] + ph["verify"] + ph["accept"]),
-        "roofline": dict({k: v for k, v in fam[dominant].items() if k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},
+        "roofline": dict({k: v for k, v in fam[dominant].items()
+                          if k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "hbm_frac_of_traffic")},
                          kernel=dominant, avg_us=fam[dominant]["avg_us"], launches=fam[dominant]["launches"]),
         "kernel_families": fam,
         "measured_peaks": peaks,
