@@ -93,3 +93,18 @@ def test_null_and_misuse_are_errors_not_crashes():
     assert L.tsd_destroy(None) == -1
     assert L.tsd_set_sigma(None, 1.0, 1.0) == -1
     assert b"NULL" in L.tsd_last_error(None)
+
+
+def test_measurement_taps_validate_before_any_launch():
+    # argument checks come first, so they can be exercised without a GPU
+    L = tsd.lib()
+    assert L.tsd_bench_mfma(8, 100, None, None) == -1 and b"sink_dev" in L.tsd_last_error(None)
+    assert L.tsd_bench_mfma(0, 100, 0x1000, None) == -1
+    assert L.tsd_bench_mfma(8, 0, 0x1000, None) == -1
+    assert L.tsd_bench_mfma(1 << 20, 1, 0x1000, None) == -1
+    assert L.tsd_bench_copy(None, 0x1000, 1024, None) == -1
+    assert L.tsd_bench_copy(0x1000, 0x2000, 1000, None) == -1                 # not a multiple of 16
+    assert L.tsd_bench_stream(None, 1024, 4, 1, 0x1000, None) == -1
+    assert L.tsd_bench_stream(0x1000, 1000, 4, 1, 0x2000, None) == -1         # slice not a multiple of 16
+    assert L.tsd_bench_gemm(tsd.TSD_BF16, 3, 64, 64, 64, 0x1000, 0x2000, 0x3000, None) == -1   # unknown variant
+    assert L.tsd_bench_gemm(tsd.TSD_BF16, 0, 64, 64, 60, 0x1000, 0x2000, 0x3000, None) == -1   # K not a multiple of 8
