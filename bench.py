@@ -39,12 +39,7 @@ def parse():
 
 def decode_spec(sess):
     sess.reset_decode()
-    rounds = 0
-    while True:
-        sess.round()
-        rounds += 1
-        if sess.num_active() == 0:
-            return rounds
+    return sess.run_rounds()[0]   # rounds until every series has its horizon (the loop lives in the library)
 
 
 def decode_target_only(sess, T):

@@ -68,6 +68,7 @@ extern "C" {
 #define TSD_FLAG_NAIVE_VERIFY 64u  /* ablation: one target pass per prefix instead of one causal pass */
 #define TSD_FLAG_THRESHOLD_RULE 128u /* variant: accept iff ||x_i - mu_p^(i)||_d^2 <= sigma_p^2, no draw */
 #define TSD_FLAG_BATCH_SYNC 256u   /* variant: every series keeps the batch's smallest accepted count */
+#define TSD_FLAG_NO_PINNED_COUNTS 512u /* tsd_num_active copies the counts back and waits on the stream */
 
 typedef struct tsd_ctx tsd_ctx; /* opaque */
 
@@ -203,6 +204,16 @@ int tsd_accept_commit(tsd_ctx* ctx, const int32_t* forced_len_dev, void* stream)
  * replayed afterwards (same for tsd_target_step); TSD_FLAG_NO_GRAPH switches that off. */
 int tsd_round(tsd_ctx* ctx, void* stream);
 
+/* Rounds until no series needs patches any more (or max_rounds rounds have run): the loop
+ *   do { tsd_round; tsd_num_active; } while (active > 0)
+ * kept inside the library, so that nothing but the count's delivery stands between two rounds.
+ * A round commits at most K + 1 patches per series, so while the neediest series is known to need
+ * more than that, the next round is enqueued without waiting for the count.  Results are those of
+ * the written-out loop, bit for bit.  rounds_host (nullable) receives the number of rounds run,
+ * active_host (nullable) the number of series still active at the end.  Synchronises `stream`
+ * like tsd_num_active. */
+int tsd_run_rounds(tsd_ctx* ctx, int32_t max_rounds, int32_t* rounds_host, int32_t* active_host, void* stream);
+
 /* Target-only autoregressive baseline (Eq. 1) from the same kernels: one target pass over the
  * pending token, whose output is committed for every active series. */
 int tsd_target_step(tsd_ctx* ctx, void* stream);
@@ -210,7 +221,11 @@ int tsd_target_step(tsd_ctx* ctx, void* stream);
 /* Number of series that still need patches.  Synchronises `stream`.  Also rebuilds the list of
  * active series; until the next prefill/reset, passes then cover only the listed series (those
  * that finish later stay listed and are masked, so the list stays valid without further calls).
- * Results are identical with or without it; finished series simply stop costing work. */
+ * Results are identical with or without it; finished series simply stop costing work.
+ * The counts reach the host through a few pinned host words that the compaction kernel writes
+ * itself (tsd_round already ends with that kernel), so this call normally launches nothing and
+ * waits for nothing but those words; it falls back to a copy and a stream wait when pinned
+ * memory could not be allocated at tsd_create. */
 int tsd_num_active(tsd_ctx* ctx, int32_t* out_host, void* stream);
 
 /* De-normalised forecast, out_dev: [B, horizon_steps] (first H steps of the committed patches;

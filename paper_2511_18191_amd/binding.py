@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 TSD_F32, TSD_BF16 = 0, 1
 TSD_TARGET, TSD_DRAFT = 0, 1
 TSD_FLAG_SCRAMBLE_PAGES, TSD_FLAG_NO_TEMPERING, TSD_FLAG_NO_GRAPH, TSD_FLAG_NO_COMPACT, TSD_FLAG_NO_SKINNY, TSD_FLAG_SAMPLE_PROPOSALS, TSD_FLAG_NAIVE_VERIFY = 1, 2, 4, 8, 16, 32, 64
-TSD_FLAG_THRESHOLD_RULE, TSD_FLAG_BATCH_SYNC = 128, 256
+TSD_FLAG_THRESHOLD_RULE, TSD_FLAG_BATCH_SYNC, TSD_FLAG_NO_PINNED_COUNTS = 128, 256, 512
 KERNEL_CLASSES = ["embed", "qkv", "attn", "resid", "gelu", "head", "accept", "route"]   # TSD_K_* order
 
 
@@ -51,6 +51,7 @@ SYMBOLS = {
     "tsd_target_verify": ([C.c_void_p, C.c_void_p], C.c_int),
     "tsd_accept_commit": ([C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_round": ([C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_run_rounds": ([C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_target_step": ([C.c_void_p, C.c_void_p], C.c_int),
     "tsd_num_active": ([C.c_void_p, C.POINTER(C.c_int32), C.c_void_p], C.c_int),
     "tsd_get_forecast": ([C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
@@ -247,6 +248,12 @@ class Session:
 
     def round(self):
         _check(lib().tsd_round(self.h, self._stream()), self.h)
+
+    def run_rounds(self, max_rounds=1 << 20):
+        """Rounds until every series has its horizon (or max_rounds): returns (rounds run, series still active)."""
+        r, n = C.c_int32(), C.c_int32()
+        _check(lib().tsd_run_rounds(self.h, max_rounds, C.byref(r), C.byref(n), self._stream()), self.h)
+        return r.value, n.value
 
     def target_step(self):
         _check(lib().tsd_target_step(self.h, self._stream()), self.h)

@@ -338,7 +338,7 @@ hipError_t launch_forecast_out(const float* forecast, const float* mean, const f
 // count[0] = number of active series, count[1] = the largest number of patches any of them still
 // needs (T - committed).
 __global__ __launch_bounds__(1024) void compact_active_kernel(const int* active, const int* committed, int T, int B,
-                                                              int* list, int* count) {
+                                                              int* list, int* count, int* host) {
   __shared__ int wave_cnt[16];
   __shared__ int base_s, max_rem;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -370,11 +370,20 @@ __global__ __launch_bounds__(1024) void compact_active_kernel(const int* active,
   if (threadIdx.x == 0) {
     count[0] = base_s;
     count[1] = max_rem;
+    if (host) {
+      // straight into pinned host memory, so the caller needs neither a copy nor a stream wait: it watches
+      // host[2] for this launch's number, which is stored last
+      const int seq = count[4] + 1;
+      count[4] = seq;
+      host[0] = base_s;
+      host[1] = max_rem;
+      __hip_atomic_store(&host[2], seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
   }
 }
 hipError_t launch_compact_active(const int* active, const int* committed, int T, int B, int* list, int* count,
-                                 hipStream_t st) {
-  hipLaunchKernelGGL(compact_active_kernel, dim3(1), dim3(1024), 0, st, active, committed, T, B, list, count);
+                                 int* host, hipStream_t st) {
+  hipLaunchKernelGGL(compact_active_kernel, dim3(1), dim3(1024), 0, st, active, committed, T, B, list, count, host);
   return hipGetLastError();
 }
 

@@ -1,6 +1,7 @@
 // Host side of libtsd: argument validation, arena carving, weight loading, and the sequencing of
 // kernel launches that make up prefill, draft proposal, single-pass verification, acceptance and
 // the target-only baseline step.  Nothing here allocates device memory.
+#include <chrono>
 #include <climits>
 #include <cmath>
 #include <cstdio>
@@ -66,6 +67,12 @@ struct tsd_ctx {
   float* moe_Y;
   char* moe_h;
   int* count_out;
+  // Pinned host words {active series, most patches still needed, launch number} that the compaction kernel
+  // writes itself (NULL when pinned memory could not be had: then the counts are copied back instead).
+  int* host_counts = nullptr;
+  int seq_launched = 0;          // compaction launches enqueued so far (the device keeps the same count)
+  bool seq_ready = false;        // the device-side launch counter has been zeroed
+  bool compact_pending = false;  // the last tsd_round already enqueued the compaction tsd_num_active wants
   int* act_list;   // series still decoding, ascending (device)
   int n_act;       // host copy of its length; -1 = unknown (use the full batch)
   long long* stats_out;
@@ -79,6 +86,7 @@ struct tsd_ctx {
   hipGraphExec_t graph_round[17] = {}, graph_step = nullptr;  // one round graph per number of positions
   bool capturing = false;  // a graph capture of this handle's launches is in progress
   int k_round = 0;  // positions the next round proposes: min(K, most patches any active series still needs)
+  int need_lb = 0;  // lower bound on the most patches any series still needs (0 = unknown)
   // measurement tap: event pairs around every launch of one kernel family
   int* refill_list = nullptr;      // device copy of the slots of the last tsd_refill
   std::vector<int> host_refill;
@@ -149,7 +157,8 @@ int check_config(const tsd_config* c, std::string& why) {
     return bad("sigma_p and sigma_q must be positive and finite");
   if (!(c->fallback_r >= 0.f) || c->fallback_r > c->sigma_p) return bad("fallback_r must lie in [0, sigma_p]");
   if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING | TSD_FLAG_NO_GRAPH | TSD_FLAG_NO_COMPACT | TSD_FLAG_NO_SKINNY | TSD_FLAG_SAMPLE_PROPOSALS |
-                   TSD_FLAG_NAIVE_VERIFY | TSD_FLAG_THRESHOLD_RULE | TSD_FLAG_BATCH_SYNC)) return bad("unknown flag bits");
+                   TSD_FLAG_NAIVE_VERIFY | TSD_FLAG_THRESHOLD_RULE | TSD_FLAG_BATCH_SYNC | TSD_FLAG_NO_PINNED_COUNTS))
+    return bad("unknown flag bits");
   if ((c->max_tokens + c->page_tokens - 1) / c->page_tokens > 64)
     return bad("max_tokens / page_tokens must not exceed 64 pages per series");
   for (const tsd_model_cfg* m : {&c->target, &c->draft})
@@ -646,6 +655,8 @@ int accept_commit_impl(tsd_ctx* ctx, const int32_t* forced, int K, hipStream_t s
   }
   HIP_TRY(ctx, timed_launch(ctx, TSD_K_ACCEPT, 4.0 * ctx->B * c.patch * (2.0 * K + 2), st, [&] { return launch_accept(a, st); }));
   ctx->injected = false;
+  ctx->compact_pending = false;  // whatever compaction was enqueued before describes an older state
+  ctx->need_lb = 0;              // ... and so does the last count of patches still needed
   return TSD_OK;
 }
 
@@ -716,6 +727,21 @@ int tsd_create(const tsd_config* cfg, void* arena_dev, size_t arena_bytes, tsd_c
       return fail(nullptr, TSD_E_HIP, msg);
     }
   }
+  {
+    // a few pinned host words for the active-series counts, and the device-side launch counter that numbers
+    // their deliveries; without them tsd_num_active copies the counts back and waits on the stream
+    int* hc = nullptr;
+    if (!(cfg->flags & TSD_FLAG_NO_PINNED_COUNTS) && hipHostMalloc((void**)&hc, 64, hipHostMallocDefault) == hipSuccess && hc) {
+      hc[0] = hc[1] = hc[2] = 0;
+      if (hipMemset(ctx->count_out + 4, 0, 4) == hipSuccess) {
+        ctx->host_counts = hc;
+        ctx->seq_ready = true;
+      } else {
+        (void)hipHostFree(hc);
+      }
+    }
+    (void)hipGetLastError();
+  }
   if (cfg->target.n_experts > 0 || cfg->draft.n_experts > 0) {
     hipError_t e = prepare_moe();
     if (e != hipSuccess) {
@@ -748,6 +774,7 @@ int tsd_destroy(tsd_ctx* ctx) {
   if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
   hipError_t e = hipDeviceSynchronize();
   drop_graphs(ctx);
+  if (ctx->host_counts) (void)hipHostFree(ctx->host_counts);
   for (auto& ev : ctx->prof_events) {
     (void)hipEventDestroy(ev.first);
     (void)hipEventDestroy(ev.second);
@@ -822,7 +849,9 @@ int tsd_prefill(tsd_ctx* ctx, const float* series_dev, int32_t B, int32_t n_ctx_
   hipStream_t st = (hipStream_t)stream;
   ctx->prefilled = false;
   ctx->n_act = -1;
+  ctx->compact_pending = false;
   ctx->k_round = 0;
+  ctx->need_lb = T;  // every series needs all T patches
   drop_graphs(ctx);  // batch size, context length and horizon are baked into the captured launches
   // page table: every series reserves the pages its whole forecast can touch
   const int need = (N + T + ctx->K_max + c.page_tokens - 1) / c.page_tokens;
@@ -913,7 +942,9 @@ int tsd_refill(tsd_ctx* ctx, const int32_t* slots_host, int32_t n, const float* 
       if ((rc = run_pass(ctx, ps, st))) return rc;
     }
   ctx->n_act = -1;  // the active list is stale until the next tsd_num_active
+  ctx->compact_pending = false;
   ctx->k_round = 0;
+  ctx->need_lb = 0;
   return TSD_OK;
 }
 
@@ -925,7 +956,9 @@ int tsd_reset_decode(tsd_ctx* ctx, void* stream) {
               ctx->count_out, ctx->B, ctx->T};
   HIP_TRY(ctx, launch_reset(pp, (hipStream_t)stream));
   ctx->n_act = -1;  // every series is active again
+  ctx->compact_pending = false;
   ctx->k_round = 0;
+  ctx->need_lb = ctx->T;  // every series needs all T patches again
   return TSD_OK;
 }
 
@@ -1055,12 +1088,24 @@ int tsd_accept_commit(tsd_ctx* ctx, const int32_t* forced_len_dev, void* stream)
 int tsd_round(tsd_ctx* ctx, void* stream) {
   int rc = require_ready(ctx, true);
   if (rc) return rc;
-  return run_graphed(ctx, &ctx->graph_round[round_positions(ctx)], (hipStream_t)stream, [&]() {
+  // With pinned host words at hand the round ends with the compaction tsd_num_active would otherwise have to
+  // launch, copy back and wait for: the caller's next tsd_num_active only watches the host words.
+  const bool deliver = ctx->host_counts && ctx->seq_ready;
+  rc = run_graphed(ctx, &ctx->graph_round[round_positions(ctx)], (hipStream_t)stream, [&]() {
     int r;
     if ((r = tsd_draft_propose(ctx, stream))) return r;
     if ((r = tsd_target_verify(ctx, stream))) return r;
-    return tsd_accept_commit(ctx, nullptr, stream);
+    if ((r = tsd_accept_commit(ctx, nullptr, stream))) return r;
+    if (deliver)
+      HIP_TRY(ctx, launch_compact_active(ctx->active, ctx->committed, ctx->T, ctx->B, ctx->act_list, ctx->count_out,
+                                         ctx->host_counts, (hipStream_t)stream));
+    return (int)TSD_OK;
   });
+  if (rc == TSD_OK && deliver) {
+    ctx->seq_launched++;
+    ctx->compact_pending = true;
+  }
+  return rc;
 }
 
 int tsd_target_step(tsd_ctx* ctx, void* stream) {
@@ -1097,14 +1142,66 @@ int tsd_num_active(tsd_ctx* ctx, int32_t* out_host, void* stream) {
   if (!out_host) return fail(ctx, TSD_E_INVALID_ARG, "out_host is NULL");
   hipStream_t st = (hipStream_t)stream;
   int32_t both[2] = {0, 0};
-  HIP_TRY(ctx, launch_compact_active(ctx->active, ctx->committed, ctx->T, ctx->B, ctx->act_list, ctx->count_out, st));
-  HIP_TRY(ctx, hipMemcpyAsync(both, ctx->count_out, 8, hipMemcpyDeviceToHost, st));
-  HIP_TRY(ctx, hipStreamSynchronize(st));
+  if (ctx->host_counts && ctx->seq_ready) {
+    if (!ctx->compact_pending) {
+      HIP_TRY(ctx, launch_compact_active(ctx->active, ctx->committed, ctx->T, ctx->B, ctx->act_list, ctx->count_out,
+                                         ctx->host_counts, st));
+      ctx->seq_launched++;
+    }
+    ctx->compact_pending = false;
+    // Watch the pinned words for this launch's number (stored last by the kernel); a wait on the stream
+    // is the fallback if it does not show up within a second.
+    const auto t0 = std::chrono::steady_clock::now();
+    bool seen = false;
+    for (unsigned spins = 0;; ++spins) {
+      if (__atomic_load_n(&ctx->host_counts[2], __ATOMIC_ACQUIRE) == ctx->seq_launched) {
+        seen = true;
+        break;
+      }
+      if ((spins & 1023) == 1023 && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(1)) break;
+      __builtin_ia32_pause();
+    }
+    if (!seen) {
+      HIP_TRY(ctx, hipStreamSynchronize(st));
+      if (__atomic_load_n(&ctx->host_counts[2], __ATOMIC_ACQUIRE) != ctx->seq_launched)
+        return fail(ctx, TSD_E_HIP, "the active-series count was not delivered");
+    }
+    both[0] = ctx->host_counts[0];
+    both[1] = ctx->host_counts[1];
+  } else {
+    HIP_TRY(ctx, launch_compact_active(ctx->active, ctx->committed, ctx->T, ctx->B, ctx->act_list, ctx->count_out, nullptr, st));
+    HIP_TRY(ctx, hipMemcpyAsync(both, ctx->count_out, 8, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+  }
   *out_host = both[0];
   if (!(ctx->cfg.flags & TSD_FLAG_NO_COMPACT)) {
     ctx->n_act = both[0];    // later passes cover only these series ...
     ctx->k_round = both[1];  // ... and only the positions one of them can still commit
   }
+  ctx->need_lb = both[1];
+  return TSD_OK;
+}
+
+int tsd_run_rounds(tsd_ctx* ctx, int32_t max_rounds, int32_t* rounds_host, int32_t* active_host, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  if (max_rounds < 1) return fail(ctx, TSD_E_INVALID_ARG, "max_rounds must be at least 1");
+  int32_t rounds = 0, active = -1;
+  int lb = ctx->need_lb;  // lower bound on the most patches any series still needs (0: unknown)
+  while (rounds < max_rounds) {
+    const int per_round = ctx->cfg.K + 1;  // the most a series can commit in one round
+    if ((rc = tsd_round(ctx, stream))) return rc;
+    ++rounds;
+    if (lb > per_round && rounds < max_rounds) {
+      lb -= per_round;  // somebody still needs patches after this round: no need to ask
+      continue;
+    }
+    if ((rc = tsd_num_active(ctx, &active, stream))) return rc;
+    lb = ctx->need_lb;
+    if (active == 0) break;
+  }
+  if (rounds_host) *rounds_host = rounds;
+  if (active_host) *active_host = active;
   return TSD_OK;
 }
 

@@ -207,9 +207,11 @@ hipError_t launch_combine(int dtype, const float* Y, const int* slot_of, const f
 
 hipError_t launch_forecast_out(const float* forecast, const float* mean, const float* sdev, const int* committed,
                                float* out, int B, int P, int T, int H, hipStream_t st);
-// stable list of the series with active != 0; count[0] = how many, count[1] = max over them of T - committed
+// stable list of the series with active != 0; count[0] = how many, count[1] = max over them of T - committed.
+// host (nullable): pinned host words; the kernel also bumps its launch counter count[4] and delivers
+// host[0] = count[0], host[1] = count[1], then host[2] = the new counter value (system-scope release).
 hipError_t launch_compact_active(const int* active, const int* committed, int T, int B, int* list, int* count,
-                                 hipStream_t st);
+                                 int* host, hipStream_t st);
 // active list = identity, count[0] = B, count[1] = T
 hipError_t launch_identity_list(int* list, int* count, int B, int T, hipStream_t st);
 hipError_t launch_sum_stats(const long long* stat, int B, long long* out5, hipStream_t st);

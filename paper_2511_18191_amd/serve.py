@@ -74,8 +74,7 @@ def run_batches(sess, contexts, n_ctx, horizon):
     out = torch.empty(S, horizon, dtype=torch.float32, device=sess.device)
     for s0 in range(0, S, B):
         sess.prefill(ctx_dev[s0:s0 + B], n_ctx, horizon)
-        while sess.num_active() > 0:
-            sess.round()
+        sess.run_rounds()
         fc = sess.get_forecast()
         with torch.cuda.stream(sess.stream):
             out[s0:s0 + B] = fc

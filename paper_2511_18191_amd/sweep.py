@@ -27,12 +27,7 @@ from .binding import session_for
 
 def _decode_spec(sess):
     sess.reset_decode()
-    rounds = 0
-    while True:
-        sess.round()
-        rounds += 1
-        if sess.num_active() == 0:
-            return rounds
+    return sess.run_rounds()[0]
 
 
 def _decode_target(sess, T):

@@ -121,3 +121,37 @@ def test_calibrated_temperature_hits_the_rate_and_the_oracle_agrees():
         if st["near_ties"] == 0:
             assert (st["tested"], st["accepted"]) == (tested, accepted)
         assert abs(accepted / tested - target) <= 0.06
+
+
+@pytest.mark.parametrize("name", ["cfg1", "mini3", "mini5"])
+def test_run_rounds_is_the_written_out_loop(name):
+    # the in-library loop (counts through pinned host words, the count skipped while the neediest series
+    # certainly needs another round) against round + num_active called one by one: same bits, same counters
+    from harness import Case
+    case = Case(name, sigma=0.5)
+    c = case.cfg
+    # the written-out loop also takes the route without pinned host words (copy + stream wait)
+    a, b = case.session(flags=tsd.TSD_FLAG_NO_PINNED_COUNTS), case.session()
+    a.prefill(case.context, c.n_ctx, c.horizon)
+    b.prefill(case.context, c.n_ctx, c.horizon)
+    for rep in range(2):                      # the second decode runs from reset, on replayed graphs
+        if rep:
+            a.reset_decode()
+            b.reset_decode()
+        rounds = 0
+        while True:
+            a.round()
+            rounds += 1
+            if a.num_active() == 0:
+                break
+        r, left = b.run_rounds()
+        assert (r, left) == (rounds, 0)
+        assert np.array_equal(a.get_forecast().cpu().numpy(), b.get_forecast().cpu().numpy())
+        assert a.get_stats() == b.get_stats()
+    # a cap on the number of rounds is honoured and reports who is left
+    b.reset_decode()
+    r, left = b.run_rounds(max_rounds=1)
+    assert r == 1 and left == b.num_active() and (left > 0 or c.T <= c.K + 1)
+    r2, left2 = b.run_rounds()
+    assert left2 == 0 and r + r2 >= rounds - 1
+    assert np.isfinite(b.get_forecast().cpu().numpy()).all()
