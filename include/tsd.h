@@ -208,7 +208,8 @@ int tsd_round(tsd_ctx* ctx, void* stream);
  *   do { tsd_round; tsd_num_active; } while (active > 0)
  * kept inside the library, so that nothing but the count's delivery stands between two rounds.
  * A round commits at most K + 1 patches per series, so while the neediest series is known to need
- * more than that, the next round is enqueued without waiting for the count.  Results are those of
+ * more than that, the next round is enqueued without waiting for the count (only for handles whose
+ * passes follow the device-side count; routed models size their passes from every count).  Results are those of
  * the written-out loop, bit for bit.  rounds_host (nullable) receives the number of rounds run,
  * active_host (nullable) the number of series still active at the end.  Synchronises `stream`
  * like tsd_num_active. */

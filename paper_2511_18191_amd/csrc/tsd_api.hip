@@ -1192,7 +1192,8 @@ int tsd_run_rounds(tsd_ctx* ctx, int32_t max_rounds, int32_t* rounds_host, int32
     const int per_round = ctx->cfg.K + 1;  // the most a series can commit in one round
     if ((rc = tsd_round(ctx, stream))) return rc;
     ++rounds;
-    if (lb > per_round && rounds < max_rounds) {
+    // (handles whose passes are sized on the host need every count: it is what shrinks their passes)
+    if (lb > per_round && rounds < max_rounds && device_counts(ctx)) {
       lb -= per_round;  // somebody still needs patches after this round: no need to ask
       continue;
     }
