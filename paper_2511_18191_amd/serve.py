@@ -36,9 +36,12 @@ def run_stream(sess, contexts, n_ctx, horizon, track=False):
         for s in range(B):
             placement[s] = (s, 0)
     nxt, pending = B, B
+    live = B                            # slots that were decoding after the last look
     while pending:
         sess.round()
-        sess.num_active()
+        n = sess.num_active()
+        if n == live:                   # nobody finished in this round: nothing to harvest
+            continue
         committed = sess.get_state()["committed"].cpu().numpy()
         done = [b for b in range(B) if owner[b] >= 0 and committed[b] >= T]
         if not done:
@@ -60,9 +63,10 @@ def run_stream(sess, contexts, n_ctx, horizon, track=False):
                 owner[b] = nxt + j
             nxt += take
             pending += take
-            sess.num_active()
+            n = sess.num_active()
         for b in done[take:]:
             owner[b] = -1
+        live = n
     return out, placement
 
 
