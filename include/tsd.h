@@ -16,7 +16,9 @@
  *     NULL handle, for the most recent failure of a call that had no handle).
  *   - Pointers named *_dev are DEVICE pointers, *_host are HOST pointers.  The caller owns all
  *     device memory (arena, weight blobs, I/O buffers); the library owns only the opaque
- *     handle and never frees or allocates device memory.
+ *     handle and never frees or allocates device memory.  Each handle also holds 64 bytes of
+ *     pinned host memory (allocated by tsd_create, freed by tsd_destroy): the words through
+ *     which the active-series counts reach the host (see tsd_num_active).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All calls are
  *     asynchronous on that stream except where stated.  Calls on one handle must be issued
  *     from one thread at a time and on one stream at a time.
