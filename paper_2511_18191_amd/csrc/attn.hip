@@ -216,8 +216,9 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
   }
 }
 
-// ---- bf16, head_dim 64: attention on the matrix cores, no LDS (core in attn_mfma.h) -------------
+// ---- bf16, head_dim 64: attention on the matrix cores (core in attn_mfma.h) ---------------------
 __global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnP p) {
+  __shared__ __attribute__((aligned(16))) bf16 vt[2 * 32 * 64];  // the V rows of two 32-key steps
   const int lane = threadIdx.x;
   const int bl = blockIdx.x / p.Hh, h = blockIdx.x % p.Hh;
   const int b = p.act ? p.act[bl] : p.s0 + bl;  // (entries past the active count are stale but valid series)
@@ -232,7 +233,7 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnP p) {
     const bf16* qt = q + ((long)bl * p.nq + q0) * p.D + h * 64;
     bf16* ot = out + ((long)bl * p.nq + q0) * p.D + h * 64;
     attn_tile_mfma(pool, h, p.Hh, p.PT, p.pt_shift, my_page, base + q0, nqt, p.scale,
-                   [&](int r) { return qt + (long)r * p.D; }, [&](int r) { return ot + (long)r * p.D; });
+                       [&](int r) { return qt + (long)r * p.D; }, [&](int r) { return ot + (long)r * p.D; }, vt);
   }
 }
 
@@ -280,7 +281,7 @@ static hipError_t launch_t(const AttnP& p, hipStream_t st, int s_pad, size_t sme
 
 hipError_t launch_attention(int dtype, const AttnP& p, int s_max, hipStream_t st) {
   if (p.B <= 0 || p.nq <= 0 || s_max <= 0) return hipErrorInvalidValue;
-  if (p.v_transposed) {
+  if (p.mfma) {
     if (dtype != TSD_BF16 || p.hd != 64 || p.PT < 8) return hipErrorInvalidValue;
     hipLaunchKernelGGL(attn_mfma_kernel, dim3((unsigned)(p.B * p.Hh)), dim3(64), 0, st, p);
     return hipGetLastError();

@@ -1,14 +1,21 @@
 // Core of the bf16, head_dim-64 attention on the matrix cores: one wavefront handles up to 16
-// query rows of one (series, head) against that series' paged KV cache, without LDS.
+// query rows of one (series, head) against that series' paged KV cache.
 //
-// V is cached transposed inside a page ([head][dim][token]) so that both MFMA B-operands are
-// single 16-byte loads.  Keys go in steps of 32:
+// K and V pages are row-major ([head][token][dim]), so a new token's K and V are one contiguous
+// 128-byte row each per head.  Keys go in steps of 32:
 //   S^T = K Q^T   two 16x16x32 MFMAs per 16 keys; key rows are permuted so that lane group g
 //                 (lane / 16) ends up with scores of the 8 consecutive keys 8g .. 8g+7 of the step
 //                 for query lane % 16 -- exactly the A-operand layout of the next product;
 //   online softmax in fp32 (running max / sum per query, shared by its 4 lanes);
-//   O += P V      four 16x16x32 MFMAs (one per 16 output dims), V^T chunks straight from memory.
+//   O += P V      four 16x16x32 MFMAs (one per 16 output dims).  Their B operand wants, per lane,
+//                 eight consecutive tokens of one dim: the 32 V rows of a step are fetched with
+//                 coalesced 16-byte loads, parked in LDS (8 KB per wavefront for two steps) and
+//                 picked up transposed with ds_read_b64_tr_b16.
 // Every K and V byte of the head is read exactly once per tile.
+// (A cache that keeps V transposed, [head][dim][token], makes that operand a plain 16-byte load, but
+// every new token then costs 64 two-byte stores over 16 cache lines per head in the QKV epilogue:
+// 5 % of a verification pass and 9 % of a one-token step at batch 1024, against nothing measurable
+// for the transposing read.)
 #pragma once
 #include "tsd_internal.h"
 
@@ -17,9 +24,10 @@ namespace tsd {
 // pool: this layer's KV pool; my_page: this lane's entry of the series' page table (lane i holds
 // page i); base: absolute position of the tile's first query; nqt: queries in the tile (1..16);
 // q_row(r) / out_row(r): pointers to the 64 dims of query / output row r of the tile.
+// vt: LDS, bf16 [2][32][64], private to the wavefront (the workgroup is one wavefront).
 template <typename QRow, typename ORow>
 __device__ __forceinline__ void attn_tile_mfma(const bf16* pool, int h, int Hh, int PT, int pts, int my_page, int base,
-                                               int nqt, float scale, QRow q_row, ORow out_row) {
+                                               int nqt, float scale, QRow q_row, ORow out_row, bf16* vt) {
   const int lane = threadIdx.x & 63;
   const int qi = lane & 15, g = lane >> 4;
   const long page_elems = (long)2 * Hh * PT * 64;
@@ -49,12 +57,44 @@ __device__ __forceinline__ void attn_tile_mfma(const bf16* pool, int h, int Hh, 
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) kf[st][bi][kk] = *reinterpret_cast<const bf16x8*>(kp + kk * 32 + g * 8);
       }
-      // B-operand of P.V: 8 consecutive tokens sb + 8g .. of one dim, from the transposed V block
-      const int vkey = min(sb + 8 * g, ((total - 1) >> 3) << 3);
-      const int vpage = __shfl(my_page, vkey >> pts);
-      const bf16* vp = pool + vpage * page_elems + v_off + (long)h * 64 * PT + (vkey & (PT - 1));
+      // V: 8 lanes fetch one 128-byte row; load i of the lane is row (lane / 8) + 8 i of the step
 #pragma unroll
-      for (int nb = 0; nb < 4; ++nb) vf[st][nb] = *reinterpret_cast<const bf16x8*>(vp + (long)(nb * 16 + qi) * PT);
+      for (int i = 0; i < 4; ++i) {
+        const int key = min(sb + (lane >> 3) + 8 * i, total - 1);
+        const int page = __shfl(my_page, key >> pts);
+        vf[st][i] = *reinterpret_cast<const bf16x8*>(pool + page * page_elems + v_off + ((long)h * PT + (key & (PT - 1))) * 64 +
+                                                     (lane & 7) * 8);
+      }
+    }
+    {
+      // through LDS: row r of a step lands rotated by 16 (r / 8) dims, so that the four key groups of a
+      // transposed read fall on different banks
+      __syncthreads();  // (a one-wavefront workgroup: orders the previous trip's reads before these writes)
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          *reinterpret_cast<bf16x8*>(vt + (st * 32 + (lane >> 3) + 8 * i) * 64 + (((lane & 7) * 8 + 16 * i) & 63)) = vf[st][i];
+      __syncthreads();
+      // LDS transpose read (ds_read_b64_tr_b16): within 16 lanes, lane i receives element i % 4 of the
+      // 8-byte chunks addressed by lanes i / 4, i / 4 + 4, i / 4 + 8, i / 4 + 12.  Lane L of key group g
+      // therefore points at row 8g + 4 half + L / 4, dims 16 nb + 4 (L % 4) .., and lane qi gets the four
+      // tokens 8g + 4 half .. of dim 16 nb + qi: one half of its B operand per read.
+      typedef short short4v __attribute__((ext_vector_type(4)));
+      typedef short short8v __attribute__((ext_vector_type(8)));
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+          short4v hv[2];
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const bf16* src = vt + (st * 32 + 8 * g + 4 * half + (qi >> 2)) * 64 + ((nb * 16 + 4 * (qi & 3) + 16 * g) & 63);
+            hv[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)src);
+          }
+          const short8v both = __builtin_shufflevector(hv[0], hv[1], 0, 1, 2, 3, 4, 5, 6, 7);
+          vf[st][nb] = __builtin_bit_cast(bf16x8, both);
+        }
     }
 #pragma unroll
     for (int st = 0; st < 2; ++st) {

@@ -382,32 +382,6 @@ __global__ __launch_bounds__(256 * G) void gemm_kernel(const GemmP p) {
         for (int j = 0; j < 4; ++j) Cs[(ty * 4 + i) * LDC + tx * 4 + j] = accf[i][j];
     }
     __syncthreads();
-    if constexpr (EP == EP_QKV && kBf) {
-      // Tiles that lie wholly in V go to the transposed page blocks ([head][dim][token]) element by
-      // element, with the lanes of a wavefront covering 16 consecutive rows x 4 consecutive dims:
-      // consecutive rows of one series are consecutive tokens (2 bytes apart) and 4 dims share one
-      // 128-byte line of the block, so a store instruction touches a handful of lines instead of
-      // sixteen (the cache sees ~5x fewer write requests than with 4-dim groups per lane).
-      if (p.v_transposed && n0 >= 2 * p.D) {
-        const int w16 = ((tid >> 6) & 3) * 16 + (tid & 15);  // this lane's row of the 64-row pass
-        const int rs_row = pass * 64 + w16;
-        const int gm = m0 + rs_row;
-        if (gm < m_lim) {
-          const float rs = row_scale[rs_row];
-          const int pos = row_pos[rs_row], page = row_page[rs_row];
-          T* blk = reinterpret_cast<T*>(p.kv_pool) + ((long)page * 2 + 1) * p.Hh * p.PT * 64 + (pos & (p.PT - 1));
-#pragma unroll 4
-          for (int it = grp * (BN / 4 / G); it < (grp + 1) * (BN / 4 / G); ++it) {
-            const int col = it * 4 + ((tid >> 4) & 3);
-            const int gn = n0 + col;
-            if (gn >= N) continue;
-            const int c = gn - 2 * p.D;  // column inside V: head c / 64, dim c % 64
-            blk[(long)(c >> 6) * p.PT * 64 + (long)(c & 63) * p.PT] = (T)(read_c1(w16, col) * rs);
-          }
-        }
-        continue;
-      }
-    }
     constexpr int GPR = BN / 4;  // 4-column groups per row
 #pragma unroll
     for (int it = 0; it < 64 * GPR / NT; ++it) {
@@ -470,17 +444,8 @@ __global__ __launch_bounds__(256 * G) void gemm_kernel(const GemmP p) {
         } else {
           const int page = row_page[pass * 64 + row];
           const int tok = pos & (p.PT - 1);
-          if (which == 2 && p.v_transposed) {
-            // V block stored [head][dim][token]: four strided element stores
-            T* vp = reinterpret_cast<T*>(p.kv_pool) + (((long)page * 2 + 1) * p.Hh + h) * p.PT * hd + (long)d * p.PT + tok;
-            vp[0] = (T)v.x;
-            vp[p.PT] = (T)v.y;
-            vp[2 * p.PT] = (T)v.z;
-            vp[3 * p.PT] = (T)v.w;
-          } else {
-            const long off = ((((long)page * 2 + (which - 1)) * p.Hh + h) * p.PT + tok) * hd + d;
-            store4<T>(reinterpret_cast<T*>(p.kv_pool) + off, v);
-          }
+          const long off = ((((long)page * 2 + (which - 1)) * p.Hh + h) * p.PT + tok) * hd + d;
+          store4<T>(reinterpret_cast<T*>(p.kv_pool) + off, v);
         }
       }
     }

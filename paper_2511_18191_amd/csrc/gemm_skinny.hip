@@ -258,16 +258,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const GemmP p) {
     } else {
       const int page = row_page[row];
       const int tok = pos & (p.PT - 1);
-      if (which == 2 && p.v_transposed) {
-        bf16* vp = reinterpret_cast<bf16*>(p.kv_pool) + (((long)page * 2 + 1) * p.Hh + h) * p.PT * hd + (long)d * p.PT + tok;
-        vp[0] = (bf16)v.x;
-        vp[p.PT] = (bf16)v.y;
-        vp[2 * p.PT] = (bf16)v.z;
-        vp[3 * p.PT] = (bf16)v.w;
-      } else {
-        const long off = ((((long)page * 2 + (which - 1)) * p.Hh + h) * p.PT + tok) * hd + d;
-        store4_bf16(reinterpret_cast<bf16*>(p.kv_pool) + off, v);
-      }
+      const long off = ((((long)page * 2 + (which - 1)) * p.Hh + h) * p.PT + tok) * hd + d;
+      store4_bf16(reinterpret_cast<bf16*>(p.kv_pool) + off, v);
     }
   }
 }

@@ -23,7 +23,7 @@ struct Layer {
 struct ModelDev {
   tsd_model_cfg c;
   int hd;
-  int v_transposed;  // this model's V cache blocks are [head][dim][token]
+  int mfma_attn;     // attention on the matrix cores (bf16, head_dim 64, pages of at least 8 tokens)
   char* W_e;
   char* W_h;
   std::vector<Layer> layers;
@@ -198,7 +198,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
     if (md) {
       md->c = m;
       md->hd = hd;
-      md->v_transposed = (c.dtype == TSD_BF16 && hd == 64 && c.page_tokens >= 8) ? 1 : 0;
+      md->mfma_attn = (c.dtype == TSD_BF16 && hd == 64 && c.page_tokens >= 8) ? 1 : 0;
       md->W_e = at(o);
       md->layers.resize(m.n_layers);
       md->loaded = false;
@@ -391,7 +391,6 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     q.hd = md.hd;
     q.PT = c.page_tokens;
     q.pt_shift = __builtin_ctz(c.page_tokens);
-    q.v_transposed = md.v_transposed;
     HIP_TRY(ctx, timed_launch(ctx, TSD_K_QKV, 6.0 * M * D * D, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_QKV, q, st); }));
     AttnP a;
     std::memset(&a, 0, sizeof(a));
@@ -412,7 +411,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     a.D = D;
     a.PT = c.page_tokens;
     a.pt_shift = __builtin_ctz(c.page_tokens);
-    a.v_transposed = md.v_transposed;
+    a.mfma = md.mfma_attn;
     a.scale = 1.0f / std::sqrt((float)md.hd);
     // K and V rows of the shortest history this pass can see (N-1 cached tokens + the new ones), q and output rows
     const double attn_bytes = (double)ps.B * D * ctx->es * (2.0 * (ctx->N - 1 + ps.nq + (ps.base_pos ? ps.pos_off : 1 - ctx->N)) + 2.0 * ps.nq);

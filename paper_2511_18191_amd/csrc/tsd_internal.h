@@ -61,7 +61,7 @@ struct GemmP {
   void* Ct;       // EP_GELU: T [M][N]
   // EP_QKV
   void* q_out;    // T [M][D]
-  void* kv_pool;  // this layer's pool: T [n_pages][2][Hh][PT][hd]
+  void* kv_pool;  // this layer's pool: T [n_pages][2 (K, V)][Hh][PT][hd]
   const int* page_table;
   int pt_stride;
   const int* base_pos;  // per-series position of token 0 minus pos_off (NULL = 0)
@@ -74,7 +74,6 @@ struct GemmP {
   const float* rope_sin;  // [max_tokens][hd/2]
   int D, Hh, hd, PT;
   int pt_shift;  // log2(PT)
-  int v_transposed;  // V block of a page is [head][dim][token]
   // grouped (routed-FFN) mode: the row tiles come from a device-side map, one expert per tile
   const void* tile_map;  // int4 per row tile: (expert or -1, first slot, end slot of the expert, 0); NULL = dense
   const int* src_row;    // A row of slot s is src_row[s] (NULL: the slot itself)
@@ -101,7 +100,7 @@ struct AttnP {
   const int* n_dev;  // device-side series count (NULL: B): blocks of series >= *n_dev exit
   int nq, B, Hh, hd, D, PT;
   int pt_shift;  // log2(PT)
-  int v_transposed;  // V block of a page is [head][dim][token] (bf16 head_dim-64 MFMA attention)
+  int mfma;          // bf16, head_dim 64, pages of at least 8 tokens: the matrix-core kernel
   float scale;
 };
 
