@@ -79,8 +79,8 @@ def phase_times(torch, sess, reps=20):
 
 # HBM bytes per launch of each kernel family from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by the
 # copy-kernel calibration (profiles/traffic_cfg2_bench.md has the commands, raw values and factors)
-TRAFFIC = {"cfg2": {"resid": 8360400, "qkv": 8588061, "gelu": 6448329, "attn": 11916056, "head": 1221537,
-                    "embed": 1361866, "accept": 797552}}
+TRAFFIC = {"cfg2": {"resid": 8800101, "qkv": 6195097, "gelu": 6668130, "attn": 11121980, "head": 1287370,
+                    "embed": 1418090, "accept": 822359}}
 PEAK = {"bf16": 2500.0, "fp32": 157.3}   # dense MFMA bf16 / vector fp32, TFLOP/s
 HBM_PEAK = 8000.0                        # GB/s
 
