@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--threshold-rule", action="store_true", help="variant: accept iff ||x - mu_p||_d^2 <= sigma^2")
     ap.add_argument("--batch-sync", action="store_true", help="variant: all series keep the batch's smallest accepted count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-series", type=int, default=64, help="series in the oracle's bounded sample (~10-20 s of CPU work at cfg2)")
+    ap.add_argument("--cpu-series", type=int, default=128, help="series in the oracle's bounded sample (~15 s of CPU work at cfg2)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB copy kernel 5 times (known traffic, to scale profiler memory counters)")
     return ap.parse_args()
