@@ -11,24 +11,9 @@
 #include <type_traits>
 
 #include "tsd_internal.h"
+#include "gemm_epilogue.h"
 
 namespace tsd {
-
-template <typename T>
-__device__ __forceinline__ void store4(T* dst, float4 v);
-template <>
-__device__ __forceinline__ void store4<float>(float* dst, float4 v) {
-  *reinterpret_cast<float4*>(dst) = v;
-}
-template <>
-__device__ __forceinline__ void store4<bf16>(bf16* dst, float4 v) {
-  bf16x4 o;
-  o[0] = (bf16)v.x;
-  o[1] = (bf16)v.y;
-  o[2] = (bf16)v.z;
-  o[3] = (bf16)v.w;
-  *reinterpret_cast<bf16x4*>(dst) = o;
-}
 
 template <typename T, int AM, int EP, int BM, int BN, int BK, int G = 1>
 __global__ __launch_bounds__(256 * G) void gemm_kernel(const GemmP p) {
@@ -382,73 +367,7 @@ __global__ __launch_bounds__(256 * G) void gemm_kernel(const GemmP p) {
         for (int j = 0; j < 4; ++j) Cs[(ty * 4 + i) * LDC + tx * 4 + j] = accf[i][j];
     }
     __syncthreads();
-    constexpr int GPR = BN / 4;  // 4-column groups per row
-#pragma unroll
-    for (int it = 0; it < 64 * GPR / NT; ++it) {
-      const int g = tid + it * NT;
-      const int row = g / GPR, col = (g % GPR) * 4;
-      const int gm = m0 + pass * 64 + row, gn = n0 + col;
-      if (gm >= m_lim || gn >= N) continue;
-      float4 v = read_c4(row, col);
-      float rs = 1.f;
-      if constexpr (kNorm) {
-        rs = row_scale[pass * 64 + row];
-        v.x *= rs;
-        v.y *= rs;
-        v.z *= rs;
-        v.w *= rs;
-      }
-      if constexpr (EP == EP_STORE) {
-        *reinterpret_cast<float4*>(p.Cf + (long)gm * N + gn) = v;
-        if (kBf && p.Cb) store4<T>(reinterpret_cast<T*>(p.Cb) + (long)gm * N + gn, v);
-      } else if constexpr (EP == EP_RESID) {
-        float4* dst = reinterpret_cast<float4*>(p.Cf + (long)gm * N + gn);
-        float4 o;
-        if constexpr (kPrefetchC) o = oldc[it]; else o = *dst;
-        o.x += v.x;
-        o.y += v.y;
-        o.z += v.z;
-        o.w += v.w;
-        *dst = o;
-        if (kBf && p.Cb) store4<T>(reinterpret_cast<T*>(p.Cb) + (long)gm * N + gn, o);
-      } else if constexpr (EP == EP_GELU) {
-        v.x = gelu_tanh(v.x);
-        v.y = gelu_tanh(v.y);
-        v.z = gelu_tanh(v.z);
-        v.w = gelu_tanh(v.w);
-        store4<T>(reinterpret_cast<T*>(p.Ct) + (long)gm * N + gn, v);
-      } else if constexpr (EP == EP_HEAD) {
-        const int bl = gm / p.nq, t = gm % p.nq;
-        const int b = p.act ? p.act[bl] : bl;
-        if (t >= p.t_skip) *reinterpret_cast<float4*>(p.out + (long)b * p.out_stride_b + (long)(t - p.t_skip) * N + gn) = v;
-      } else {  // EP_QKV
-        const int D = p.D, hd = p.hd, half = hd >> 1;
-        const int which = gn / D, c = gn - which * D;
-        const int h = c / hd, d = c - h * hd;
-        const int pos = row_pos[pass * 64 + row];
-        if (which < 2) {
-          const bool lo = d < half;
-          const int pcol = lo ? col + half : col - half;
-          float4 pv = read_c4(row, pcol);
-          const int f = lo ? d : d - half;
-          const float4 cs = *reinterpret_cast<const float4*>(p.rope_cos + (long)pos * half + f);
-          const float4 sn = *reinterpret_cast<const float4*>(p.rope_sin + (long)pos * half + f);
-          const float sg = lo ? -rs : rs;
-          v.x = v.x * cs.x + sg * pv.x * sn.x;
-          v.y = v.y * cs.y + sg * pv.y * sn.y;
-          v.z = v.z * cs.z + sg * pv.z * sn.z;
-          v.w = v.w * cs.w + sg * pv.w * sn.w;
-        }
-        if (which == 0) {
-          store4<T>(reinterpret_cast<T*>(p.q_out) + (long)gm * D + c, v);
-        } else {
-          const int page = row_page[pass * 64 + row];
-          const int tok = pos & (p.PT - 1);
-          const long off = ((((long)page * 2 + (which - 1)) * p.Hh + h) * p.PT + tok) * hd + d;
-          store4<T>(reinterpret_cast<T*>(p.kv_pool) + off, v);
-        }
-      }
-    }
+    epilogue_pass<T, EP, kNorm, BN, NT, kPrefetchC>(p, read_c4, row_scale, row_pos, row_page, m0, n0, pass, m_lim, N, tid, oldc);
   }
 }
 
