@@ -405,7 +405,7 @@ int gemm_row_tile(int dtype, int M, int N, int force_bm) {
 // the choice depends on the shape of the product alone.
 static bool gemm_split(const GemmP& p) {
   const long t64 = (long)(p.tile_map ? p.n_mtiles : (p.M + 63) / 64) * ((p.N + 63) / 64);
-  return p.K >= 1024 && t64 <= 192;
+  return p.K >= 1024 && t64 <= 256;
 }
 
 template <typename T, int AM, int EP>
