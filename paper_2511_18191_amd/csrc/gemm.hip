@@ -394,7 +394,9 @@ int gemm_row_tile(int dtype, int M, int N, int force_bm) {
   if (dtype != TSD_BF16) return 64;
   if (force_bm) return force_bm;
   const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-  return t128 >= 192 ? 128 : 64;
+  // 128 x 128 tiles once there are at least 1.5 of them per CU; below that the 64 x 64 tiles, four times as many,
+  // keep more of the chip busy (threshold found by timing whole passes: 192 .. 1024 tried)
+  return t128 >= 384 ? 128 : 64;
 }
 
 // A long contraction with too few 64 x 64 tiles to cover the chip is bound by how fast the few busy
