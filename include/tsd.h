@@ -71,6 +71,8 @@ extern "C" {
 #define TSD_FLAG_THRESHOLD_RULE 128u /* variant: accept iff ||x_i - mu_p^(i)||_d^2 <= sigma_p^2, no draw */
 #define TSD_FLAG_BATCH_SYNC 256u   /* variant: every series keeps the batch's smallest accepted count */
 #define TSD_FLAG_NO_PINNED_COUNTS 512u /* tsd_num_active copies the counts back and waits on the stream */
+#define TSD_FLAG_NO_FUSED_DRAFT 1024u /* always run the draft phase kernel by kernel                       */
+#define TSD_FLAG_FUSED_DRAFT 2048u /* run the draft phase as one launch wherever that kernel is supported */
 
 typedef struct tsd_ctx tsd_ctx; /* opaque */
 
@@ -163,7 +165,13 @@ int tsd_reset_decode(tsd_ctx* ctx, void* stream);
  * sqrt(-2 ln u2) (cos, sin)(2 pi u3); element e takes number e mod 4.
  * Fills the internal X [B,K,P] (and mu_q [B,K,P] when sampling).  Once tsd_num_active has
  * reported that no active series needs K more patches, only min(K, largest need) steps run and
- * the later rows of X keep stale values (no series tests them). */
+ * the later rows of X keep stale values (no series tests them).
+ * A dense bf16 draft with head_dim 64 whose 16-row working set fits one compute unit's LDS can run
+ * the whole phase as ONE launch (a workgroup keeps a few series through all steps and layers,
+ * streaming the draft weights once per step); the per-row arithmetic is that of the kernel-by-kernel
+ * path up to the summation order inside the products.  It is the default where it was measured to
+ * win (draft weights of at most 4 MiB, widths in multiples of 256, max_batch 64..512);
+ * TSD_FLAG_FUSED_DRAFT selects it wherever it is supported, TSD_FLAG_NO_FUSED_DRAFT never. */
 int tsd_draft_propose(tsd_ctx* ctx, void* stream);
 
 /* Single-pass verification (Sec. "Single-Pass Verification"): one causal target pass over the
@@ -299,7 +307,8 @@ int tsd_set_sigma_diag(tsd_ctx* ctx, const float* sigma_p_dev, const float* sigm
 #define TSD_K_HEAD 5   /* RMSNorm + output-head GEMM                    */
 #define TSD_K_ACCEPT 6 /* acceptance + commit + rollback                */
 #define TSD_K_ROUTE 7  /* routed FFN: router, expert sort, gated combine (bytes) */
-#define TSD_K_COUNT 8
+#define TSD_K_DRAFT 8  /* the draft phase as one launch (flops of the passes it replaces) */
+#define TSD_K_COUNT 9
 int tsd_profile_begin(tsd_ctx* ctx, int kernel_class);
 int tsd_profile_end(tsd_ctx* ctx, int64_t* launches_host, double* ms_host, double* work_host, void* stream);
 

@@ -9,8 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 TSD_F32, TSD_BF16 = 0, 1
 TSD_TARGET, TSD_DRAFT = 0, 1
 TSD_FLAG_SCRAMBLE_PAGES, TSD_FLAG_NO_TEMPERING, TSD_FLAG_NO_GRAPH, TSD_FLAG_NO_COMPACT, TSD_FLAG_NO_SKINNY, TSD_FLAG_SAMPLE_PROPOSALS, TSD_FLAG_NAIVE_VERIFY = 1, 2, 4, 8, 16, 32, 64
-TSD_FLAG_THRESHOLD_RULE, TSD_FLAG_BATCH_SYNC, TSD_FLAG_NO_PINNED_COUNTS = 128, 256, 512
-KERNEL_CLASSES = ["embed", "qkv", "attn", "resid", "gelu", "head", "accept", "route"]   # TSD_K_* order
+TSD_FLAG_THRESHOLD_RULE, TSD_FLAG_BATCH_SYNC, TSD_FLAG_NO_PINNED_COUNTS, TSD_FLAG_NO_FUSED_DRAFT, TSD_FLAG_FUSED_DRAFT = 128, 256, 512, 1024, 2048
+KERNEL_CLASSES = ["embed", "qkv", "attn", "resid", "gelu", "head", "accept", "route", "draft"]   # TSD_K_* order
 
 
 class TsdModelCfg(C.Structure):

@@ -24,8 +24,11 @@ namespace tsd {
 // pool: this layer's KV pool; my_page: this lane's entry of the series' page table (lane i holds
 // page i); base: absolute position of the tile's first query; nqt: queries in the tile (1..16);
 // q_row(r) / out_row(r): pointers to the 64 dims of query / output row r of the tile.
-// vt: LDS, bf16 [2][32][64], private to the wavefront (the workgroup is one wavefront).
-template <typename QRow, typename ORow>
+// vt: LDS, bf16 [2][32][64], private to the wavefront.  kOneWave: the workgroup is this one wavefront
+// (then a workgroup barrier orders the tile's LDS traffic); otherwise the wavefront may be one of
+// several that run different trip counts, and only its own LDS operations, which the hardware
+// executes in issue order, are fenced.
+template <bool kOneWave = true, typename QRow, typename ORow>
 __device__ __forceinline__ void attn_tile_mfma(const bf16* pool, int h, int Hh, int PT, int pts, int my_page, int base,
                                                int nqt, float scale, QRow q_row, ORow out_row, bf16* vt) {
   const int lane = threadIdx.x & 63;
@@ -42,6 +45,15 @@ __device__ __forceinline__ void attn_tile_mfma(const bf16* pool, int h, int Hh, 
 #pragma unroll
   for (int nb = 0; nb < 4; ++nb) o[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.f;
+  auto lds_order = [] {
+    if constexpr (kOneWave) {
+      __syncthreads();
+    } else {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+  };
 
   for (int s0 = 0; s0 < total; s0 += 64) {  // two 32-key steps per trip, loads issued together
     bf16x8 kf[2][2][2], vf[2][4];
@@ -69,13 +81,13 @@ __device__ __forceinline__ void attn_tile_mfma(const bf16* pool, int h, int Hh, 
     {
       // through LDS: row r of a step lands rotated by 16 (r / 8) dims, so that the four key groups of a
       // transposed read fall on different banks
-      __syncthreads();  // (a one-wavefront workgroup: orders the previous trip's reads before these writes)
+      lds_order();  // the previous trip's reads before these writes
 #pragma unroll
       for (int st = 0; st < 2; ++st)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
           *reinterpret_cast<bf16x8*>(vt + (st * 32 + (lane >> 3) + 8 * i) * 64 + (((lane & 7) * 8 + 16 * i) & 63)) = vf[st][i];
-      __syncthreads();
+      lds_order();
       // LDS transpose read (ds_read_b64_tr_b16): within 16 lanes, lane i receives element i % 4 of the
       // 8-byte chunks addressed by lanes i / 4, i / 4 + 4, i / 4 + 8, i / 4 + 12.  Lane L of key group g
       // therefore points at row 8g + 4 half + L / 4, dims 16 nb + 4 (L % 4) .., and lane qi gets the four

@@ -27,6 +27,10 @@ struct ModelDev {
   char* W_e;
   char* W_h;
   std::vector<Layer> layers;
+  // second copy in MFMA-fragment order for the one-launch draft phase (draft only, NULL otherwise)
+  char* fW_e = nullptr;
+  char* fW_h = nullptr;
+  std::vector<Layer> flayers;
   float *rope_cos, *rope_sin;
   char* kv_pool;
   size_t layer_pool_bytes;
@@ -58,6 +62,7 @@ struct tsd_ctx {
   char* xb;   // its bf16 shadow (GEMM A operand in bf16 mode)
   char *qbuf, *abuf, *hbuf;
   int rows_max;
+  bool fused_draft = false;  // tsd_draft_propose is one launch (see draft_fused.hip)
   int skinny;  // all decode passes have at most 32 rows: they take the skinny GEMM (fixed per handle so that a
                // series' bits never depend on how many other series are still active)
   int* moe_ids;
@@ -157,8 +162,11 @@ int check_config(const tsd_config* c, std::string& why) {
     return bad("sigma_p and sigma_q must be positive and finite");
   if (!(c->fallback_r >= 0.f) || c->fallback_r > c->sigma_p) return bad("fallback_r must lie in [0, sigma_p]");
   if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING | TSD_FLAG_NO_GRAPH | TSD_FLAG_NO_COMPACT | TSD_FLAG_NO_SKINNY | TSD_FLAG_SAMPLE_PROPOSALS |
-                   TSD_FLAG_NAIVE_VERIFY | TSD_FLAG_THRESHOLD_RULE | TSD_FLAG_BATCH_SYNC | TSD_FLAG_NO_PINNED_COUNTS))
+                   TSD_FLAG_NAIVE_VERIFY | TSD_FLAG_THRESHOLD_RULE | TSD_FLAG_BATCH_SYNC | TSD_FLAG_NO_PINNED_COUNTS |
+                   TSD_FLAG_NO_FUSED_DRAFT | TSD_FLAG_FUSED_DRAFT))
     return bad("unknown flag bits");
+  if ((c->flags & TSD_FLAG_NO_FUSED_DRAFT) && (c->flags & TSD_FLAG_FUSED_DRAFT))
+    return bad("TSD_FLAG_FUSED_DRAFT and TSD_FLAG_NO_FUSED_DRAFT exclude each other");
   if ((c->max_tokens + c->page_tokens - 1) / c->page_tokens > 64)
     return bad("max_tokens / page_tokens must not exceed 64 pages per series");
   for (const tsd_model_cfg* m : {&c->target, &c->draft})
@@ -179,6 +187,25 @@ struct Carver {
     return r;
   }
 };
+
+// The whole draft phase as one kernel.  Supported: dense bf16 draft with head_dim 64 on the matrix-core
+// attention, widths in whole MFMA k-steps and column blocks, mean proposals, and everything it keeps in LDS
+// fits.  Chosen by default where it was measured to win: every workgroup streams all draft weights per
+// step, which beats a chain of launch-bound kernels only while those weights are small (at most 4 MiB, in
+// 8-step chunks) and the batch neither so small that the kernel-per-stage path runs its skinny products
+// nor so large that its tiled products fill the chip (64 .. 512 series).  TSD_FLAG_FUSED_DRAFT selects it
+// wherever it is supported, TSD_FLAG_NO_FUSED_DRAFT never.
+bool fused_draft_ok(const tsd_config& c) {
+  const tsd_model_cfg& d = c.draft;
+  const bool supported = c.dtype == TSD_BF16 && !(c.flags & TSD_FLAG_SAMPLE_PROPOSALS) && d.n_experts == 0 &&
+                         d.d_model == 64 * d.n_heads && c.page_tokens >= 8 && d.d_model % 32 == 0 && d.d_ff % 32 == 0 &&
+                         c.patch % 16 == 0 && d.n_layers <= kDraftFusedMaxLayers &&
+                         draft_fused_lds_bytes(d.d_model, d.d_ff, c.patch) <= 160 * 1024;
+  if (!supported || (c.flags & TSD_FLAG_NO_FUSED_DRAFT)) return false;
+  if (c.flags & TSD_FLAG_FUSED_DRAFT) return true;
+  const size_t wbytes = (size_t)d.n_layers * (4 * (size_t)d.d_model * d.d_model + 2 * (size_t)d.d_model * d.d_ff) * 2;
+  return draft_fused_chunk(d.d_model, d.d_ff) == 8 && wbytes <= ((size_t)4 << 20) && c.max_batch >= 64 && c.max_batch <= 512;
+}
 
 // Lays out everything the handle needs inside the arena.  With ctx == nullptr only sizes it.
 size_t carve(const tsd_config& c, tsd_ctx* ctx) {
@@ -211,6 +238,20 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
     }
     o = cv.take(D * P * es);
     if (md) md->W_h = at(o);
+    if (w == 1 && fused_draft_ok(c)) {
+      const int ch = draft_fused_chunk((int)D, (int)F);
+      auto frag = [&](size_t N, size_t K) { return cv.take(draft_fused_packed_elems((int)N, (int)K, ch) * 2); };
+      size_t fe = frag(D, P), fh = frag(P, D);
+      if (md) {
+        md->fW_e = at(fe);
+        md->fW_h = at(fh);
+        md->flayers.resize(m.n_layers);
+      }
+      for (int l = 0; l < m.n_layers; ++l) {
+        size_t fq = frag(3 * D, D), fo = frag(D, D), f1 = frag(F, D), f2 = frag(D, F);
+        if (md) md->flayers[l] = Layer{at(fq), at(fo), at(f1), at(f2), nullptr};
+      }
+    }
     size_t oc = cv.take((size_t)c.max_tokens * (hd / 2) * 4), os = cv.take((size_t)c.max_tokens * (hd / 2) * 4);
     if (md) {
       md->rope_cos = (float*)at(oc);
@@ -281,6 +322,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
     ctx->rows_max = (int)rows;
     ctx->K_max = K;
     ctx->skinny = (c.dtype == TSD_BF16 && !(c.flags & TSD_FLAG_NO_SKINNY) && (size_t)B * (K + 1) <= 32) ? 1 : 0;
+    ctx->fused_draft = fused_draft_ok(c);
     ctx->count_out = (int*)at(o_cnt);
     ctx->act_list = (int*)at(o_alist);
     ctx->refill_list = (int*)at(o_rlist);
@@ -757,6 +799,14 @@ int tsd_create(const tsd_config* cfg, void* arena_dev, size_t arena_bytes, tsd_c
       return fail(nullptr, TSD_E_HIP, msg);
     }
   }
+  if (ctx->fused_draft) {
+    hipError_t e = prepare_draft_fused();
+    if (e != hipSuccess) {
+      std::string msg = std::string("raising the fused draft kernel's LDS limit: ") + hipGetErrorString(e);
+      delete ctx;
+      return fail(nullptr, TSD_E_HIP, msg);
+    }
+  }
   for (int w = 0; w < 2; ++w) {
     hipError_t e = prepare_attention(cfg->dtype, ctx->model[w].hd, cfg->max_tokens, cfg->page_tokens);
     if (e != hipSuccess) {
@@ -832,6 +882,19 @@ int tsd_load_weights(tsd_ctx* ctx, int which, const float* blob_dev, size_t n_fl
   const float* gf = w;
   w += D;
   HIP_TRY(ctx, pack(w, gf, md.W_h, (int)D, (int)P));
+  if (which == TSD_DRAFT && ctx->fused_draft) {
+    auto frag = [&](const char* src, char* dst, size_t N, size_t K, int heads) {
+      return launch_repack_fragments(src, dst, (int)N, (int)K, draft_fused_chunk((int)D, (int)F), heads, (int)D, st);
+    };
+    HIP_TRY(ctx, frag(md.W_e, md.fW_e, D, P, 0));
+    HIP_TRY(ctx, frag(md.W_h, md.fW_h, P, D, 0));
+    for (int l = 0; l < md.c.n_layers; ++l) {
+      HIP_TRY(ctx, frag(md.layers[l].Wqkv, md.flayers[l].Wqkv, 3 * D, D, md.c.n_heads));
+      HIP_TRY(ctx, frag(md.layers[l].Wo, md.flayers[l].Wo, D, D, 0));
+      HIP_TRY(ctx, frag(md.layers[l].W1, md.flayers[l].W1, F, D, 0));
+      HIP_TRY(ctx, frag(md.layers[l].W2, md.flayers[l].W2, D, F, 0));
+    }
+  }
   md.loaded = true;
   return TSD_OK;
 }
@@ -974,6 +1037,52 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
   // never consumed it); for the other series the rewrite stores identical values.
   const Cover cv = cover(ctx);
   if (cv.n == 0) return TSD_OK;
+  if (ctx->fused_draft) {
+    const ModelDev& md = ctx->model[TSD_DRAFT];
+    DraftFusedP f;
+    std::memset(&f, 0, sizeof(f));
+    f.W_e = reinterpret_cast<const bf16*>(md.fW_e);
+    f.W_h = reinterpret_cast<const bf16*>(md.fW_h);
+    for (int l = 0; l < md.c.n_layers; ++l) {
+      f.Wqkv[l] = reinterpret_cast<const bf16*>(md.flayers[l].Wqkv);
+      f.Wo[l] = reinterpret_cast<const bf16*>(md.flayers[l].Wo);
+      f.W1[l] = reinterpret_cast<const bf16*>(md.flayers[l].W1);
+      f.W2[l] = reinterpret_cast<const bf16*>(md.flayers[l].W2);
+    }
+    f.kv_pool = reinterpret_cast<bf16*>(md.kv_pool);
+    f.layer_pool_elems = md.layer_pool_bytes / 2;
+    f.rope_cos = md.rope_cos;
+    f.rope_sin = md.rope_sin;
+    f.page_table = ctx->page_table;
+    f.pt_stride = ctx->pages_per_series;
+    f.len = ctx->len;
+    f.act = cv.act;
+    f.n_dev = cv.n_dev;
+    f.n = cv.n;
+    f.prev = ctx->prev;
+    f.pending = ctx->pending;
+    f.X = ctx->X;
+    f.x_stride = (long)K * P;
+    f.Kr = Kr;
+    f.L = md.c.n_layers;
+    f.D = md.c.d_model;
+    f.F = md.c.d_ff;
+    f.Hh = md.c.n_heads;
+    f.P = P;
+    f.PT = c.page_tokens;
+    f.pt_shift = __builtin_ctz(c.page_tokens);
+    f.scale = 1.0f / std::sqrt((float)md.hd);
+    f.chunk = draft_fused_chunk(f.D, f.F);
+    // series per workgroup: two keep a workgroup's attention stage to one (series, head) pair per wavefront
+    // at 4 heads; beyond 512 series more per workgroup keep the grid near one workgroup per compute unit.
+    // (From the batch the handle was created for: a series' bits do not depend on who else is active.)
+    f.spw = c.max_batch == 1 ? 1 : c.max_batch <= 512 ? 2 : c.max_batch <= 1024 ? 4 : 8;
+    // work: the flops of the Kr + 1 token passes it replaces
+    const double D = f.D, tok = (double)cv.n * (Kr + 1);
+    const double flops = 2.0 * tok * (2.0 * P * D + f.L * (4.0 * D * D + 2.0 * D * f.F));
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_DRAFT, flops, st, [&] { return launch_draft_fused(f, st); }));
+    return TSD_OK;
+  }
   Pass ps;
   std::memset(&ps, 0, sizeof(ps));
   ps.which = TSD_DRAFT;

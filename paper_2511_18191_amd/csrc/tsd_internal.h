@@ -117,6 +117,47 @@ hipError_t launch_attention(int dtype, const AttnP& p, int s_max, hipStream_t st
 size_t attention_lds_bytes(int dtype, int hd, int s_max, int page_tokens);
 hipError_t prepare_attention(int dtype, int hd, int s_max, int page_tokens);
 
+// ---- the draft phase in one launch (dense bf16 draft, head_dim 64): see draft_fused.hip ----
+constexpr int kDraftFusedSeries = 8;     // most series per workgroup
+constexpr int kDraftFusedMaxLayers = 8;
+struct DraftFusedP {
+  // the draft's weights in fragment order (launch_repack_fragments)
+  const bf16* W_e;  // of [D][P]
+  const bf16* W_h;  // of [P][D]
+  const bf16* Wqkv[kDraftFusedMaxLayers];  // of [3D][D], columns in rotary-pair order
+  const bf16* Wo[kDraftFusedMaxLayers];    // of [D][D]
+  const bf16* W1[kDraftFusedMaxLayers];    // of [F][D]
+  const bf16* W2[kDraftFusedMaxLayers];    // of [D][F]
+  bf16* kv_pool;           // the draft's pools, layer after layer
+  size_t layer_pool_elems;
+  const float* rope_cos;
+  const float* rope_sin;   // [max_tokens][32]
+  const int* page_table;
+  int pt_stride;           // pages per series (at most 64)
+  const int* len;          // committed tokens per series: the pending patch sits at position len
+  const int* act;          // slot j is series act[j] (NULL: series j)
+  const int* n_dev;        // device-side count of listed series (NULL: n)
+  int n;                   // listed series (the grid covers them)
+  int spw;                 // series per workgroup: 1, 2, 4 or 8
+  const float* prev;       // [B][P] token before the pending one
+  const float* pending;    // [B][P]
+  float* X;                // proposals: x_i of series b at X + b * x_stride + (i - 1) * P
+  long x_stride;
+  int Kr;                  // steps (proposals) of this round
+  int L, D, F, Hh, P, PT, pt_shift;
+  float scale;             // 1 / sqrt(head_dim)
+  int chunk;               // k-steps per streamed chunk the fragment copy was padded for: 4 or 8
+};
+size_t draft_fused_lds_bytes(int D, int F, int P);
+// k-steps per streamed chunk for a draft of these widths (the fragment copy pads every block's k to whole chunks)
+int draft_fused_chunk(int D, int F);
+// elements of the fragment-order copy of a bf16 [N][K] matrix
+size_t draft_fused_packed_elems(int N, int K, int chunk);
+// dst <- src [N][K] in fragment order; qkv_heads > 0: N = 3 D and the columns take the QKV block order
+hipError_t launch_repack_fragments(const void* src, void* dst, int N, int K, int chunk, int qkv_heads, int D, hipStream_t st);
+hipError_t prepare_draft_fused();
+hipError_t launch_draft_fused(const DraftFusedP& p, hipStream_t st);
+
 struct PackP {
   const float* W;     // [K][N] row-major source (y = x W)
   const float* gain;  // [K] or NULL: folded as W'[n][k] = gain[k] * W[k][n]
