@@ -81,8 +81,8 @@ def phase_times(torch, sess, reps=20):
 
 # HBM bytes per launch of each kernel family from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by the
 # copy-kernel calibration (profiles/traffic_cfg2_bench.md has the commands, raw values and factors)
-TRAFFIC = {"cfg2": {"resid": 8800101, "qkv": 6195097, "gelu": 6668130, "attn": 11121980, "head": 1287370,
-                    "embed": 1418090, "accept": 822359}}
+TRAFFIC = {"cfg2": {"resid": 12815024, "qkv": 8749845, "gelu": 9236859, "attn": 13896298, "head": 2648014,
+                    "embed": 3006557, "accept": 818561, "draft": 114459550}}
 PEAK = {"bf16": 2500.0, "fp32": 157.3}   # dense MFMA bf16 / vector fp32, TFLOP/s
 HBM_PEAK = 8000.0                        # GB/s
 
@@ -103,7 +103,8 @@ def kernel_rooflines(sess, dtype, steps, workload, cfg=None):
             # one launch runs all K draft steps; every workgroup streams the draft's weights once per step
             # through its compute unit's vector-memory path (64 B/clk at 2.4 GHz = 153.6 GB/s per unit)
             out[name] = dict(bound="cu_stream", launches=n, avg_us=ms * 1e3 / n, total_ms=ms,
-                             mfma_tflops=work / (ms * 1e-3) / 1e12, peak_gbs_per_cu=153.6, unit="GB/s per CU")
+                             mfma_tflops=work / (ms * 1e-3) / 1e12, peak_gbs_per_cu=153.6, unit="GB/s per CU",
+                             traffic=TRAFFIC.get(workload, {}).get(name))
             if cfg is not None:
                 d = cfg.draft
                 wbytes = 2 * (d.n_layers * (4 * d.d_model ** 2 + 2 * d.d_model * d.d_ff) + 2 * cfg.patch * d.d_model)

@@ -19,7 +19,7 @@ import numpy as np
 
 import synth
 
-from .binding import (TSD_FLAG_BATCH_SYNC, TSD_FLAG_NAIVE_VERIFY, TSD_FLAG_NO_TEMPERING, TSD_FLAG_SAMPLE_PROPOSALS,
+from .binding import (TSD_FLAG_BATCH_SYNC, TSD_FLAG_NAIVE_VERIFY, TSD_FLAG_NO_FUSED_DRAFT, TSD_FLAG_NO_TEMPERING, TSD_FLAG_SAMPLE_PROPOSALS,
                       TSD_FLAG_THRESHOLD_RULE, session_for)
 from .sweep import _decode_spec, _decode_target, _time
 
@@ -55,6 +55,7 @@ def main(argv=None):
     rows = [("full rule", 0, 0.0), ("w/o 1/d tempering", TSD_FLAG_NO_TEMPERING, 0.0),
             ("w/o mean proposal (x_i ~ q)", TSD_FLAG_SAMPLE_PROPOSALS, 0.0), ("w/o clean fallback (r = sigma)", 0, c.sigma),
             ("w/o single-pass verification", TSD_FLAG_NAIVE_VERIFY, 0.0),
+            ("full rule, draft phase kernel by kernel", TSD_FLAG_NO_FUSED_DRAFT, 0.0),
             ("batch-synchronised commits", TSD_FLAG_BATCH_SYNC, 0.0),
             ("threshold rule", TSD_FLAG_THRESHOLD_RULE, 0.0),
             ("threshold rule, batch-synchronised", TSD_FLAG_THRESHOLD_RULE | TSD_FLAG_BATCH_SYNC, 0.0),
