@@ -170,7 +170,8 @@ int tsd_reset_decode(tsd_ctx* ctx, void* stream);
  * the whole phase as ONE launch (a workgroup keeps a few series through all steps and layers,
  * streaming the draft weights once per step); the per-row arithmetic is that of the kernel-by-kernel
  * path up to the summation order inside the products.  It is the default where it was measured to
- * win (draft weights of at most 4 MiB, widths in multiples of 256, max_batch 64..256);
+ * win (draft weights of at most 4 MiB, widths in multiples of 256, more than 32 rows per pass and
+ * max_batch <= 384);
  * TSD_FLAG_FUSED_DRAFT selects it wherever it is supported, TSD_FLAG_NO_FUSED_DRAFT never. */
 int tsd_draft_propose(tsd_ctx* ctx, void* stream);
 
