@@ -110,3 +110,83 @@ def test_fused_draft_full_size_cfg2_in_step_with_the_unfused_path():
     for xa, xb in zip(a, b):
         assert np.isfinite(xa).all()
         assert rel_err(xa, xb).max() <= 1e-2
+
+
+def _decode(sess):
+    sess.run_rounds()
+    return sess.get_forecast().cpu().numpy().copy(), sess.get_stats()
+
+
+def test_fused_draft_page_scramble_batch_independence_and_small_pages():
+    """The one-launch draft walks the same page tables: physical page placement is invisible, a series alone
+    decodes as it does in the batch (whatever the other slots of its workgroup hold), 8-token pages work."""
+    case = Case("mini3", sigma=0.5)
+    c = case.cfg
+
+    def run(ctx, **kw):
+        sess = case.session(**kw)
+        sess.prefill(ctx, c.n_ctx, c.horizon)
+        return _decode(sess)[0]
+
+    full = run(case.context, flags=FUSED)
+    scr = run(case.context, flags=FUSED | tsd.TSD_FLAG_SCRAMBLE_PAGES, page_tokens=8)
+    np.testing.assert_array_equal(full, scr)
+    alone = run(case.context[:1], flags=FUSED)
+    np.testing.assert_array_equal(alone[0], full[0])
+    three = run(case.context[:3], flags=FUSED)       # an odd count: the last workgroup has a dead slot
+    np.testing.assert_array_equal(three, full[:3])
+
+
+@pytest.mark.parametrize("name,K,horizon,n_ctx", [("mini2", 1, 96, 2), ("mini2", 16, 96 * 20, 3), ("mini2", 3, 50, 6)])
+def test_fused_draft_edge_shapes(name, K, horizon, n_ctx):
+    """K = 1, K = 16 (maximum), a two-patch context, a horizon shorter than one patch."""
+    import dataclasses
+    case = Case(name, K=K, horizon=horizon, sigma=0.7)
+    case.cfg = dataclasses.replace(case.cfg, context=n_ctx * 96)
+    case.context = np.ascontiguousarray(case.series[:, : n_ctx * 96])
+    c = case.cfg
+    sess = case.session(flags=FUSED)
+    rep = lockstep(case, sess, tol=0.06 if K == 16 else None)
+    assert all(1 <= L <= K + 1 for L in rep["lengths"])
+    assert sess.num_active() == 0 and sess.get_stats()["committed"] == c.batch * c.T
+
+
+def test_fused_draft_block_size_change_equals_a_fresh_handle_bitwise():
+    big = Case("mini3", K=6, sigma=0.5)
+    small = Case("mini3", K=3, sigma=0.5)
+    c = small.cfg
+    flags = FUSED | tsd.TSD_FLAG_NO_SKINNY
+    s_big = big.session(flags=flags)
+    s_big.prefill(big.context, c.n_ctx, c.horizon)
+    s_big.set_block_size(3)
+    f1, st1 = _decode(s_big)
+    s_small = small.session(flags=flags)
+    s_small.prefill(small.context, c.n_ctx, c.horizon)
+    f2, st2 = _decode(s_small)
+    np.testing.assert_array_equal(f1, f2)
+    assert st1 == st2
+
+
+def test_fused_draft_stream_through_refilled_slots():
+    """Continuous batching: finished slots are refilled mid-decode and the one-launch draft picks the new
+    series up from the slot's state; draft = target accepts everything, so stream and batches agree exactly."""
+    from paper_2511_18191_amd import serve
+    case = Case("mini2", B=10, sigma=0.5, draft_is_target=True)
+    c = case.cfg
+    sess = case.session(max_batch=5, flags=FUSED)
+    out, _ = serve.run_stream(sess, case.context, c.n_ctx, c.horizon)
+    ref = serve.run_batches(sess, case.context, c.n_ctx, c.horizon)
+    np.testing.assert_array_equal(out.cpu().numpy(), ref.cpu().numpy())
+    # and against the kernel-by-kernel draft within the bf16 tolerance (identical decisions: all accepted)
+    sess2 = case.session(max_batch=5, flags=UNFUSED)
+    ref2 = serve.run_batches(sess2, case.context, c.n_ctx, c.horizon)
+    assert rel_err(out.cpu().numpy(), ref2.cpu().numpy()).max() <= 6e-2
+
+
+def test_fused_draft_with_threshold_rule_and_batch_sync():
+    case = Case("mini3", sigma=0.6)
+    c = case.cfg
+    sess = case.session(flags=FUSED | tsd.TSD_FLAG_THRESHOLD_RULE | tsd.TSD_FLAG_BATCH_SYNC)
+    rep = lockstep(case, sess, rule="threshold", sync=True)
+    assert rep["max_rel_X"] <= TOL[c.dtype] and rep["max_rel_mu_p"] <= TOL[c.dtype]
+    assert sess.get_stats()["committed"] == c.batch * c.T
