@@ -141,8 +141,13 @@ __device__ __forceinline__ void wave_gemm(const Wsrc& w, const Wsrc& next, const
   const int nks = w.nks, nch = w.nksp / CH;
   f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
   // (k-steps past nks meet zero fragments of W: their A operand is re-read from the last real step, no branch)
-  auto consume = [&](int item, const bf16x8 (&use)[CH]) {
-    const int j = item / nch, c = item - j * nch;
+  int cj = 0, cc = 0;  // block and chunk of the chunk consumed next (counted along: no division per chunk)
+  auto consume = [&](const bf16x8 (&use)[CH]) {
+    const int j = cj, c = cc;
+    if (++cc == nch) {
+      cc = 0;
+      ++cj;
+    }
     if constexpr (kSplit) {
 #pragma unroll
       for (int u = 0; u < CH; ++u) {
@@ -169,21 +174,34 @@ __device__ __forceinline__ void wave_gemm(const Wsrc& w, const Wsrc& next, const
       acc = f32x4{0.f, 0.f, 0.f, 0.f};
     }
   };
+  // chunk 3 is the next to fetch: its address, then a walk by pointer (chunks of a block are contiguous, the
+  // wavefront's next block lies NW blocks further on)
+  const long chunk_elems = (long)CH * 512, block_skip = (long)(NW - 1) * w.nksp * 512;
+  int fc = 3 % nch;
+  const bf16* fptr = w.Wp + lane * 8 + ((long)(wave + (3 / nch) * NW) * w.nksp + fc * CH) * 512;
   auto fetch = [&](int item, bf16x8 (&dst)[CH]) {
-    if (item < total) fetch_chunk<NW, CH>(w, item, wave, lane, dst);
+    if (item < total) {
+#pragma unroll
+      for (int u = 0; u < CH; ++u) dst[u] = *reinterpret_cast<const bf16x8*>(fptr + u * 512);
+    }
+    fptr += chunk_elems;
+    if (++fc == nch) {
+      fc = 0;
+      fptr += block_skip;
+    }
   };
   for (int it = 0; it < total; it += 4) {
     fetch(it + 3, B.b3);
-    consume(it, B.b0);
+    consume(B.b0);
     if (it + 1 >= total) break;
     fetch(it + 4, B.b0);
-    consume(it + 1, B.b1);
+    consume(B.b1);
     if (it + 2 >= total) break;
     fetch(it + 5, B.b1);
-    consume(it + 2, B.b2);
+    consume(B.b2);
     if (it + 3 >= total) break;
     fetch(it + 6, B.b2);
-    consume(it + 3, B.b3);
+    consume(B.b3);
   }
   prime<NW, CH>(next, wave, lane, B);
 }
@@ -291,6 +309,11 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
     }
     lds_barrier();
     auto row_live = [&](int r) { return r < nrows && j0 + (step == 1 ? r >> 1 : r) < n; };
+    // (the epilogues below read everything they need first, compute, then store: written with `if`s per
+    //  element they cost 1300 cycles per QKV block, mostly LDS round trips waited for one at a time)
+    bool live4[4];  // rows 4 lg + i of this lane's accumulators
+#pragma unroll
+    for (int i = 0; i < 4; ++i) live4[i] = row_live(4 * lg + i);
 
     // ---- patch embedding: x = W_e patch ----
     wave_gemm<NW, CH, true>(
@@ -314,23 +337,32 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
       // (with 4-step chunks the next product's first operands can stay in registers through the attention stage)
       constexpr bool kPrimeOverAttn = CH <= 4;
       wave_gemm<NW, CH, false>(w_qkv(l), kPrimeOverAttn ? w_o(l) : none, xb, ldb, wave, lane, B, [&](int blk, f32x4 acc) {
-        const int which = blk / (4 * Hh), rem = blk - which * 4 * Hh;
+        const int which = blk / (4 * Hh), rem = blk - which * 4 * Hh;  // (uniform over the wavefront)
         const int h = rem >> 2, f = (rem & 3) * 8 + (li & 7), d = f + (li >> 3) * 32;
-        const bool lo = li < 8;
+        float v[4], pv[4], cs[4], sn[4];
+        long kvo[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int r = 4 * lg + i;
-          float v = acc[i] * rs[i];
-          const float pv = __shfl_xor(v, 8);
-          if (which < 2) {
-            const float cs = rcos[r * 32 + f], sn = rsin[r * 32 + f];
-            v = v * cs + (lo ? -pv : pv) * sn;
-          }
-          if (which == 0) {
-            qb[r * ldb + h * 64 + d] = (bf16)v;
-          } else if (row_live(r)) {
-            pool[kvrow[r] + ((long)((which - 1) * Hh + h) * p.PT) * 64 + d] = (bf16)v;
-          }
+          cs[i] = rcos[(4 * lg + i) * 32 + f];
+          sn[i] = rsin[(4 * lg + i) * 32 + f];
+          kvo[i] = kvrow[4 * lg + i];
+          v[i] = acc[i] * rs[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pv[i] = __shfl_xor(v[i], 8);
+        if (which < 2) {
+          const float sg = li < 8 ? -1.f : 1.f;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[i] = v[i] * cs[i] + sg * pv[i] * sn[i];
+        }
+        if (which == 0) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) qb[(4 * lg + i) * ldb + h * 64 + d] = (bf16)v[i];
+        } else {
+          const long plane = ((long)((which - 1) * Hh + h) * p.PT) * 64 + d;
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (live4[i]) pool[kvo[i] + plane] = (bf16)v[i];
         }
       });
       __syncthreads();  // (also makes the cache rows written above visible to the workgroup's loads)
@@ -355,12 +387,15 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
       // ---- attention output projection + residual ----
       auto resid_epi = [&](int blk, f32x4 acc) {
         const int c = blk * 16 + li;
+        float o[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = xs[(4 * lg + i) * ldx + c];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] += acc[i];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int r = 4 * lg + i;
-          const float o = xs[r * ldx + c] + acc[i];
-          xs[r * ldx + c] = o;
-          xb[r * ldb + c] = (bf16)o;
+          xs[(4 * lg + i) * ldx + c] = o[i];
+          xb[(4 * lg + i) * ldb + c] = (bf16)o[i];
         }
       };
       wave_gemm<NW, CH, false>(w_o(l), w_1(l), ab, ldb, wave, lane, B, resid_epi);
@@ -370,11 +405,11 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
       row_scales(xb, ldb, D, lane, rs);
       wave_gemm<NW, CH, false>(w_1(l), w_2(l), xb, ldb, wave, lane, B, [&](int blk, f32x4 acc) {
         const int c = blk * 16 + li;
+        float g[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int r = 4 * lg + i;
-          hb[r * ldh + c] = (bf16)gelu_tanh(acc[i] * rs[i]);
-        }
+        for (int i = 0; i < 4; ++i) g[i] = gelu_tanh(acc[i] * rs[i]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) hb[(4 * lg + i) * ldh + c] = (bf16)g[i];
       });
       lds_barrier();
 
