@@ -81,8 +81,8 @@ def phase_times(torch, sess, reps=20):
 
 # HBM bytes per launch of each kernel family from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by the
 # copy-kernel calibration (profiles/traffic_cfg2_bench.md has the commands, raw values and factors)
-TRAFFIC = {"cfg2": {"resid": 12815024, "qkv": 8749845, "gelu": 9236859, "attn": 13896298, "head": 2648014,
-                    "embed": 3006557, "accept": 818561, "draft": 114459550}}
+TRAFFIC = {"cfg2": {"resid": 12815008, "qkv": 8749837, "gelu": 9236849, "attn": 13896280, "head": 2648011,
+                    "embed": 3006556, "accept": 818654, "draft": 113752075}}
 PEAK = {"bf16": 2500.0, "fp32": 157.3}   # dense MFMA bf16 / vector fp32, TFLOP/s
 HBM_PEAK = 8000.0                        # GB/s
 
