@@ -190,3 +190,21 @@ def test_fused_draft_with_threshold_rule_and_batch_sync():
     rep = lockstep(case, sess, rule="threshold", sync=True)
     assert rep["max_rel_X"] <= TOL[c.dtype] and rep["max_rel_mu_p"] <= TOL[c.dtype]
     assert sess.get_stats()["committed"] == c.batch * c.T
+
+
+@pytest.mark.parametrize("draft", [(2, 384, 6, 1536), (1, 256, 4, 1024), (3, 192, 3, 768)])
+def test_fused_draft_other_widths_follow_the_oracle(draft):
+    """Draft shapes of the benchmark configurations on the scaled-down target: 6 heads with 12 k-steps in
+    4-step chunks (configuration 3's draft), 4 heads in 8-step chunks (configurations 2, 4, 5), and an odd
+    width (6 k-steps: the fragment copy pads every block to 8) with three layers."""
+    from synth.configs import ModelCfg
+    case = Case("mini3", sigma=0.6, draft=ModelCfg(*draft))
+    c = case.cfg
+    sess = case.session(flags=FUSED)
+    rep = lockstep(case, sess)
+    assert rep["max_rel_X"] <= TOL[c.dtype] and rep["max_rel_mu_p"] <= TOL[c.dtype]
+    assert sess.get_stats()["committed"] == c.batch * c.T
+    # and the kernel-by-kernel path on the same shapes
+    a = _proposals(case, FUSED, 1)[0]
+    b = _proposals(case, UNFUSED, 1)[0]
+    assert np.isfinite(a).all() and rel_err(a, b).max() <= 1e-2
