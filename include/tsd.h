@@ -169,7 +169,8 @@ int tsd_reset_decode(tsd_ctx* ctx, void* stream);
  * A dense bf16 draft with head_dim 64 whose 16-row working set fits one compute unit's LDS can run
  * the whole phase as ONE launch (a workgroup keeps a few series through all steps and layers,
  * streaming the draft weights once per step); the per-row arithmetic is that of the kernel-by-kernel
- * path up to the summation order inside the products.  It is the default where it was measured to
+ * path up to the summation order inside the products (sampled proposals are drawn inside it from
+ * the same counters).  It is the default where it was measured to
  * win (draft weights of at most 4 MiB, widths in multiples of 256, more than 32 rows per pass and
  * max_batch <= 384);
  * TSD_FLAG_FUSED_DRAFT selects it wherever it is supported, TSD_FLAG_NO_FUSED_DRAFT never. */

@@ -23,6 +23,7 @@
 #include <algorithm>
 
 #include "attn_mfma.h"
+#include "philox.h"
 #include "tsd_internal.h"
 
 namespace tsd {
@@ -429,8 +430,16 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
                                 const int r = 4 * lg + i;
                                 if (r >= nrows || (step == 1 && !(r & 1))) continue;  // step 1 emits from the pending token only
                                 const int s = step == 1 ? r >> 1 : r;
-                                const float v = acc[i] * rs[i];
-                                if (j0 + s < n) p.X[(long)ser[s] * p.x_stride + (long)(step - 1) * P + c] = v;
+                                float v = acc[i] * rs[i];
+                                const long xo = (long)ser[s] * p.x_stride + (long)(step - 1) * P + c;
+                                if (p.mu_q) {
+                                  // sampled proposals: the mean goes to its own buffer, the draw x_i = mu_q + sigma_q eps
+                                  // (the series' own round counter, position `step`) is what everyone downstream consumes
+                                  if (j0 + s < n) p.mu_q[xo] = v;
+                                  v += (p.sigma_q_vec ? p.sigma_q_vec[c] : p.sigma_q) *
+                                       normal_draw((unsigned)ser[s], (unsigned)p.round[ser[s]], (unsigned)step, kStreamProposal, c, p.key0, p.key1);
+                                }
+                                if (j0 + s < n) p.X[xo] = v;
                                 pin[s * ldp + c] = v;
                               }
                             });

@@ -189,7 +189,7 @@ struct Carver {
 };
 
 // The whole draft phase as one kernel.  Supported: dense bf16 draft with head_dim 64 on the matrix-core
-// attention, widths in whole MFMA k-steps and column blocks, mean proposals, and everything it keeps in LDS
+// attention, widths in whole MFMA k-steps and column blocks, and everything it keeps in LDS
 // fits.  Chosen by default where it was measured to win: every workgroup streams all draft weights per
 // step, which beats a chain of launch-bound kernels only while those weights are small (at most 4 MiB, in
 // 8-step chunks) and the batch neither so small that the kernel-per-stage path runs its skinny products
@@ -198,7 +198,7 @@ struct Carver {
 // TSD_FLAG_NO_FUSED_DRAFT never.
 bool fused_draft_ok(const tsd_config& c) {
   const tsd_model_cfg& d = c.draft;
-  const bool supported = c.dtype == TSD_BF16 && !(c.flags & TSD_FLAG_SAMPLE_PROPOSALS) && d.n_experts == 0 &&
+  const bool supported = c.dtype == TSD_BF16 && d.n_experts == 0 &&
                          d.d_model == 64 * d.n_heads && c.page_tokens >= 8 && d.d_model % 32 == 0 && d.d_ff % 32 == 0 &&
                          c.patch % 16 == 0 && d.n_layers <= kDraftFusedMaxLayers &&
                          draft_fused_lds_bytes(d.d_model, d.d_ff, c.patch) <= 160 * 1024;
@@ -1065,6 +1065,14 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
     f.pending = ctx->pending;
     f.X = ctx->X;
     f.x_stride = (long)K * P;
+    if (c.flags & TSD_FLAG_SAMPLE_PROPOSALS) {
+      f.mu_q = ctx->mu_q;
+      f.round = ctx->round;
+      f.sigma_q = c.sigma_q;
+      f.sigma_q_vec = ctx->diag_on ? ctx->diag + 2 * P : nullptr;
+      f.key0 = (unsigned)(c.seed & 0xFFFFFFFFull);
+      f.key1 = (unsigned)(c.seed >> 32);
+    }
     f.Kr = Kr;
     f.L = md.c.n_layers;
     f.D = md.c.d_model;

@@ -142,6 +142,12 @@ struct DraftFusedP {
   const float* prev;       // [B][P] token before the pending one
   const float* pending;    // [B][P]
   float* X;                // proposals: x_i of series b at X + b * x_stride + (i - 1) * P
+  // sampled proposals (mu_q NULL: x_i is the mean): means to mu_q (laid out like X), x_i = mu_q^(i) + sigma_q eps
+  float* mu_q;
+  const int* round;        // per-series round counter (second word of the draw's counter)
+  float sigma_q;
+  const float* sigma_q_vec;  // per-dimension scales (NULL: sigma_q)
+  unsigned key0, key1;
   long x_stride;
   int Kr;                  // steps (proposals) of this round
   int L, D, F, Hh, P, PT, pt_shift;

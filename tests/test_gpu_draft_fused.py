@@ -208,3 +208,29 @@ def test_fused_draft_other_widths_follow_the_oracle(draft):
     a = _proposals(case, FUSED, 1)[0]
     b = _proposals(case, UNFUSED, 1)[0]
     assert np.isfinite(a).all() and rel_err(a, b).max() <= 1e-2
+
+
+@pytest.mark.parametrize("name,sigma,r", [("mini2", 0.5, 0.25), ("mini3", 0.6, 0.3)])
+def test_fused_draft_with_sampled_proposals(name, sigma, r):
+    """Sec. "Fallback Correction and Sampled Variants": x_i = mu_q^(i) + sigma_q eps drawn inside the one-launch
+    draft (the next step consumes the draw): rounds in step with the oracle, and X - mu_q is sigma_q times the
+    oracle generator's normals, element by element."""
+    from oracle import tsd_oracle as orc
+    flags = FUSED | tsd.TSD_FLAG_SAMPLE_PROPOSALS
+    case = Case(name, sigma=sigma)
+    c = case.cfg
+    sess = case.session(flags=flags, fallback_r=r)
+    rep = lockstep(case, sess, sample_proposals=True, fallback_r=r)
+    assert rep["max_rel_X"] <= TOL[c.dtype] and rep["max_rel_mu_p"] <= TOL[c.dtype]
+    assert sess.get_stats()["committed"] == c.batch * c.T
+    sess = case.session(flags=flags, fallback_r=r)
+    sess.prefill(case.context, c.n_ctx, c.horizon)
+    for rnd in range(2):
+        sess.draft_propose()
+        sess.target_verify()
+        sess.accept_commit()
+        io = {k: v.cpu().numpy() for k, v in sess.get_round_io().items()}
+        for b in range(c.batch):
+            for i in range(c.K):
+                z = (io["X"][b, i].astype(np.float64) - io["mu_q"][b, i]) / c.sigma
+                np.testing.assert_allclose(z, orc.normal(case.seed, b, rnd, i + 1, orc.STREAM_PROPOSAL, c.patch), atol=2e-4)
