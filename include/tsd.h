@@ -172,7 +172,7 @@ int tsd_reset_decode(tsd_ctx* ctx, void* stream);
  * path up to the summation order inside the products (sampled proposals are drawn inside it from
  * the same counters).  It is the default where it was measured to
  * win (draft weights of at most 4 MiB, widths in multiples of 256, more than 32 rows per pass and
- * max_batch <= 384);
+ * max_batch <= 512);
  * TSD_FLAG_FUSED_DRAFT selects it wherever it is supported, TSD_FLAG_NO_FUSED_DRAFT never. */
 int tsd_draft_propose(tsd_ctx* ctx, void* stream);
 

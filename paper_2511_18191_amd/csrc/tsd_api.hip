@@ -194,7 +194,7 @@ struct Carver {
 // step, which beats a chain of launch-bound kernels only while those weights are small (at most 4 MiB, in
 // 8-step chunks) and the batch neither so small that the kernel-per-stage path runs its skinny products
 // (passes of at most 32 rows) nor so large that its tiled products fill the chip (wins measured from 8 to
-// 384 series, a tie at 512 with long contexts).  TSD_FLAG_FUSED_DRAFT selects it wherever it is supported,
+// 512 series; at 1024 series with a larger draft it loses).  TSD_FLAG_FUSED_DRAFT selects it wherever it is supported,
 // TSD_FLAG_NO_FUSED_DRAFT never.
 bool fused_draft_ok(const tsd_config& c) {
   const tsd_model_cfg& d = c.draft;
@@ -206,7 +206,7 @@ bool fused_draft_ok(const tsd_config& c) {
   if (c.flags & TSD_FLAG_FUSED_DRAFT) return true;
   const size_t wbytes = (size_t)d.n_layers * (4 * (size_t)d.d_model * d.d_model + 2 * (size_t)d.d_model * d.d_ff) * 2;
   return draft_fused_chunk(d.d_model, d.d_ff) == 8 && wbytes <= ((size_t)4 << 20) && (size_t)c.max_batch * (c.K + 1) > 32 &&
-         c.max_batch <= 384;
+         c.max_batch <= 512;
 }
 
 // Lays out everything the handle needs inside the arena.  With ctx == nullptr only sizes it.
