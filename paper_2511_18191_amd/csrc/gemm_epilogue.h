@@ -33,6 +33,71 @@ __device__ __forceinline__ void epilogue_pass(const GemmP& p, ReadC read_c4, con
                                               const float4* oldc) {
   constexpr bool kBf = !std::is_same<T, float>::value;
   constexpr int GPR = BN / 4;  // 4-column groups per row
+  if constexpr (EP == EP_QKV && BN == 64) {
+    // RoPE + q / KV-cache write, four 4-column groups per lane at a time: first every read (accumulators and
+    // rotary partners from LDS, positions and pages, cos / sin from global memory, clamped for groups outside
+    // the product), then the arithmetic, then the stores.  Written as one read-compute-store body per group,
+    // each group's global loads wait for the previous group's stores to issue and pay a full round trip.
+    // (64-column tiles only: in the 128 x 128 kernel the extra live registers cost occupancy and 9 % of a
+    //  verification pass at 7168 rows.)
+    constexpr int ITS = 64 * GPR / NT, BATCH = ITS < 4 ? ITS : 4;
+    const int D = p.D, hd = p.hd, half = hd >> 1;
+#pragma unroll
+    for (int it0 = 0; it0 < ITS; it0 += BATCH) {
+      float4 v[BATCH], pv[BATCH], cs[BATCH], sn[BATCH];
+      int pos[BATCH], page[BATCH], gmv[BATCH], gnv[BATCH];
+      bool ok[BATCH];
+#pragma unroll
+      for (int j = 0; j < BATCH; ++j) {
+        const int g = tid + (it0 + j) * NT;
+        const int row = g / GPR, col = (g % GPR) * 4;
+        gmv[j] = m0 + pass * 64 + row;
+        gnv[j] = n0 + col;
+        ok[j] = gmv[j] < m_lim && gnv[j] < N;
+        const int c = gnv[j] % D, d = c % hd;
+        const bool lo = d < half;
+        v[j] = read_c4(row, col);
+        pv[j] = read_c4(row, lo ? col + half : col - half);
+        pos[j] = ok[j] ? row_pos[pass * 64 + row] : 0;
+        page[j] = ok[j] ? row_page[pass * 64 + row] : 0;
+        const int f = lo ? d : d - half;
+        cs[j] = *reinterpret_cast<const float4*>(p.rope_cos + (long)pos[j] * half + f);
+        sn[j] = *reinterpret_cast<const float4*>(p.rope_sin + (long)pos[j] * half + f);
+        if constexpr (kNorm) {
+          const float rs = row_scale[pass * 64 + row];
+          v[j].x *= rs;
+          v[j].y *= rs;
+          v[j].z *= rs;
+          v[j].w *= rs;
+          pv[j].x *= rs;
+          pv[j].y *= rs;
+          pv[j].z *= rs;
+          pv[j].w *= rs;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < BATCH; ++j) {
+        const int which = gnv[j] / D, c = gnv[j] - which * D;
+        const int h = c / hd, d = c - h * hd;
+        if (which < 2) {
+          const float sg = d < half ? -1.f : 1.f;
+          v[j].x = v[j].x * cs[j].x + sg * pv[j].x * sn[j].x;
+          v[j].y = v[j].y * cs[j].y + sg * pv[j].y * sn[j].y;
+          v[j].z = v[j].z * cs[j].z + sg * pv[j].z * sn[j].z;
+          v[j].w = v[j].w * cs[j].w + sg * pv[j].w * sn[j].w;
+        }
+        if (!ok[j]) continue;
+        if (which == 0) {
+          store4<T>(reinterpret_cast<T*>(p.q_out) + (long)gmv[j] * D + c, v[j]);
+        } else {
+          const int tok = pos[j] & (p.PT - 1);
+          const long off = ((((long)page[j] * 2 + (which - 1)) * p.Hh + h) * p.PT + tok) * hd + d;
+          store4<T>(reinterpret_cast<T*>(p.kv_pool) + off, v[j]);
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int it = 0; it < 64 * GPR / NT; ++it) {
     const int g = tid + it * NT;
