@@ -25,6 +25,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--sigma", type=float, default=None)
+    ap.add_argument("--batch", type=int, default=None, help="series in the batch (default: the configuration's; other sizes are side experiments)")
     ap.add_argument("--sample-proposals", action="store_true", help="ablation: x_i = mu_q + sigma_q eps")
     ap.add_argument("--fallback-r", type=float, default=0.0, help="ablation: fallback / bonus noise scale")
     ap.add_argument("--naive-verify", action="store_true", help="ablation: one target pass per prefix")
@@ -194,7 +195,7 @@ def main():
         assert torch.equal(dst[:1024], src[:1024])
         del src, dst
 
-    case = synth.Inputs(a.config, sigma=a.sigma)
+    case = synth.Inputs(a.config, sigma=a.sigma, B=a.batch)
     c = case.cfg
     flags = (tsd.TSD_FLAG_SAMPLE_PROPOSALS if a.sample_proposals else 0) | (tsd.TSD_FLAG_NAIVE_VERIFY if a.naive_verify else 0)
     flags |= (tsd.TSD_FLAG_THRESHOLD_RULE if a.threshold_rule else 0) | (tsd.TSD_FLAG_BATCH_SYNC if a.batch_sync else 0)
@@ -216,7 +217,7 @@ def main():
     t_base = timed(torch, lambda: decode_target_only(sess, c.T), a.steps)
     ph = phase_times(torch, sess)
 
-    fam = kernel_rooflines(sess, c.dtype, max(2, a.steps // 4), c.name if a.sigma is None else None, cfg=c)
+    fam = kernel_rooflines(sess, c.dtype, max(2, a.steps // 4), c.name if a.sigma is None and a.batch is None else None, cfg=c)
     # the one-launch draft kernel is listed with its own bound below; the headline roofline goes to the
     # largest family that one of the two published peaks (MFMA, HBM) bounds
     dominant = max((k for k in fam if k != "draft"), key=lambda k: fam[k]["total_ms"])
