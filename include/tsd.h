@@ -333,6 +333,16 @@ int tsd_bench_copy(void* dst_dev, const void* src_dev, size_t bytes, void* strea
  * published peak.  sink_dev: float [blocks * 256], written once at the end (keeps the chains live). */
 int tsd_bench_mfma(int32_t blocks, int32_t iters, float* sink_dev, void* stream);
 
+/* Measurement tap of the one-launch draft phase: runs tsd_draft_propose once with workgroup 0 noting the
+ * 100 MHz wall clock (s_memrealtime) after every one of its stage barriers, and returns the stamps in
+ * order: 2 of the set-up, then per draft step: inputs, patch embedding, per layer (QKV, attention,
+ * attention output, FFN up, FFN down), head -- 2 + steps * (3 + 5 * layers) values; consecutive
+ * differences are stage durations in units of 10 ns.  ticks_host: host array of max_ticks entries;
+ * *n_host receives the number of stamps taken (at most 512; only the first max_ticks are stored).
+ * The round tensors are left as after tsd_draft_propose.  Synchronises the stream.
+ * TSD_E_BAD_STATE if the handle runs the draft phase kernel by kernel. */
+int tsd_trace_draft(tsd_ctx* ctx, int64_t* ticks_host, int32_t max_ticks, int32_t* n_host, void* stream);
+
 /* Measurement tap: `blocks` workgroups of 256 lanes, workgroup w reading its own slice
  * src_dev[w * bytes_per_block ...) `iters` times with 16-byte loads (the way a GEMM workgroup walks
  * its operand panels); slices that fit L2 measure the cache-to-CU operand stream that bounds a

@@ -64,6 +64,7 @@ SYMBOLS = {
     "tsd_bench_gemm": ([C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_bench_copy": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
     "tsd_bench_mfma": ([C.c_int32, C.c_int32, C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_trace_draft": ([C.c_void_p, C.POINTER(C.c_int64), C.c_int32, C.POINTER(C.c_int32), C.c_void_p], C.c_int),
     "tsd_bench_stream": ([C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_set_accept_override": ([C.c_void_p, C.c_float], C.c_int),
     "tsd_get_series_stats": ([C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
@@ -235,6 +236,13 @@ class Session:
 
     def draft_propose(self):
         _check(lib().tsd_draft_propose(self.h, self._stream()), self.h)
+
+    def trace_draft(self, max_ticks=512):
+        """Stage stamps (units of 10 ns) of one traced draft phase: see tsd_trace_draft."""
+        buf = (C.c_int64 * max_ticks)()
+        n = C.c_int32(0)
+        _check(lib().tsd_trace_draft(self.h, buf, max_ticks, C.byref(n), self._stream()), self.h)
+        return list(buf[: min(n.value, max_ticks)])
 
     def target_verify(self):
         _check(lib().tsd_target_verify(self.h, self._stream()), self.h)

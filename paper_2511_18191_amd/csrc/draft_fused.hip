@@ -242,6 +242,13 @@ template <int NW, int CH>
 __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP p) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), li = lane & 15, lg = lane >> 4;
+  // measurement tap: workgroup 0 notes the 100 MHz wall clock after every stage barrier (trace NULL: off)
+  long long* const trace = blockIdx.x == 0 && threadIdx.x == 0 ? p.trace : nullptr;
+  int n_stamps = 0;
+#define STAGE_STAMP()                                                        \
+  do {                                                                       \
+    if (trace && n_stamps < p.trace_max) trace[n_stamps++] = wall_clock64(); \
+  } while (0)
   const int n = p.n_dev ? min(*p.n_dev, p.n) : p.n;
   const int kSer = p.spw;  // series of this workgroup: 1, 2, 4 or 8
   const int j0 = blockIdx.x * kSer;
@@ -267,11 +274,13 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
   if (tid < kSerMax) ser[tid] = p.act ? p.act[min(j0 + tid, n - 1)] : min(j0 + tid, n - 1);  // slots past n clone the last series
   for (int i = tid; i < kRows * ldp; i += NW * 64) pin[i] = 0.f;
   __syncthreads();
+  STAGE_STAMP();
   for (int i = tid; i < kSerMax * 64; i += NW * 64) {
     const int s = i >> 6, pg = i & 63;
     spt[i] = p.page_table[(long)ser[s] * p.pt_stride + min(pg, p.pt_stride - 1)];
   }
   __syncthreads();
+  STAGE_STAMP();
 
   // the products of a step, in the order the weights are streamed
   const Wsrc none{nullptr, 0, 0, 0};
@@ -309,6 +318,7 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
       }
     }
     lds_barrier();
+    STAGE_STAMP();
     auto row_live = [&](int r) { return r < nrows && j0 + (step == 1 ? r >> 1 : r) < n; };
     // (the epilogues below read everything they need first, compute, then store: written with `if`s per
     //  element they cost 1300 cycles per QKV block, mostly LDS round trips waited for one at a time)
@@ -329,6 +339,7 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
           }
         });
     lds_barrier();
+    STAGE_STAMP();
 
     for (int l = 0; l < p.L; ++l) {
       bf16* pool = p.kv_pool + (size_t)l * p.layer_pool_elems;
@@ -367,6 +378,7 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
         }
       });
       __syncthreads();  // (also makes the cache rows written above visible to the workgroup's loads)
+      STAGE_STAMP();
 
       // ---- causal attention of the new tokens over the series' cache: one (series, head) per wavefront turn ----
       if (wave < 8) {
@@ -384,6 +396,7 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
       }
       if constexpr (!kPrimeOverAttn) prime<NW, CH>(w_o(l), wave, lane, B);
       lds_barrier();
+      STAGE_STAMP();
 
       // ---- attention output projection + residual ----
       auto resid_epi = [&](int blk, f32x4 acc) {
@@ -401,6 +414,7 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
       };
       wave_gemm<NW, CH, false>(w_o(l), w_1(l), ab, ldb, wave, lane, B, resid_epi);
       lds_barrier();
+      STAGE_STAMP();
 
       // ---- RMSNorm + FFN up + GELU ----
       row_scales(xb, ldb, D, lane, rs);
@@ -413,10 +427,12 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
         for (int i = 0; i < 4; ++i) hb[(4 * lg + i) * ldh + c] = (bf16)g[i];
       });
       lds_barrier();
+      STAGE_STAMP();
 
       // ---- FFN down + residual ----
       wave_gemm<NW, CH, false>(w_2(l), l + 1 < p.L ? w_qkv(l + 1) : w_h, hb, ldh, wave, lane, B, resid_epi);
       lds_barrier();
+      STAGE_STAMP();
     }
 
     // ---- RMSNorm (of the fp32 residual) + head: the step's proposal, also the next step's input ----
@@ -444,8 +460,11 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
                               }
                             });
     lds_barrier();
+    STAGE_STAMP();
   }
 }
+
+#undef STAGE_STAMP
 
 // dst (fragment order, nksp k-steps per block: k zero-padded to whole chunks of 32-wide steps) <- src [N][K];
 // Hh > 0: the QKV column order

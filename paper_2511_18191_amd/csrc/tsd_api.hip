@@ -63,6 +63,8 @@ struct tsd_ctx {
   char *qbuf, *abuf, *hbuf;
   int rows_max;
   bool fused_draft = false;  // tsd_draft_propose is one launch (see draft_fused.hip)
+  long long* trace_buf = nullptr;  // [kTraceMax] stage stamps of tsd_trace_draft
+  bool trace_on = false;
   int skinny;  // all decode passes have at most 32 rows: they take the skinny GEMM (fixed per handle so that a
                // series' bits never depend on how many other series are still active)
   int* moe_ids;
@@ -178,6 +180,8 @@ int check_config(const tsd_config* c, std::string& why) {
   return TSD_OK;
 }
 
+constexpr int kTraceMax = 512;  // stage stamps tsd_trace_draft can return
+
 struct Carver {
   size_t off = 0;
   size_t take(size_t bytes) {
@@ -279,6 +283,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
   const size_t rows = std::max((size_t)B * (K + 1), (size_t)c.max_tokens);
   size_t o_xb = cv.take(rows * Dm * es);
   size_t o_x = cv.take(rows * Dm * 4), o_q = cv.take(rows * Dm * es), o_a = cv.take(rows * Dm * es), o_h = cv.take(rows * Fm * es);
+  size_t o_trace = cv.take(kTraceMax * 8);
   size_t o_cnt = cv.take(256), o_so = cv.take(256), o_alist = cv.take((size_t)B * 4), o_rlist = cv.take((size_t)B * 4);
   // routed FFN scratch: one slot per (token, chosen expert)
   const size_t topk = std::max(c.target.n_experts > 0 ? c.target.top_k : 0, c.draft.n_experts > 0 ? c.draft.top_k : 0);
@@ -325,6 +330,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
     ctx->K_max = K;
     ctx->skinny = (c.dtype == TSD_BF16 && !(c.flags & TSD_FLAG_NO_SKINNY) && (size_t)B * (K + 1) <= 32) ? 1 : 0;
     ctx->fused_draft = fused_draft_ok(c);
+    ctx->trace_buf = (long long*)at(o_trace);
     ctx->count_out = (int*)at(o_cnt);
     ctx->act_list = (int*)at(o_alist);
     ctx->refill_list = (int*)at(o_rlist);
@@ -1083,6 +1089,8 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
     f.pt_shift = __builtin_ctz(c.page_tokens);
     f.scale = 1.0f / std::sqrt((float)md.hd);
     f.chunk = draft_fused_chunk(f.D, f.F);
+    f.trace = ctx->trace_on ? ctx->trace_buf : nullptr;
+    f.trace_max = kTraceMax;
     // series per workgroup: two keep a workgroup's attention stage to one (series, head) pair per wavefront
     // at 4 heads; beyond 512 series more per workgroup keep the grid near one workgroup per compute unit.
     // (From the batch the handle was created for: a series' bits do not depend on who else is active.)
@@ -1469,6 +1477,29 @@ int tsd_bench_stream(const void* src_dev, size_t bytes_per_block, int32_t blocks
   if (bytes_per_block < 16 || (bytes_per_block % 16) || ((uintptr_t)src_dev % 16) || blocks < 1 || blocks > 65536 || iters < 1)
     return fail(nullptr, TSD_E_INVALID_ARG, "need bytes_per_block a positive multiple of 16, 1..65536 blocks, iters >= 1");
   HIP_TRY(nullptr, launch_stream(src_dev, bytes_per_block, blocks, iters, sink_dev, (hipStream_t)stream));
+  return TSD_OK;
+}
+
+int tsd_trace_draft(tsd_ctx* ctx, int64_t* ticks_host, int32_t max_ticks, int32_t* n_host, void* stream) {
+  int rc = require_ready(ctx, true);
+  if (rc) return rc;
+  if (!ticks_host || !n_host) return fail(ctx, TSD_E_INVALID_ARG, "ticks_host and n_host must not be NULL");
+  if (max_ticks < 1) return fail(ctx, TSD_E_INVALID_ARG, "max_ticks must be positive");
+  if (!ctx->fused_draft) return fail(ctx, TSD_E_BAD_STATE, "this handle runs the draft phase kernel by kernel: there are no stages to stamp");
+  hipStream_t st = (hipStream_t)stream;
+  static_assert(sizeof(long long) == 2 * sizeof(int), "the stamp buffer is cleared as ints");
+  HIP_TRY(ctx, launch_fill_int(reinterpret_cast<int*>(ctx->trace_buf), 0, 2 * kTraceMax, st));
+  ctx->trace_on = true;
+  rc = tsd_draft_propose(ctx, stream);
+  ctx->trace_on = false;
+  if (rc) return rc;
+  std::vector<long long> h(kTraceMax);
+  HIP_TRY(ctx, hipMemcpyAsync(h.data(), ctx->trace_buf, sizeof(long long) * kTraceMax, hipMemcpyDeviceToHost, st));
+  HIP_TRY(ctx, hipStreamSynchronize(st));
+  int n = 0;
+  while (n < kTraceMax && h[n] != 0) ++n;
+  *n_host = n;
+  for (int i = 0; i < n && i < max_ticks; ++i) ticks_host[i] = h[i];
   return TSD_OK;
 }
 

@@ -153,6 +153,8 @@ struct DraftFusedP {
   int L, D, F, Hh, P, PT, pt_shift;
   float scale;             // 1 / sqrt(head_dim)
   int chunk;               // k-steps per streamed chunk the fragment copy was padded for: 4 or 8
+  long long* trace;        // measurement tap (NULL: off): wall-clock ticks after every stage barrier of workgroup 0
+  int trace_max;
 };
 size_t draft_fused_lds_bytes(int D, int F, int P);
 // k-steps per streamed chunk for a draft of these widths (the fragment copy pads every block's k to whole chunks)

@@ -109,3 +109,4 @@ def test_measurement_taps_validate_before_any_launch():
     assert L.tsd_bench_stream(0x1000, 1000, 4, 1, 0x2000, None) == -1         # slice not a multiple of 16
     assert L.tsd_bench_gemm(tsd.TSD_BF16, 3, 64, 64, 64, 0x1000, 0x2000, 0x3000, None) == -1   # unknown variant
     assert L.tsd_bench_gemm(tsd.TSD_BF16, 0, 64, 64, 60, 0x1000, 0x2000, 0x3000, None) == -1   # K not a multiple of 8
+    assert L.tsd_trace_draft(None, None, 8, None, None) != 0                 # no handle

@@ -234,3 +234,24 @@ def test_fused_draft_with_sampled_proposals(name, sigma, r):
             for i in range(c.K):
                 z = (io["X"][b, i].astype(np.float64) - io["mu_q"][b, i]) / c.sigma
                 np.testing.assert_allclose(z, orc.normal(case.seed, b, rnd, i + 1, orc.STREAM_PROPOSAL, c.patch), atol=2e-4)
+
+
+def test_stage_tap_of_the_one_launch_draft():
+    """tsd_trace_draft: 2 + steps * (3 + 5 * layers) increasing stamps, proposals unchanged by tracing, and a
+    clean error on a handle that runs the draft kernel by kernel."""
+    case = Case("mini3")
+    c = case.cfg
+    sess = case.session(flags=FUSED)
+    sess.prefill(case.context, c.n_ctx, c.horizon)
+    sess.draft_propose()
+    x0 = sess.get_round_io()["X"].cpu().numpy().copy()
+    t = sess.trace_draft()
+    assert len(t) == 2 + c.K * (3 + 5 * c.draft.n_layers)
+    assert all(b > a for a, b in zip(t, t[1:]))
+    assert (t[-1] - t[0]) * 0.01 < 5000.0          # the whole phase takes well under 5 ms
+    np.testing.assert_array_equal(sess.get_round_io()["X"].cpu().numpy(), x0)
+    assert len(sess.trace_draft(max_ticks=5)) == 5
+    plain = case.session(flags=UNFUSED)
+    plain.prefill(case.context, c.n_ctx, c.horizon)
+    with pytest.raises(tsd.TsdError):
+        plain.trace_draft()
