@@ -167,27 +167,51 @@ __global__ __launch_bounds__(64) void accept_kernel(const AcceptP p) {
   const float* MQ = p.mu_q + (long)b * K * P;
   const float* MP = p.mu_p + (long)b * (K + 1) * P;
   float my_ep = 0.f, my_eq = 0.f;
-  for (int i = 0; i < Kb; ++i) {
-    float ep = 0.f, eq = 0.f;
+  // four positions at a time: all their loads are issued before the first is used and the eight butterfly
+  // reductions interleave (one position after the other, every position paid its own memory round trip and
+  // twelve dependent cross-lane steps); positions past Kb re-read the last one and are dropped
+  for (int i0 = 0; i0 < Kb; i0 += 4) {
+    float ep[4] = {0.f, 0.f, 0.f, 0.f}, eq[4] = {0.f, 0.f, 0.f, 0.f};
     for (int e = lane; e < P; e += 64) {
-      float x = X[i * P + e];
-      float dp = x - MP[i * P + e], dq = x - MQ[i * P + e];
+      float x[4], mp[4], mq[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int ii = min(i0 + j, Kb - 1);
+        x[j] = X[ii * P + e];
+        mp[j] = MP[ii * P + e];
+        mq[j] = MQ[ii * P + e];
+      }
+      float wp = 1.f, wq = 1.f;
       if (p.inv2sp2_vec) {  // Mahalanobis energies of the diagonal surrogate, already halved
-        ep = fmaf(dp * dp, p.inv2sp2_vec[e], ep);
-        eq = fmaf(dq * dq, p.inv2sq2_vec[e], eq);
-      } else {
-        ep = fmaf(dp, dp, ep);
-        eq = fmaf(dq, dq, eq);
+        wp = p.inv2sp2_vec[e];
+        wq = p.inv2sq2_vec[e];
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float dp = x[j] - mp[j], dq = x[j] - mq[j];
+        if (p.inv2sp2_vec) {
+          ep[j] = fmaf(dp * dp, wp, ep[j]);
+          eq[j] = fmaf(dq * dq, wq, eq[j]);
+        } else {
+          ep[j] = fmaf(dp, dp, ep[j]);
+          eq[j] = fmaf(dq, dq, eq[j]);
+        }
       }
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) {
-      ep += __shfl_xor(ep, o);
-      eq += __shfl_xor(eq, o);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        ep[j] += __shfl_xor(ep[j], o);
+        eq[j] += __shfl_xor(eq[j], o);
+      }
     }
-    if (lane == i) {
-      my_ep = ep;
-      my_eq = eq;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (i0 + j < Kb && lane == i0 + j) {
+        my_ep = ep[j];
+        my_eq = eq[j];
+      }
     }
   }
   bool reject = false;
