@@ -335,7 +335,7 @@ int tsd_bench_mfma(int32_t blocks, int32_t iters, float* sink_dev, void* stream)
 
 /* Measurement tap of the one-launch draft phase: runs tsd_draft_propose once with workgroup 0 noting the
  * 100 MHz wall clock (s_memrealtime) after every one of its stage barriers, and returns the stamps in
- * order: 2 of the set-up, then per draft step: inputs, patch embedding, per layer (QKV, attention,
+ * order: 2 of the set-up, then per draft step: positions, patch embedding, per layer (QKV, attention,
  * attention output, FFN up, FFN down), head -- 2 + steps * (3 + 5 * layers) values; consecutive
  * differences are stage durations in units of 10 ns.  ticks_host: host array of max_ticks entries;
  * *n_host receives the number of stamps taken (at most 512; only the first max_ticks are stored).

@@ -58,8 +58,8 @@ __host__ __device__ inline Lds carve(int D, int F, int P) {
   l.hb = o;  // hidden activations; the attention stage parks its V tiles here (8 KB per wavefront, 8 wavefronts)
   const size_t hid = (size_t)kRows * l.ldh * 2, vt = (size_t)8 * 2 * 32 * 64 * 2;
   o += hid > vt ? hid : vt;
-  l.misc = o;  // kvrow[16] long, pos[16] int, page[16] int, ser[8] int, spt[8][64] int, rope cos / sin [16][32] float
-  o += (size_t)(2 * 16 + 16 + 16 + 8 + 8 * 64 + 2 * 16 * 32) * 4;
+  l.misc = o;  // kvrow[16] long, pos[16] int, page[16] int, ser[8] int, lens[8] int, spt[8][64] int, rope cos / sin [16][32] float
+  o += (size_t)(2 * 16 + 16 + 16 + 8 + 8 + 8 * 64 + 2 * 16 * 32) * 4;
   l.total = (o + 15) & ~(size_t)15;
   return l;
 }
@@ -265,7 +265,8 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
   int* pos = reinterpret_cast<int*>(kvrow + 16);
   int* page = pos + 16;
   int* ser = page + 16;
-  int* spt = ser + 8;  // [8][64]: the series' page tables
+  int* lens = ser + 8;  // [8]: committed tokens of the series (position of the pending patch)
+  int* spt = lens + 8;  // [8][64]: the series' page tables
   float* rcos = reinterpret_cast<float*>(spt + 8 * 64);  // [16][32]: the rows' rotary factors
   float* rsin = rcos + 16 * 32;
   const int ldx = L.ldx, ldb = L.ldb, ldh = L.ldh, ldp = L.ldp;
@@ -278,6 +279,13 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
   for (int i = tid; i < kSerMax * 64; i += NW * 64) {
     const int s = i >> 6, pg = i & 63;
     spt[i] = p.page_table[(long)ser[s] * p.pt_stride + min(pg, p.pt_stride - 1)];
+  }
+  if (tid < kSerMax) lens[tid] = p.len[ser[tid]];
+  // the two tokens step 1 ingests (in the same round trip as the page tables)
+  for (int i = tid; i < kRows * P; i += NW * 64) {
+    const int r = i / P, e = i - r * P;
+    const float* src = (r & 1) ? p.pending : p.prev;
+    pin[r * ldp + e] = src[(long)ser[r >> 1] * P + e];
   }
   __syncthreads();
   STAGE_STAMP();
@@ -297,18 +305,12 @@ __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP 
   for (int step = 1; step <= p.Kr; ++step) {
     const int nq = step == 1 ? 2 : 1;
     const int nrows = kSer * nq;
-    // ---- inputs of the step ----
-    if (step == 1) {
-      for (int i = tid; i < kRows * P; i += NW * 64) {
-        const int r = i / P, e = i - r * P;
-        const float* src = (r & 1) ? p.pending : p.prev;
-        pin[r * ldp + e] = src[(long)ser[r >> 1] * P + e];
-      }
-    }
+    // ---- positions and rotary factors of the step's rows (its input patches are in place: loaded at set-up
+    //      for step 1, left there by the previous step's head afterwards) ----
     for (int i = tid; i < kRows * 32; i += NW * 64) {
       const int r = i >> 5, f = i & 31;
       const int s = step == 1 ? r >> 1 : min(r, kSer - 1);
-      const int ps = p.len[ser[s]] + (step == 1 ? (r & 1) - 1 : step - 1);
+      const int ps = lens[s] + (step == 1 ? (r & 1) - 1 : step - 1);
       rcos[i] = p.rope_cos[(long)ps * 32 + f];
       rsin[i] = p.rope_sin[(long)ps * 32 + f];
       if (f == 0) {

@@ -16,9 +16,9 @@ from .binding import TSD_FLAG_FUSED_DRAFT, session_for
 
 
 def stage_names(steps, layers):
-    names = ["set-up: series, zeroed rows", "set-up: page tables"]
+    names = ["set-up: series, zeroed rows", "set-up: page tables, lengths, step 1 inputs"]
     for s in range(1, steps + 1):
-        names += [f"step {s}: inputs, rotary factors", f"step {s}: patch embedding"]
+        names += [f"step {s}: positions, rotary factors", f"step {s}: patch embedding"]
         for l in range(layers):
             names += [f"step {s} layer {l}: {x}" for x in ("QKV + RoPE + cache write", "attention", "attention output", "FFN up + GELU", "FFN down")]
         names.append(f"step {s}: head")
