@@ -12,41 +12,46 @@ constexpr int kMaxExperts = 16;
 constexpr int kMaxTopK = 4;
 
 // One wavefront per token.  x: fp32 residual rows [M][D]; Wr: fp32 [E][D] with the norm gain folded.
+// EMAX (8 or 16) bounds the expert count at compile time so that the loads of one k-step carry no
+// branch and are all in flight together: rows past E re-read row E - 1 and their sums are ignored.
+template <int EMAX>
 __global__ __launch_bounds__(64) void router_kernel(const float* x, const float* Wr, int M, int D, int E, int topk,
                                                     int* ids, float* gates) {
   const int row = blockIdx.x, lane = threadIdx.x;
   const float* xr = x + (long)row * D;
-  float ss = 0.f, dot[kMaxExperts];
+  float ss = 0.f, dot[EMAX];
+  const float* wr[EMAX];
 #pragma unroll
-  for (int e = 0; e < kMaxExperts; ++e) dot[e] = 0.f;
+  for (int e = 0; e < EMAX; ++e) {
+    dot[e] = 0.f;
+    wr[e] = Wr + (long)min(e, E - 1) * D;
+  }
   for (int k = lane * 4; k < D; k += 256) {
     const float4 v = *reinterpret_cast<const float4*>(xr + k);
+    float4 w[EMAX];
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) w[e] = *reinterpret_cast<const float4*>(wr[e] + k);
     ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
 #pragma unroll
-    for (int e = 0; e < kMaxExperts; ++e) {
-      if (e < E) {
-        const float4 w = *reinterpret_cast<const float4*>(Wr + (long)e * D + k);
-        dot[e] += v.x * w.x + v.y * w.y + v.z * w.z + v.w * w.w;
-      }
-    }
+    for (int e = 0; e < EMAX; ++e) dot[e] += v.x * w[e].x + v.y * w[e].y + v.z * w[e].z + v.w * w[e].w;
   }
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) {
     ss += __shfl_xor(ss, o);
 #pragma unroll
-    for (int e = 0; e < kMaxExperts; ++e) dot[e] += __shfl_xor(dot[e], o);
+    for (int e = 0; e < EMAX; ++e) dot[e] += __shfl_xor(dot[e], o);
   }
   if (lane == 0) {
     const float rs = rsqrtf(ss / (float)D + kRmsEps);
-    float pr[kMaxExperts], mx = -INFINITY;
+    float pr[EMAX], mx = -INFINITY;
 #pragma unroll
-    for (int e = 0; e < kMaxExperts; ++e) {
+    for (int e = 0; e < EMAX; ++e) {
       pr[e] = e < E ? dot[e] * rs : -INFINITY;
       mx = fmaxf(mx, pr[e]);
     }
     float sum = 0.f;
 #pragma unroll
-    for (int e = 0; e < kMaxExperts; ++e) {
+    for (int e = 0; e < EMAX; ++e) {
       pr[e] = e < E ? expf(pr[e] - mx) : 0.f;
       sum += pr[e];
     }
@@ -58,7 +63,7 @@ __global__ __launch_bounds__(64) void router_kernel(const float* x, const float*
         int best = 0;
         float bv = -1.f;
 #pragma unroll
-        for (int e = 0; e < kMaxExperts; ++e)
+        for (int e = 0; e < EMAX; ++e)
           if (e < E && pr[e] > bv) {  // strict: the first (lowest) index wins ties
             bv = pr[e];
             best = e;
@@ -67,7 +72,7 @@ __global__ __launch_bounds__(64) void router_kernel(const float* x, const float*
         g[j] = bv / sum;
         gsum += g[j];
 #pragma unroll
-        for (int e = 0; e < kMaxExperts; ++e)
+        for (int e = 0; e < EMAX; ++e)
           if (e == best) pr[e] = -1.f;  // remove from later picks (probabilities are >= 0)
       }
     }
@@ -80,59 +85,65 @@ __global__ __launch_bounds__(64) void router_kernel(const float* x, const float*
   }
 }
 
+// Of the 64 assignments of one step (lane l holds expert id `id`, `valid` says whether there is
+// one), the lanes whose id equals THIS lane's number modulo 2^NB, as a bit mask: one ballot per bit
+// of the id and one for validity, combined per lane.  flip[b] is all ones where bit b of the lane
+// number is clear.  Lane e < 2^NB so learns where expert e's assignments sit.
+template <int NB>
+__device__ __forceinline__ unsigned long long lanes_of_my_expert(int id, bool valid, const unsigned long long (&flip)[NB]) {
+  unsigned long long m = __ballot(valid);
+#pragma unroll
+  for (int b = 0; b < NB; ++b) m &= __ballot((id >> b) & 1) ^ flip[b];
+  return m;
+}
+
 // One block of 1024 lanes: a stable counting sort of the assignments a = token * topk + choice by
-// expert.  Lane t owns the contiguous run of assignments [t * per, (t + 1) * per), so "earlier lane,
-// then earlier position" is assignment order and the sort is stable.  Per expert: counts per lane,
-// an exclusive scan over the lanes of a wavefront (shuffles) and over the wavefronts (LDS), then
-// every lane places its own run.  The expert ids are first staged in LDS (one byte each) by
-// coalesced loads, eight in flight per lane: read straight from memory, a lane's run would be a
-// chain of dependent-latency loads.  The tile map of the grouped GEMMs (one entry per BM-row tile
-// of an expert's run of slots) is written by one lane per tile.
+// expert.  Wavefront w owns the contiguous run of assignments [w * chunk, (w + 1) * chunk) and walks
+// it 64 at a time, lane l holding assignment base + l, so "earlier wavefront, earlier step, lower
+// lane" is assignment order and the sort is stable.  In a step, lane e finds the mask of the lanes
+// that chose expert e (see above); its population is what the step adds to the wavefront's count of
+// expert e, and an assignment's rank among the step's assignments of its expert is the number of
+// set bits of that expert's mask below its own lane.  So the only scans left are the two small
+// ones over wavefronts and over experts.  The first pass counts and keeps the expert ids in LDS
+// (one byte each); the second pass places.  The tile map of the grouped GEMMs (one entry per
+// BM-row tile of an expert's run of slots) is written by one lane per tile.  EMAX (8 or 16) is the
+// compile-time bound of the expert count.
+template <int EMAX>
 __global__ __launch_bounds__(1024) void permute_kernel(const int* ids, int n_assign, int topk, int E, int BM, int n_mtiles,
                                                        int* src_row, int* slot_of, int4* tile_map) {
-  extern __shared__ unsigned char lds_id[];   // [n_assign]
-  __shared__ int wave_tot[16][kMaxExperts];   // assignments of expert e in wavefront w
-  __shared__ int wave_base[16][kMaxExperts];  // ... in the wavefronts before w
-  __shared__ int tot[kMaxExperts];
-  __shared__ int beg[kMaxExperts + 1];       // first slot of expert e
-  __shared__ int tile_beg[kMaxExperts + 1];  // first tile of expert e
+  extern __shared__ unsigned char lds_id[];  // [n_assign]
+  __shared__ int wave_tot[16][EMAX];         // assignments of expert e in wavefront w
+  __shared__ int wave_base[16][EMAX];        // ... in the wavefronts before w
+  __shared__ int tot[EMAX];
+  __shared__ int beg[EMAX + 1];       // first slot of expert e
+  __shared__ int tile_beg[EMAX + 1];  // first tile of expert e
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-  for (int a = t; a < n_assign; a += 8 * 1024) {
+  const int chunk = ((n_assign + 15) / 16 + 63) & ~63;
+  const int a0 = w * chunk, a1 = min(a0 + chunk, n_assign);
+  constexpr int NB = EMAX == 8 ? 3 : 4;
+  static_assert(EMAX == 8 || EMAX == 16, "expert bound");
+  unsigned long long flip[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) flip[b] = ((lane >> b) & 1) ? 0ull : ~0ull;
+  int cnt = 0;  // lane e: this wavefront's assignments of expert e
+  for (int base = a0; base < a1; base += 8 * 64) {  // eight loads in flight per lane
     int v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = ids[min(a + u * 1024, n_assign - 1)];
+    for (int u = 0; u < 8; ++u) v[u] = ids[min(base + u * 64 + lane, n_assign - 1)];
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (a + u * 1024 < n_assign) lds_id[a + u * 1024] = (unsigned char)v[u];
-  }
-  __syncthreads();
-  const int per = (n_assign + 1023) / 1024;
-  const int a0 = min(t * per, n_assign), a1 = min(a0 + per, n_assign);
-  int cnt[kMaxExperts];
-#pragma unroll
-  for (int e = 0; e < kMaxExperts; ++e) cnt[e] = 0;
-  for (int a = a0; a < a1; ++a) {
-    const int id = lds_id[a];
-#pragma unroll
-    for (int e = 0; e < kMaxExperts; ++e) cnt[e] += (id == e) ? 1 : 0;
-  }
-  // exclusive prefix of cnt[e] over the lanes of this wavefront, and the wavefront's total
-  int start[kMaxExperts];
-#pragma unroll
-  for (int e = 0; e < kMaxExperts; ++e) {
-    int incl = cnt[e];
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int up = __shfl_up(incl, o);
-      if (lane >= o) incl += up;
+    for (int u = 0; u < 8; ++u) {
+      if (base + u * 64 < a1) {  // the same for the whole wavefront
+        const int a = base + u * 64 + lane;
+        if (a < a1) lds_id[a] = (unsigned char)v[u];
+        cnt += (int)__popcll(lanes_of_my_expert<NB>(v[u], a < a1, flip));
+      }
     }
-    start[e] = incl - cnt[e];
-    if (lane == 63) wave_tot[w][e] = incl;
   }
+  if (lane < EMAX) wave_tot[w][lane] = cnt;
   __syncthreads();
-  // Scans over the 16 wavefronts (per expert) and over the 16 experts, by lanes rather than by one
-  // lane walking LDS: 256 lanes hold (expert, wavefront) pairs, 16 consecutive lanes per expert.
-  if (t < 256) {
+  // Scans over the 16 wavefronts (per expert) and over the experts, by lanes rather than by one
+  // lane walking LDS: 16 * EMAX lanes hold (expert, wavefront) pairs, 16 consecutive lanes per expert.
+  if (t < 16 * EMAX) {
     const int e = t >> 4, i = t & 15;
     const int v = wave_tot[i][e];
     int incl = v;
@@ -146,7 +157,7 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int* ids, int n_ass
   }
   __syncthreads();
   if (t < 64) {
-    const int c = t < kMaxExperts ? tot[t] : 0;
+    const int c = t < EMAX ? tot[t] : 0;
     const int tl = (c + BM - 1) / BM;
     int ic = c, it = tl;
 #pragma unroll
@@ -157,35 +168,36 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int* ids, int n_ass
         it += ut;
       }
     }
-    if (t < kMaxExperts) {
+    if (t < EMAX) {
       beg[t] = ic - c;
       tile_beg[t] = it - tl;
-      if (t == kMaxExperts - 1) {
-        beg[kMaxExperts] = ic;
-        tile_beg[kMaxExperts] = it;
+      if (t == EMAX - 1) {
+        beg[EMAX] = ic;
+        tile_beg[EMAX] = it;
       }
     }
   }
   __syncthreads();
-#pragma unroll
-  for (int e = 0; e < kMaxExperts; ++e) start[e] += beg[e] + wave_base[w][e];
-  for (int a = a0; a < a1; ++a) {
-    const int id = lds_id[a];
-    int slot = 0;
-#pragma unroll
-    for (int e = 0; e < kMaxExperts; ++e)
-      if (id == e) {
-        slot = start[e];
-        start[e] += 1;
-      }
-    src_row[slot] = a / topk;
-    slot_of[a] = slot;
+  int run = lane < EMAX ? beg[lane] + wave_base[w][lane] : 0;  // lane e: next slot of expert e for this wavefront
+  for (int base = a0; base < a1; base += 64) {
+    const int a = base + lane;
+    const bool valid = a < a1;
+    const int id = valid ? (int)lds_id[a] : 0;
+    const unsigned long long m = lanes_of_my_expert<NB>(id, valid, flip);
+    // the mask and the running slot of the expert this lane's assignment chose sit in lane `id`
+    const unsigned lo = (unsigned)__shfl((int)(unsigned)m, id), hi = (unsigned)__shfl((int)(unsigned)(m >> 32), id);
+    const int slot = __shfl(run, id) + (int)__builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));
+    run += (int)__popcll(m);
+    if (valid) {
+      src_row[slot] = topk == 2 ? a >> 1 : a / topk;
+      slot_of[a] = slot;
+    }
   }
   // tile map: tile j belongs to the expert e with tile_beg[e] <= j < tile_beg[e + 1]
   for (int j = t; j < n_mtiles; j += 1024) {
     int4 entry = make_int4(-1, 0, 0, 0);
 #pragma unroll
-    for (int e = 0; e < kMaxExperts; ++e)
+    for (int e = 0; e < EMAX; ++e)
       if (e < E && j >= tile_beg[e] && j < tile_beg[e + 1])
         entry = make_int4(e, beg[e] + (j - tile_beg[e]) * BM, beg[e + 1], 0);
     tile_map[j] = entry;
@@ -219,22 +231,33 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* Y, const int*
 constexpr size_t kPermuteLdsMax = 144 * 1024;  // one byte per assignment
 // More than 64 KB of dynamic LDS needs a one-time opt-in (done at handle creation).
 hipError_t prepare_moe() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&permute_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&permute_kernel<8>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPermuteLdsMax);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&permute_kernel<16>), hipFuncAttributeMaxDynamicSharedMemorySize,
                              (int)kPermuteLdsMax);
 }
 
 hipError_t launch_router(const float* x, const float* Wr, int M, int D, int E, int topk, int* ids, float* gates,
                          hipStream_t st) {
-  if (E > kMaxExperts || topk > kMaxTopK || topk > E || D % 4) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(router_kernel, dim3(M), dim3(64), 0, st, x, Wr, M, D, E, topk, ids, gates);
+  if (E < 1 || E > kMaxExperts || topk < 1 || topk > kMaxTopK || topk > E || D % 4 || M < 1) return hipErrorInvalidValue;
+  if (E <= 8)
+    hipLaunchKernelGGL(router_kernel<8>, dim3(M), dim3(64), 0, st, x, Wr, M, D, E, topk, ids, gates);
+  else
+    hipLaunchKernelGGL(router_kernel<16>, dim3(M), dim3(64), 0, st, x, Wr, M, D, E, topk, ids, gates);
   return hipGetLastError();
 }
 
 hipError_t launch_permute(const int* ids, int n_assign, int topk, int E, int BM, int n_mtiles, int* src_row,
                           int* slot_of, void* tile_map, hipStream_t st) {
-  if (E > kMaxExperts || n_assign < 1 || (size_t)n_assign > kPermuteLdsMax) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(1024), (size_t)((n_assign + 15) & ~15), st, ids, n_assign, topk, E, BM, n_mtiles, src_row, slot_of,
-                     reinterpret_cast<int4*>(tile_map));
+  if (E < 1 || E > kMaxExperts || topk < 1 || n_assign < 1 || (size_t)n_assign > kPermuteLdsMax) return hipErrorInvalidValue;
+  const size_t lds = (size_t)((n_assign + 15) & ~15);
+  if (E <= 8)
+    hipLaunchKernelGGL(permute_kernel<8>, dim3(1), dim3(1024), lds, st, ids, n_assign, topk, E, BM, n_mtiles, src_row, slot_of,
+                       reinterpret_cast<int4*>(tile_map));
+  else
+    hipLaunchKernelGGL(permute_kernel<16>, dim3(1), dim3(1024), lds, st, ids, n_assign, topk, E, BM, n_mtiles, src_row, slot_of,
+                       reinterpret_cast<int4*>(tile_map));
   return hipGetLastError();
 }
 

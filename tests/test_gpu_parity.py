@@ -62,6 +62,24 @@ def test_round_lockstep(name, sigma):
     assert st["rounds"] == len(rep["lengths"])
 
 
+@pytest.mark.parametrize("experts,top_k,batch,d_model", [(3, 1, 6, 128), (4, 2, 6, 128), (8, 2, 40, 128), (12, 3, 6, 128),
+                                                         (16, 4, 19, 128), (12, 3, 256, 128), (5, 2, 301, 128),
+                                                         (8, 2, 5, 704), (6, 2, 5, 1024), (8, 2, 5, 1280), (12, 2, 5, 640)])
+def test_round_lockstep_expert_counts(experts, top_k, batch, d_model):
+    """Routed FFN at other expert counts, batch sizes and widths (both compile-time expert bounds;
+    router rows of one and of several k-steps, with a ragged last one; sorts of one step and of
+    many), fp32 so that the two sides route alike.  The large batches are followed on a few
+    series."""
+    target = synth.ModelCfg(2 if d_model == 128 else 1, d_model, d_model // 64, 256, experts, top_k)
+    case = Case("mini5_fp32", sigma=0.6, B=batch, target=target)
+    sess = case.session()
+    rep = lockstep(case, sess, max_rounds=3, subset=None if batch <= 40 else [0, 1, batch // 2, batch - 2, batch - 1])
+    print(f"\nE={experts} top-{top_k} B={batch} d={d_model}: rel X {rep['max_rel_X']:.2e} mu_p {rep['max_rel_mu_p']:.2e} "
+          f"mismatched {rep['mismatched']} near-ties {rep['near_ties']}")
+    assert rep["max_rel_X"] <= TOL["fp32"] and rep["max_rel_mu_p"] <= TOL["fp32"]
+    assert rep["mismatched"] <= rep["near_ties"]
+
+
 @pytest.mark.parametrize("name,sigma", [("cfg1", 1.0), ("cfg1", 0.05), ("mini2_fp32", 0.5)])
 def test_free_running_fp32_matches_oracle(name, sigma):
     case = Case(name, sigma=sigma)
