@@ -204,20 +204,43 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int* ids, int n_ass
   }
 }
 
-template <typename T>
+// TOPK > 0: the number of choices per token at compile time, so that the slots and gates of all
+// choices, and then their Y rows, are fetched together (two memory latencies, not two per choice).
+// The sums are taken in choice order either way.
+template <typename T, int TOPK>
 __global__ __launch_bounds__(256) void combine_kernel(const float* Y, const int* slot_of, const float* gates, float* x,
                                                       T* xb, int M, int D, int topk) {
   const long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i >= (long)M * D) return;
   const int row = (int)(i / D), col = (int)(i % D);
   float4 o = *reinterpret_cast<const float4*>(x + i);
-  for (int j = 0; j < topk; ++j) {
-    const float g = gates[(long)row * topk + j];
-    const float4 y = *reinterpret_cast<const float4*>(Y + (long)slot_of[(long)row * topk + j] * D + col);
-    o.x = fmaf(g, y.x, o.x);
-    o.y = fmaf(g, y.y, o.y);
-    o.z = fmaf(g, y.z, o.z);
-    o.w = fmaf(g, y.w, o.w);
+  if constexpr (TOPK > 0) {
+    int slot[TOPK];
+    float g[TOPK];
+    float4 y[TOPK];
+#pragma unroll
+    for (int j = 0; j < TOPK; ++j) {
+      slot[j] = slot_of[(long)row * TOPK + j];
+      g[j] = gates[(long)row * TOPK + j];
+    }
+#pragma unroll
+    for (int j = 0; j < TOPK; ++j) y[j] = *reinterpret_cast<const float4*>(Y + (long)slot[j] * D + col);
+#pragma unroll
+    for (int j = 0; j < TOPK; ++j) {
+      o.x = fmaf(g[j], y[j].x, o.x);
+      o.y = fmaf(g[j], y[j].y, o.y);
+      o.z = fmaf(g[j], y[j].z, o.z);
+      o.w = fmaf(g[j], y[j].w, o.w);
+    }
+  } else {
+    for (int j = 0; j < topk; ++j) {
+      const float g = gates[(long)row * topk + j];
+      const float4 y = *reinterpret_cast<const float4*>(Y + (long)slot_of[(long)row * topk + j] * D + col);
+      o.x = fmaf(g, y.x, o.x);
+      o.y = fmaf(g, y.y, o.y);
+      o.z = fmaf(g, y.z, o.z);
+      o.w = fmaf(g, y.w, o.w);
+    }
   }
   *reinterpret_cast<float4*>(x + i) = o;
   if (xb) {
@@ -261,13 +284,24 @@ hipError_t launch_permute(const int* ids, int n_assign, int topk, int E, int BM,
   return hipGetLastError();
 }
 
+template <typename T>
+static void combine_dispatch(unsigned grid, hipStream_t st, const float* Y, const int* slot_of, const float* gates, float* x,
+                             T* xb, int M, int D, int topk) {
+  if (topk == 1)
+    hipLaunchKernelGGL((combine_kernel<T, 1>), dim3(grid), dim3(256), 0, st, Y, slot_of, gates, x, xb, M, D, topk);
+  else if (topk == 2)
+    hipLaunchKernelGGL((combine_kernel<T, 2>), dim3(grid), dim3(256), 0, st, Y, slot_of, gates, x, xb, M, D, topk);
+  else
+    hipLaunchKernelGGL((combine_kernel<T, 0>), dim3(grid), dim3(256), 0, st, Y, slot_of, gates, x, xb, M, D, topk);
+}
+
 hipError_t launch_combine(int dtype, const float* Y, const int* slot_of, const float* gates, float* x, void* xb, int M,
                           int D, int topk, hipStream_t st) {
   const unsigned grid = (unsigned)(((long)M * D / 4 + 255) / 256);
   if (dtype == TSD_BF16)
-    hipLaunchKernelGGL(combine_kernel<bf16>, dim3(grid), dim3(256), 0, st, Y, slot_of, gates, x, reinterpret_cast<bf16*>(xb), M, D, topk);
+    combine_dispatch<bf16>(grid, st, Y, slot_of, gates, x, reinterpret_cast<bf16*>(xb), M, D, topk);
   else
-    hipLaunchKernelGGL(combine_kernel<float>, dim3(grid), dim3(256), 0, st, Y, slot_of, gates, x, (float*)nullptr, M, D, topk);
+    combine_dispatch<float>(grid, st, Y, slot_of, gates, x, (float*)nullptr, M, D, topk);
   return hipGetLastError();
 }
 
