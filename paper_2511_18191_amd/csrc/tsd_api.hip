@@ -81,6 +81,7 @@ struct tsd_ctx {
   bool seq_ready = false;        // the device-side launch counter has been zeroed
   bool compact_pending = false;  // the last tsd_round already enqueued the compaction tsd_num_active wants
   int* act_list;   // series still decoding, ascending (device)
+  int* act_list_alt;  // handles whose passes are sized on the host: the buffer the next compaction writes (see compact_target)
   int n_act;       // host copy of its length; -1 = unknown (use the full batch)
   long long* stats_out;
   // forecast in flight
@@ -285,6 +286,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
   size_t o_x = cv.take(rows * Dm * 4), o_q = cv.take(rows * Dm * es), o_a = cv.take(rows * Dm * es), o_h = cv.take(rows * Fm * es);
   size_t o_trace = cv.take(kTraceMax * 8);
   size_t o_cnt = cv.take(256), o_so = cv.take(256), o_alist = cv.take((size_t)B * 4), o_rlist = cv.take((size_t)B * 4);
+  size_t o_alist2 = cv.take((size_t)B * 4);
   // routed FFN scratch: one slot per (token, chosen expert)
   const size_t topk = std::max(c.target.n_experts > 0 ? c.target.top_k : 0, c.draft.n_experts > 0 ? c.draft.top_k : 0);
   const size_t slots = rows * topk, nEmax = std::max(c.target.n_experts, c.draft.n_experts);
@@ -333,6 +335,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
     ctx->trace_buf = (long long*)at(o_trace);
     ctx->count_out = (int*)at(o_cnt);
     ctx->act_list = (int*)at(o_alist);
+    ctx->act_list_alt = (int*)at(o_alist2);
     ctx->refill_list = (int*)at(o_rlist);
     ctx->moe_ids = topk ? (int*)at(o_ids) : nullptr;
     ctx->moe_gates = (float*)at(o_gates);
@@ -584,11 +587,20 @@ bool device_counts(const tsd_ctx* ctx) {
   return !(ctx->cfg.flags & TSD_FLAG_NO_COMPACT) && ctx->cfg.target.n_experts == 0 && ctx->cfg.draft.n_experts == 0 &&
          ctx->B > 1;
 }
+// The compaction that ends every tsd_round rewrites the list on the device, while the host's copy of its
+// length is refreshed only by tsd_num_active.  A launch that pairs an older (larger) host count with the newer
+// list must not read the list's stale tail (it can repeat series that are still active: two workgroups would
+// then commit for one series).  Handles that follow the device-side count therefore ALWAYS cap their work by
+// it, captured or not: list and count are rewritten together, in stream order.  Handles whose passes are sized
+// on the host (routed FFN, one series, ...) keep two list buffers instead: compactions write the one not in use,
+// and tsd_num_active switches over when it takes delivery of the matching count.
 Cover cover(const tsd_ctx* ctx) {
   if (ctx->capturing && device_counts(ctx)) return Cover{ctx->act_list, ctx->B, ctx->count_out};
-  if (ctx->n_act >= 0 && ctx->n_act < ctx->B) return Cover{ctx->act_list, ctx->n_act, nullptr};
+  if (ctx->n_act >= 0 && ctx->n_act < ctx->B) return Cover{ctx->act_list, ctx->n_act, device_counts(ctx) ? ctx->count_out : nullptr};
   return Cover{nullptr, ctx->B, nullptr};
 }
+// The list buffer a compaction may write now.
+int* compact_target(const tsd_ctx* ctx) { return device_counts(ctx) ? ctx->act_list : ctx->act_list_alt; }
 
 void drop_graphs(tsd_ctx* ctx) {
   for (hipGraphExec_t& g : ctx->graph_round)
@@ -1217,19 +1229,24 @@ int tsd_round(tsd_ctx* ctx, void* stream) {
   // With pinned host words at hand the round ends with the compaction tsd_num_active would otherwise have to
   // launch, copy back and wait for: the caller's next tsd_num_active only watches the host words.
   const bool deliver = ctx->host_counts && ctx->seq_ready;
+  const int need_before = ctx->need_lb;  // a round commits at most K + 1 patches per series
   rc = run_graphed(ctx, &ctx->graph_round[round_positions(ctx)], (hipStream_t)stream, [&]() {
     int r;
     if ((r = tsd_draft_propose(ctx, stream))) return r;
     if ((r = tsd_target_verify(ctx, stream))) return r;
     if ((r = tsd_accept_commit(ctx, nullptr, stream))) return r;
     if (deliver)
-      HIP_TRY(ctx, launch_compact_active(ctx->active, ctx->committed, ctx->T, ctx->B, ctx->act_list, ctx->count_out,
+      HIP_TRY(ctx, launch_compact_active(ctx->active, ctx->committed, ctx->T, ctx->B, compact_target(ctx), ctx->count_out,
                                          ctx->host_counts, (hipStream_t)stream));
     return (int)TSD_OK;
   });
-  if (rc == TSD_OK && deliver) {
-    ctx->seq_launched++;
-    ctx->compact_pending = true;
+  if (rc == TSD_OK) {
+    // (a replayed graph does not pass through accept_commit_impl: keep the bound on the patches still needed honest here)
+    ctx->need_lb = std::max(0, need_before - (ctx->cfg.K + 1));
+    if (deliver) {
+      ctx->seq_launched++;
+      ctx->compact_pending = true;
+    }
   }
   return rc;
 }
@@ -1270,7 +1287,7 @@ int tsd_num_active(tsd_ctx* ctx, int32_t* out_host, void* stream) {
   int32_t both[2] = {0, 0};
   if (ctx->host_counts && ctx->seq_ready) {
     if (!ctx->compact_pending) {
-      HIP_TRY(ctx, launch_compact_active(ctx->active, ctx->committed, ctx->T, ctx->B, ctx->act_list, ctx->count_out,
+      HIP_TRY(ctx, launch_compact_active(ctx->active, ctx->committed, ctx->T, ctx->B, compact_target(ctx), ctx->count_out,
                                          ctx->host_counts, st));
       ctx->seq_launched++;
     }
@@ -1295,10 +1312,12 @@ int tsd_num_active(tsd_ctx* ctx, int32_t* out_host, void* stream) {
     both[0] = ctx->host_counts[0];
     both[1] = ctx->host_counts[1];
   } else {
-    HIP_TRY(ctx, launch_compact_active(ctx->active, ctx->committed, ctx->T, ctx->B, ctx->act_list, ctx->count_out, nullptr, st));
+    HIP_TRY(ctx, launch_compact_active(ctx->active, ctx->committed, ctx->T, ctx->B, compact_target(ctx), ctx->count_out, nullptr, st));
     HIP_TRY(ctx, hipMemcpyAsync(both, ctx->count_out, 8, hipMemcpyDeviceToHost, st));
     HIP_TRY(ctx, hipStreamSynchronize(st));
   }
+  // the list that belongs to these counts is the one the last compaction wrote
+  if (!device_counts(ctx)) std::swap(ctx->act_list, ctx->act_list_alt);
   *out_host = both[0];
   if (!(ctx->cfg.flags & TSD_FLAG_NO_COMPACT)) {
     ctx->n_act = both[0];    // later passes cover only these series ...
@@ -1313,18 +1332,12 @@ int tsd_run_rounds(tsd_ctx* ctx, int32_t max_rounds, int32_t* rounds_host, int32
   if (rc) return rc;
   if (max_rounds < 1) return fail(ctx, TSD_E_INVALID_ARG, "max_rounds must be at least 1");
   int32_t rounds = 0, active = -1;
-  int lb = ctx->need_lb;  // lower bound on the most patches any series still needs (0: unknown)
   while (rounds < max_rounds) {
-    const int per_round = ctx->cfg.K + 1;  // the most a series can commit in one round
-    if ((rc = tsd_round(ctx, stream))) return rc;
+    if ((rc = tsd_round(ctx, stream))) return rc;  // lowers need_lb (a bound on the most patches any series still needs) by K + 1
     ++rounds;
     // (handles whose passes are sized on the host need every count: it is what shrinks their passes)
-    if (lb > per_round && rounds < max_rounds && device_counts(ctx)) {
-      lb -= per_round;  // somebody still needs patches after this round: no need to ask
-      continue;
-    }
+    if (ctx->need_lb > 0 && rounds < max_rounds && device_counts(ctx)) continue;  // somebody still needs patches: no need to ask
     if ((rc = tsd_num_active(ctx, &active, stream))) return rc;
-    lb = ctx->need_lb;
     if (active == 0) break;
   }
   if (rounds_host) *rounds_host = rounds;

@@ -378,6 +378,53 @@ def test_active_list_compaction_changes_nothing(name):
     assert outs[0][2] == outs[1][2] and sorted(outs[1][2], reverse=True) == outs[1][2] and outs[1][2][0] < c.batch
 
 
+@pytest.mark.parametrize("name,horizon,sigma", [("mini3", 96 * 14, 0.45), ("mini5", 32 * 22, 0.5), ("mini2", 96 * 9, 0.4)])
+def test_rounds_between_polls_without_graph(name, horizon, sigma):
+    # Several rounds per tsd_num_active with kernel-by-kernel launches: every round ends with a compaction that
+    # rewrites the active list on the device while the host still holds the length of an older, longer list.
+    # No launch may read the list's stale tail (it can repeat series that are still decoding, and two workgroups
+    # would then commit for one series): forecasts, counters and per-series state must equal, to the bit, those
+    # of a handle that never compacts.  mini5 sizes its passes on the host (routed FFN), mini3 / mini2 follow the
+    # device-side count; mini2 (5 series, K = 4: at most 25 rows) runs the skinny products.
+    import paper_2511_18191_amd as tsd
+    case = Case(name, B=None if name == "mini2" else 29, horizon=horizon, sigma=sigma)
+    c = case.cfg
+    outs = []
+    for flags, every in ((tsd.TSD_FLAG_NO_COMPACT | tsd.TSD_FLAG_NO_GRAPH, 1), (tsd.TSD_FLAG_NO_GRAPH, 3), (tsd.TSD_FLAG_NO_GRAPH, 4),
+                         (0, 3)):
+        sess = case.session(flags=flags)
+        sess.prefill(case.context, c.n_ctx, c.horizon)
+        sess.round()
+        counts = [sess.num_active()]
+        for r in range(1, c.T):                # every round commits at least one patch per active series
+            sess.round()
+            if r % every == 0:
+                counts.append(sess.num_active())
+        assert sess.num_active() == 0
+        st = sess.get_state()
+        outs.append((sess.get_forecast().cpu(), sess.get_stats(), st["committed"].cpu(), st["len"].cpu(),
+                     sess.get_series_stats().cpu()))
+        assert counts[0] > 0 and sorted(counts, reverse=True) == counts
+        sess.close()
+    for o in outs[1:]:
+        assert torch.equal(o[0], outs[0][0]) and o[1] == outs[0][1]
+        assert torch.equal(o[2], outs[0][2]) and torch.equal(o[3], outs[0][3]) and torch.equal(o[4], outs[0][4])
+    # the library's own loop after rounds the caller ran itself: same books, and no more rounds than needed
+    sess = case.session()
+    sess.prefill(case.context, c.n_ctx, c.horizon)
+    sess.round(); sess.round()
+    extra, left = sess.run_rounds()
+    assert left == 0 and torch.equal(sess.get_forecast().cpu(), outs[0][0]) and sess.get_stats() == outs[0][1]
+    sess.reset_decode()
+    for _ in range(3):
+        sess.round()
+    more, left = sess.run_rounds()
+    assert left == 0
+    if extra >= 2:
+        assert more + 3 == extra + 2, (more, extra)   # the bound on patches still needed followed the replayed rounds
+    assert torch.equal(sess.get_forecast().cpu(), outs[0][0])
+
+
 def test_batch_position_invariance():
     # a series' proposals and target means do not depend, to the bit, on where it sits in the
     # batch (which tile row, which prefill chunk, which physical pages)

@@ -139,3 +139,77 @@ def test_context_stats_frozen_on_context():
     x = np.random.default_rng(7).standard_normal(64) * 3 + 5
     m, s = orc.context_stats(x)
     assert math.isclose(m, x.mean()) and math.isclose(s, math.sqrt(x.var() + 1e-5))
+    # the same through the standard library's population statistics and torch's biased variance
+    import statistics
+    assert math.isclose(m, statistics.fmean(x.tolist()), rel_tol=1e-12)
+    assert math.isclose(s * s - 1e-5, statistics.pvariance(x.tolist()), rel_tol=1e-10)
+    assert math.isclose(s * s - 1e-5, float(torch.var(torch.tensor(x, dtype=T64), unbiased=False)), rel_tol=1e-10)
+    # a constant context: zero variance, the scale is the floor sqrt(1e-5); a shifted and scaled one follows
+    m0, s0 = orc.context_stats(np.full(32, 4.0))
+    assert m0 == 4.0 and math.isclose(s0, math.sqrt(1e-5))
+    m2, s2 = orc.context_stats(3.0 * x - 7.0)
+    assert math.isclose(m2, 3.0 * m - 7.0, rel_tol=1e-12) and math.isclose(s2 ** 2 - 1e-5, 9.0 * (s ** 2 - 1e-5), rel_tol=1e-10)
+
+
+def _rope_complex(x, pos, base=10000.0):
+    """Rotary embedding written a second way: the pair (x_i, x_{i + hd/2}) is the complex number
+    x_i + j x_{i + hd/2}, multiplied by exp(j pos base^(-2i/hd)).  x: torch [n, heads, hd]."""
+    hd = x.shape[-1]
+    half = hd // 2
+    z = torch.complex(x[..., :half], x[..., half:])
+    theta = torch.tensor(pos, dtype=T64)[:, None] * base ** (-2.0 * torch.arange(half, dtype=T64) / hd)[None, :]
+    z = z * torch.polar(torch.ones_like(theta), theta)[:, None, :]
+    return torch.cat([z.real, z.imag], dim=-1)
+
+
+def test_rope_complex_form_is_the_hand_rotation():
+    # the helper the composition pin below relies on, against rotation matrices written out by hand
+    rng = np.random.default_rng(21)
+    hd, pos = 8, [0, 3, 17]
+    x = rng.standard_normal((3, 2, hd))
+    got = _rope_complex(torch.tensor(x, dtype=T64), pos).numpy()
+    for t, p in enumerate(pos):
+        for h in range(2):
+            for i in range(hd // 2):
+                th = p * 10000.0 ** (-2.0 * i / hd)
+                a, b = x[t, h, i], x[t, h, i + hd // 2]
+                assert math.isclose(got[t, h, i], a * math.cos(th) - b * math.sin(th), rel_tol=1e-12, abs_tol=1e-14)
+                assert math.isclose(got[t, h, i + hd // 2], a * math.sin(th) + b * math.cos(th), rel_tol=1e-12, abs_tol=1e-14)
+
+
+def _forward_from_library_pieces(W, m, tokens):
+    """The documented model composed from torch float64 library routines (rms_norm, scaled_dot_product_attention
+    with its own causal mask, tanh gelu) and the complex-form rotary embedding; heads are split by
+    view(n, heads, hd) of the projection's columns, positions are 0..n-1."""
+    t = lambda a: torch.tensor(np.asarray(a), dtype=T64)
+    n, D, H = tokens.shape[0], m.d_model, m.n_heads
+    hd = D // H
+    pos = list(range(n))
+    x = t(tokens) @ t(W["W_e"])
+    for l in range(m.n_layers):
+        a = F.rms_norm(x, (D,), t(W[f"l{l}.g1"]), eps=1e-6)
+        q = _rope_complex((a @ t(W[f"l{l}.W_q"])).view(n, H, hd), pos)
+        k = _rope_complex((a @ t(W[f"l{l}.W_k"])).view(n, H, hd), pos)
+        v = (a @ t(W[f"l{l}.W_v"])).view(n, H, hd)
+        o = F.scaled_dot_product_attention(q.permute(1, 0, 2)[None], k.permute(1, 0, 2)[None], v.permute(1, 0, 2)[None],
+                                           is_causal=True)[0]                      # [H, n, hd], scale 1/sqrt(hd)
+        x = x + o.permute(1, 0, 2).reshape(n, D) @ t(W[f"l{l}.W_o"])
+        b = F.rms_norm(x, (D,), t(W[f"l{l}.g2"]), eps=1e-6)
+        x = x + F.gelu(b @ t(W[f"l{l}.W_1"]), approximate="tanh") @ t(W[f"l{l}.W_2"])
+    return (F.rms_norm(x, (D,), t(W["g_f"]), eps=1e-6) @ t(W["W_h"])).numpy()
+
+
+def test_forward_multi_token_multi_head_matches_library_composition():
+    # The whole forward (several layers, heads and tokens at positions > 0) against a composition of library
+    # routines: a wrong head split, RoPE on the wrong tensor or with the wrong position, a missing residual, a
+    # transposed projection or a mask off by one all fail this.
+    for (L, D, H, Fd, P, n, seed) in ((2, 32, 2, 64, 8, 9, 31), (3, 48, 3, 80, 16, 13, 32), (2, 64, 1, 96, 8, 5, 33)):
+        m = synth.ModelCfg(L, D, H, Fd)
+        W = orc.as_f64(synth.make_weights(m, P, np.random.default_rng(seed), random_gains=True, std=0.3))
+        tok = np.random.default_rng(seed + 100).standard_normal((n, P))
+        ref = _forward_from_library_pieces(W, m, tok)
+        got = orc.forward(W, m, tok)
+        assert np.abs(ref).max() > 0.1                       # not a degenerate comparison
+        np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-12)
+        # (and the comparison can fail: the composition on the reversed token order is far away)
+        assert np.abs(got - _forward_from_library_pieces(W, m, tok[::-1].copy())[::-1]).max() > 1e-3
