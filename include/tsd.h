@@ -211,6 +211,29 @@ int tsd_target_verify(tsd_ctx* ctx, void* stream);
  * Under TSD_FLAG_BATCH_SYNC the overridden value is the series' own count that enters the minimum. */
 int tsd_accept_commit(tsd_ctx* ctx, const int32_t* forced_len_dev, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it) and that run their own models: the acceptance / correction / commit step of ONE
+ * round (the rule of tsd_accept_commit, same kernel) on caller tensors, without a handle or an arena.  The
+ * state the kernel keeps (per-series round counter, committed count, active flag, pending / previous token,
+ * counters, the synchronised round's minimum) lives in a fixed device array inside the library, about 2.8 MB,
+ * held on every GPU the library has run this call on until the process ends; the call allocates nothing and
+ * frees nothing.  Limits: B <= 4096, K <= 16, B * P <= 262144; larger sizes return TSD_E_OUT_OF_RANGE.
+ *   inputs (device): X, mu_q [B,K,P]; mu_p [B,K+1,P]; round_dev int32 [B] (nullable = all 0): the second word
+ *     of each series' Philox counter, as the handle keeps it per series.
+ *   sigma_p, sigma_q, fallback_r, seed: as in tsd_config.  flags: TSD_FLAG_NO_TEMPERING, TSD_FLAG_THRESHOLD_RULE
+ *     and TSD_FLAG_BATCH_SYNC apply; any other bit is an error.
+ *   outputs (device): n_acc int32 [B]: leading accepts found by each series' own test; commit [B,K+1,P]: rows
+ *     0..n-1 = x_1..x_n and row n = the corrected (n < K) or bonus (n = K) patch, n = n_acc or, synchronised, the
+ *     batch's smallest; later rows are left untouched; ell, logu [B,K] (nullable): the statistics and log draws,
+ *     NaN where a position was not tested.
+ * Every call on a GPU shares that GPU's array and overwrites the previous call's state (nothing carries over:
+ * the state is set up afresh by a small kernel at the start of every call); calls that overlap on one GPU,
+ * on different streams or from different threads, race.  Asynchronous on `stream`. */
+int tsd_accept_commit_static(const float* X_dev, const float* mu_q_dev, const float* mu_p_dev, const int32_t* round_dev,
+                             int32_t B, int32_t K, int32_t P, float sigma_p, float sigma_q, float fallback_r,
+                             uint64_t seed, uint32_t flags, int32_t* n_acc_dev, float* commit_dev, float* ell_dev,
+                             float* logu_dev, void* stream);
+
 /* tsd_draft_propose; tsd_target_verify; tsd_accept_commit(NULL).  On a non-NULL stream that is not
  * being captured by the caller, the launch sequence is captured into a HIP graph on first use and
  * replayed afterwards (same for tsd_target_step); TSD_FLAG_NO_GRAPH switches that off. */

@@ -50,6 +50,9 @@ SYMBOLS = {
     "tsd_draft_propose": ([C.c_void_p, C.c_void_p], C.c_int),
     "tsd_target_verify": ([C.c_void_p, C.c_void_p], C.c_int),
     "tsd_accept_commit": ([C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+    "tsd_accept_commit_static": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                  C.c_float, C.c_float, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                  C.c_void_p], C.c_int),
     "tsd_round": ([C.c_void_p, C.c_void_p], C.c_int),
     "tsd_run_rounds": ([C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_target_step": ([C.c_void_p, C.c_void_p], C.c_int),
@@ -128,6 +131,24 @@ def bench_gemm(A, Wt, out=None, variant=0):
     _check(lib().tsd_bench_gemm(dt, variant, M, N, K, A.data_ptr(), Wt.data_ptr(), out.data_ptr(),
                                 torch.cuda.current_stream(A.device).cuda_stream))
     return out
+
+
+def accept_commit_static(X, mu_q, mu_p, sigma_p, sigma_q=None, rounds=None, fallback_r=0.0, seed=0, flags=0, want_taps=True):
+    """tsd_accept_commit_static on torch's current stream.  X, mu_q: [B,K,P], mu_p: [B,K+1,P] float32 GPU tensors;
+    rounds: int32 [B] or None.  Returns dict(n_acc, commit, ell, logu); the output tensors are allocated HERE, by
+    the caller's side, before the call: the library call itself allocates nothing."""
+    import torch
+    B, K, P = X.shape
+    dev = X.device
+    n_acc = torch.full((B,), -7, dtype=torch.int32, device=dev)
+    commit = torch.zeros(B, K + 1, P, dtype=torch.float32, device=dev)
+    ell = torch.zeros(B, K, dtype=torch.float32, device=dev) if want_taps else None
+    logu = torch.zeros(B, K, dtype=torch.float32, device=dev) if want_taps else None
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check(lib().tsd_accept_commit_static(X.data_ptr(), mu_q.data_ptr(), mu_p.data_ptr(), ptr(rounds), B, K, P, sigma_p,
+                                          sigma_p if sigma_q is None else sigma_q, fallback_r, seed, flags, n_acc.data_ptr(),
+                                          commit.data_ptr(), ptr(ell), ptr(logu), torch.cuda.current_stream(dev).cuda_stream))
+    return dict(n_acc=n_acc, commit=commit, ell=ell, logu=logu)
 
 
 def bench_copy(dst, src):

@@ -723,6 +723,10 @@ int accept_commit_impl(tsd_ctx* ctx, const int32_t* forced, int K, hipStream_t s
 
 }  // namespace
 
+namespace tsd {
+int fail_no_handle(int code, const std::string& msg) { return fail(nullptr, code, msg); }
+}  // namespace tsd
+
 extern "C" {
 
 int tsd_abi_version(void) { return 1; }

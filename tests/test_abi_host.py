@@ -110,3 +110,20 @@ def test_measurement_taps_validate_before_any_launch():
     assert L.tsd_bench_gemm(tsd.TSD_BF16, 3, 64, 64, 64, 0x1000, 0x2000, 0x3000, None) == -1   # unknown variant
     assert L.tsd_bench_gemm(tsd.TSD_BF16, 0, 64, 64, 60, 0x1000, 0x2000, 0x3000, None) == -1   # K not a multiple of 8
     assert L.tsd_trace_draft(None, None, 8, None, None) != 0                 # no handle
+
+
+def test_static_accept_validates_before_touching_the_gpu():
+    # tsd_accept_commit_static checks sizes against its fixed device array and its flags on the host first;
+    # the pointers below are never dereferenced
+    L = tsd.lib()
+    dummy = C.c_void_p(4096)
+    call = lambda B, K, P, flags=0, X=dummy: L.tsd_accept_commit_static(X, dummy, dummy, None, B, K, P, 1.0, 1.0, 0.0, 0, flags,
+                                                                       dummy, dummy, None, None, None)
+    assert call(4097, 4, 16) == -3 and b"4096" in L.tsd_last_error(None)
+    assert call(8, 17, 16) == -3
+    assert call(4096, 4, 96) == -3
+    assert call(0, 4, 16) == -1 and call(8, 0, 16) == -1
+    assert call(8, 4, 16, flags=tsd.TSD_FLAG_NO_GRAPH) == -1 and b"flags" in L.tsd_last_error(None)
+    assert call(8, 4, 16, X=None) == -1
+    assert L.tsd_accept_commit_static(dummy, dummy, dummy, None, 8, 4, 16, 0.0, 1.0, 0.0, 0, 0, dummy, dummy, None, None, None) == -1
+    assert L.tsd_accept_commit_static(dummy, dummy, dummy, None, 8, 4, 16, 1.0, 1.0, 2.0, 0, 0, dummy, dummy, None, None, None) == -1
