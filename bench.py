@@ -4,26 +4,34 @@
 A step is one whole speculative decode of the batch: reset to the post-prefill state, then
 rounds (draft proposal, single-pass verification, acceptance/commit/rollback) until every series
 has its horizon.  Inputs (weights, KV cache of the context) are resident in HBM before the
-timed region.  Prints ONE JSON line.
+timed region.  Prints ONE JSON line: the headline workload (default cfg3, the largest configuration
+that one GPU holds and the one whose GEMMs and attention the MFMA / HBM rooflines bound), its dominant
+kernel family's roofline, the CPU oracle on a bounded sample of the same workload, and a `configs`
+block with the same figures for every one of the five configurations.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2] [--sigma 1.0]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg3] [--sigma 1.0] [--only]
 """
 import argparse
+import hashlib
 import json
 import os
+import re
 import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+ALL_CONFIGS = ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"]
+
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="cfg3")
+    ap.add_argument("--only", action="store_true", help="skip the `configs` block (the other four configurations)")
     ap.add_argument("--sigma", type=float, default=None)
     ap.add_argument("--batch", type=int, default=None, help="series in the batch (default: the configuration's; other sizes are side experiments)")
     ap.add_argument("--sample-proposals", action="store_true", help="ablation: x_i = mu_q + sigma_q eps")
@@ -34,7 +42,8 @@ def parse():
     ap.add_argument("--fused-draft", choices=["auto", "on", "off"], default="auto",
                     help="the draft phase as one launch: where the library picks it (auto), wherever supported (on), never (off)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-series", type=int, default=128, help="series in the oracle's bounded sample (~15 s of CPU work at cfg2)")
+    ap.add_argument("--cpu-workers", type=int, default=0, help="oracle worker processes (default: the CPUs this process may use, at most 16)")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="the oracle keeps taking series until about this much wall time has passed")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB copy kernel 5 times (known traffic, to scale profiler memory counters)")
     return ap.parse_args()
@@ -60,7 +69,7 @@ def timed(torch, fn, steps):
     return (time.perf_counter() - t0) / steps
 
 
-def phase_times(torch, sess, reps=20):
+def phase_times(torch, sess, reps=10):
     """hipEvent time of one draft proposal, one verification, one acceptance, one target-only
     step (each repeated from the post-prefill state)."""
     ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -80,48 +89,79 @@ def phase_times(torch, sess, reps=20):
     return out
 
 
-# HBM bytes per launch of each kernel family from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by the
-# copy-kernel calibration (profiles/traffic_cfg2_bench.md has the commands, raw values and factors)
-TRAFFIC = {"cfg2": {"resid": 12815008, "qkv": 8749837, "gelu": 9236849, "attn": 13896280, "head": 2648011,
-                    "embed": 3006556, "accept": 818654, "draft": 113752075}}
 PEAK = {"bf16": 2500.0, "fp32": 157.3}   # dense MFMA bf16 / vector fp32, TFLOP/s
 HBM_PEAK = 8000.0                        # GB/s
 
 
-def kernel_rooflines(sess, dtype, steps, workload, cfg=None):
-    """Per kernel family: HIP-event time of every launch during `steps` speculative decodes
-    (kernel-by-kernel launches on the session's stream), and the algorithmic work they did."""
-    from paper_2511_18191_amd.binding import KERNEL_CLASSES
+def library_sources_hash():
+    """Identifies the kernel sources a profile was taken with (profiles/traffic_*.md carry the same value)."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2511_18191_amd", "csrc")
+    for f in sorted(os.listdir(d)):
+        if f.endswith((".hip", ".h")):
+            h.update(f.encode())
+            h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of each kernel family from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of
+    this workload (profiles/traffic_<workload>_bench.md: commands, raw values, copy-kernel scale factors).  Used
+    only when that summary was taken with the kernel sources as they are now; otherwise no traffic is reported."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}_bench.md")
+    if workload is None or not os.path.exists(path):
+        return {}, "no committed counter summary for this workload"
+    text = open(path).read()
+    m = re.search(r"kernel sources: ([0-9a-f]{16})", text)
+    if not m or m.group(1) != library_sources_hash():
+        return {}, "the committed counter summary is of other kernel sources"
     out = {}
-    for cls, name in enumerate(KERNEL_CLASSES):
-        sess.profile_begin(cls)
-        for _ in range(steps):
-            decode_spec(sess)
-        n, ms, work = sess.profile_end()
-        if n == 0:
-            continue
+    for row in re.findall(r"^\| *([a-z]+(?:\[[0-9a-z]+\])?) *\|(?:[^|]*\|){5} *([0-9.]+) *\|", text, flags=re.M):
+        out[row[0]] = int(round(float(row[1]) * 1e6))
+    return out, os.path.relpath(path, ROOT)
+
+
+TILE_LABEL = {128: "128x128", 64: "64x64", 464: "64x64k4", 16: "skinny"}
+
+
+def kernel_rooflines(sess, dtype, steps, traffic, cfg=None):
+    """Per kernel (family and, for the GEMM families, the tile variant the launcher picked): HIP-event time of
+    every launch during `steps` speculative decodes (kernel-by-kernel launches on the session's stream, every
+    launch bracketed by two events) and the algorithmic work they did."""
+    from paper_2511_18191_amd.binding import KERNEL_CLASSES
+    sess.profile_begin(len(KERNEL_CLASSES))       # every family at once
+    for _ in range(steps):
+        decode_spec(sess)
+    sess.profile_end()
+    groups = {}
+    for r in sess.profile_launches():
+        name = KERNEL_CLASSES[r["kernel_class"]]
+        key = f"{name}[{TILE_LABEL[r['tile']]}]" if r["tile"] in TILE_LABEL and name not in ("attn", "accept", "route", "draft") else name
+        g = groups.setdefault(key, dict(family=name, n=0, ms=0.0, work=0.0, rows=0))
+        g["n"] += 1; g["ms"] += r["ms"]; g["work"] += r["work"]; g["rows"] += r["M"]
+    out = {}
+    for key, g in groups.items():
+        name, n, ms, work = g["family"], g["n"], g["ms"], g["work"]
         if name == "draft":
             # one launch runs all K draft steps; every workgroup streams the draft's weights once per step
             # through its compute unit's vector-memory path (64 B/clk at 2.4 GHz = 153.6 GB/s per unit)
-            out[name] = dict(bound="cu_stream", launches=n, avg_us=ms * 1e3 / n, total_ms=ms,
-                             mfma_tflops=work / (ms * 1e-3) / 1e12, peak_gbs_per_cu=153.6, unit="GB/s per CU",
-                             traffic=TRAFFIC.get(workload, {}).get(name))
+            out[key] = dict(bound="cu_stream", launches=n, avg_us=ms * 1e3 / n, total_ms=ms,
+                            mfma_tflops=work / (ms * 1e-3) / 1e12, peak_gbs_per_cu=153.6, unit="GB/s per CU",
+                            traffic=traffic.get(key))
             if cfg is not None:
                 d = cfg.draft
                 wbytes = 2 * (d.n_layers * (4 * d.d_model ** 2 + 2 * d.d_model * d.d_ff) + 2 * cfg.patch * d.d_model)
                 # (K steps per launch; the last rounds of a decode run fewer, so this is a slight overestimate)
-                out[name]["achieved_gbs_per_cu"] = wbytes * cfg.K / (ms * 1e-3 / n) / 1e9
+                out[key]["achieved_gbs_per_cu"] = wbytes * cfg.K / (ms * 1e-3 / n) / 1e9
             continue
         hbm = name in ("attn", "accept", "route")
         achieved = work / (ms * 1e-3) / (1e9 if hbm else 1e12)
         peak = HBM_PEAK if hbm else PEAK[dtype]
-        out[name] = dict(bound="hbm" if hbm else "mfma", achieved=achieved, peak=peak, unit="GB/s" if hbm else "TFLOP/s",
-                         frac=achieved / peak, launches=n, avg_us=ms * 1e3 / n, total_ms=ms,
-                         traffic=TRAFFIC.get(workload, {}).get(name))
-        # the GEMMs of this size sit near the ridge (intensity ~ 300 flop per HBM byte): besides the
-        # MFMA fraction, the measured HBM bytes per launch against the memory peak
-        if out[name]["traffic"]:
-            out[name]["hbm_frac_of_traffic"] = out[name]["traffic"] / (ms * 1e-3 / n) / 1e9 / HBM_PEAK
+        out[key] = dict(bound="hbm" if hbm else ("mfma" if dtype == "bf16" else "alu"), achieved=achieved, peak=peak,
+                        unit="GB/s" if hbm else "TFLOP/s", frac=achieved / peak, launches=n, avg_us=ms * 1e3 / n,
+                        total_ms=ms, avg_rows=g["rows"] / n, work_per_launch=work / n, traffic=traffic.get(key))
+        if out[key]["traffic"]:
+            out[key]["hbm_frac_of_traffic"] = out[key]["traffic"] / (ms * 1e-3 / n) / 1e9 / HBM_PEAK
     return out
 
 
@@ -150,31 +190,111 @@ def measured_peaks(torch, tsd):
     return {"mfma_bf16_tflops": mfma, "hbm_copy_gbs": copy}
 
 
-def cpu_baseline(case, n_series, batch_sync=False, **oracle_kw):
-    """The oracle, as it stands, on a bounded sample: n_series series, whole horizon,
-    single-pass mode, one process (numpy's BLAS threads).  The only place the oracle is used."""
+# ---- the CPU oracle on a bounded sample: runs BEFORE anything touches the GPU (forked workers) -------------
+_ORC = {}
+
+
+def _oracle_series(b):
+    """One series, whole horizon, in a worker process (BLAS held to one thread: the threading is over series)."""
+    o = _ORC
+    c = o["case"].cfg
+    from threadpoolctl import threadpool_limits
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        o["orc"].forecast_spec(o["Wt"], c.target, o["Wd"], c.draft, o["case"].context[b], c.patch, c.horizon, c.K, c.sigma,
+                               c.sigma, o["case"].seed, b, **o["kw"])
+        return time.perf_counter() - t0
+
+
+def cpu_baseline(case, workers, seconds, batch_sync=False, **oracle_kw):
+    """The oracle, as it stands, timed on this machine's host cores on a bounded sample of the workload: whole
+    series (full horizon, single-pass mode), one per worker process at a time, until about `seconds` have
+    passed.  The only place the benchmark uses the oracle."""
+    import multiprocessing as mp
     from oracle import tsd_oracle as orc
     c = case.cfg
     Wt, Wd = orc.as_f64(case.wt), orc.as_f64(case.wd)
-    t0 = time.perf_counter()
-    if batch_sync:   # the sample decodes as one synchronised batch of its own
-        orc.forecast_spec_sync(Wt, c.target, Wd, c.draft, case.context[:n_series], c.patch, c.horizon, c.K, c.sigma,
-                               c.sigma, case.seed, **oracle_kw)
-    else:
-        for b in range(n_series):
-            orc.forecast_spec(Wt, c.target, Wd, c.draft, case.context[b], c.patch, c.horizon, c.K, c.sigma,
-                              c.sigma, case.seed, b, **oracle_kw)
+    if batch_sync:   # the synchronised loop couples the series of a batch: one process, the sample as its own batch
+        n = min(c.batch, 8)
+        t0 = time.perf_counter()
+        orc.forecast_spec_sync(Wt, c.target, Wd, c.draft, case.context[:n], c.patch, c.horizon, c.K, c.sigma, c.sigma,
+                               case.seed, **oracle_kw)
+        dt = time.perf_counter() - t0
+        return dict(value=n * c.horizon / dt, unit="forecast steps/s", cores=1, kind="oracle",
+                    sample=f"{n} of {c.batch} series as one synchronised batch, whole horizon of {c.horizon} steps, {dt:.1f} s")
+    _ORC.update(case=case, Wt=Wt, Wd=Wd, orc=orc, kw=oracle_kw)
+    workers = max(1, min(workers, c.batch))
+    done, t0 = 0, time.perf_counter()
+    with mp.get_context("fork").Pool(workers) as pool:       # forked: the float64 weights are shared, not copied
+        while done < c.batch:
+            take = list(range(done, min(c.batch, done + workers)))
+            per_series = pool.map(_oracle_series, take, chunksize=1)
+            done += len(take)
+            if time.perf_counter() - t0 >= seconds:
+                break
     dt = time.perf_counter() - t0
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = os.cpu_count()
-    return dict(value=n_series * c.horizon / dt, unit="forecast steps/s", cores=cores, kind="oracle",
-                sample=f"{n_series} of {c.batch} series, whole horizon of {c.horizon} steps, "
+    _ORC.clear()
+    return dict(value=done * c.horizon / dt, unit="forecast steps/s", cores=workers, kind="oracle",
+                sample=f"{done} of {c.batch} series of {c.name}, whole horizon of {c.horizon} steps, "
                        f"{'single-pass' if oracle_kw.get('single_pass', True) else 'per-prefix'} oracle"
-                       f"{', threshold rule' if oracle_kw.get('rule') == 'threshold' else ''}"
-                       f"{', batch-synchronised' if batch_sync else ''}, {dt:.1f} s")
+                       f"{', threshold rule' if oracle_kw.get('rule') == 'threshold' else ''}, one series per worker process "
+                       f"(BLAS single-threaded), {dt:.1f} s wall, last batch {max(per_series):.1f} s per series")
+
+
+def run_config(torch, tsd, synth, a, name, steps, warmup, fam_steps, flags, case=None, full=True):
+    """One configuration: speculative decode, target-only decode, phases, kernel families."""
+    if case is None:
+        case = synth.Inputs(name, sigma=a.sigma if full else None, B=a.batch if full else None)
+    c = case.cfg
+    sess = tsd.session_for(case, flags=flags, fallback_r=a.fallback_r if full else 0.0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    sess.prefill(case.context, c.n_ctx, c.horizon)
+    torch.cuda.synchronize()
+    prefill_ms = (time.perf_counter() - t0) * 1e3
+    for _ in range(warmup):
+        decode_spec(sess)
+    rounds = decode_spec(sess)
+    st = sess.get_stats()
+    t_spec = timed(torch, lambda: decode_spec(sess), steps)
+    for _ in range(max(1, warmup // 2)):
+        decode_target_only(sess, c.T)
+    t_base = timed(torch, lambda: decode_target_only(sess, c.T), steps)
+    ph = phase_times(torch, sess, reps=10 if full else 5)
+    standard = full and a.sigma is None and a.batch is None and flags == 0 and a.fallback_r == 0.0
+    traffic, traffic_src = measured_traffic(c.name if (standard or not full) else None)
+    fam = kernel_rooflines(sess, c.dtype, fam_steps, traffic, cfg=c)
+    sess.close()
+    # the one-launch draft kernel is listed with its own bound; the headline roofline goes to the largest
+    # family that one of the published peaks (MFMA, HBM) bounds
+    dominant = max((k for k in fam if fam[k]["bound"] != "cu_stream"), key=lambda k: fam[k]["total_ms"])
+    alpha = st["accepted"] / max(1, st["tested"])
+    mean_L = st["committed"] / max(1, st["rounds"])
+    cc = ph["draft"] / c.K / ph["target_step"]
+    v = (ph["verify"] + ph["accept"]) / ph["target_step"]
+    rec = {
+        "workload": f"{c.name}: B={c.batch} P={c.patch} N={c.n_ctx} H={c.horizon} K={c.K} sigma={c.sigma} "
+                    f"target {c.target.n_layers}L/d{c.target.d_model}{'/%dx top-%d experts' % (c.target.n_experts, c.target.top_k) if c.target.n_experts else ''} "
+                    f"draft {c.draft.n_layers}L/d{c.draft.d_model}",
+        "dtype": c.dtype,
+        "value": c.batch * c.horizon / t_spec, "unit": "forecast steps/s", "ms_per_step": t_spec * 1e3, "steps": steps,
+        "speedup_vs_target_only": t_base / t_spec,
+        "target_only_steps_per_s": c.batch * c.horizon / t_base, "target_only_ms": t_base * 1e3,
+        "prefill_ms": prefill_ms, "rounds_per_decode": rounds,
+        "acceptance": alpha, "mean_committed_per_round": mean_L,
+        "phase_ms": ph, "c": cc, "v": v,
+        "predicted_speedup_eq8": tsd.law.speedup(alpha, c.K, cc, v),
+        # committed patches per unit time against one patch per target step: what Eq. 8 predicts (the batch-level
+        # figure above also pays for rounds in which only the slowest series are still decoding)
+        "patch_rate_speedup": mean_L * ph["target_step"] / (ph["draft"] + ph["verify"] + ph["accept"]),
+        "near_ties": st["near_ties"],
+        "roofline": dict({k: v_ for k, v_ in fam[dominant].items()
+                          if k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "hbm_frac_of_traffic")},
+                         kernel=dominant, avg_us=fam[dominant]["avg_us"], launches=fam[dominant]["launches"],
+                         traffic_source=traffic_src),
+        "kernel_families": fam,
+    }
+    return rec
 
 
 def main():
@@ -182,9 +302,23 @@ def main():
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    import synth
+
+    # The oracle's leg first, in forked worker processes, before this process has touched the GPU.
+    case = synth.Inputs(a.config, sigma=a.sigma, B=a.batch)
+    cpu = None
+    if not a.no_cpu_baseline:
+        try:
+            avail = len(os.sched_getaffinity(0))
+        except AttributeError:
+            avail = os.cpu_count() or 1
+        workers = a.cpu_workers or min(16, avail)
+        cpu = cpu_baseline(case, workers, a.cpu_seconds, sample_proposals=a.sample_proposals, fallback_r=a.fallback_r,
+                           single_pass=not a.naive_verify, rule="threshold" if a.threshold_rule else "ratio",
+                           batch_sync=a.batch_sync)
+
     import torch
     import paper_2511_18191_amd as tsd
-    import synth
 
     if a.copy_calibration:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")      # 256 MiB
@@ -195,72 +329,47 @@ def main():
         assert torch.equal(dst[:1024], src[:1024])
         del src, dst
 
-    case = synth.Inputs(a.config, sigma=a.sigma, B=a.batch)
-    c = case.cfg
     flags = (tsd.TSD_FLAG_SAMPLE_PROPOSALS if a.sample_proposals else 0) | (tsd.TSD_FLAG_NAIVE_VERIFY if a.naive_verify else 0)
     flags |= (tsd.TSD_FLAG_THRESHOLD_RULE if a.threshold_rule else 0) | (tsd.TSD_FLAG_BATCH_SYNC if a.batch_sync else 0)
     flags |= {"auto": 0, "on": tsd.TSD_FLAG_FUSED_DRAFT, "off": tsd.TSD_FLAG_NO_FUSED_DRAFT}[a.fused_draft]
-    sess = tsd.session_for(case, flags=flags, fallback_r=a.fallback_r)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    sess.prefill(case.context, c.n_ctx, c.horizon)
-    torch.cuda.synchronize()
-    prefill_ms = (time.perf_counter() - t0) * 1e3
-
-    for _ in range(a.warmup):
-        decode_spec(sess)
-    rounds = decode_spec(sess)
-    st = sess.get_stats()
-    t_spec = timed(torch, lambda: decode_spec(sess), a.steps)
-    for _ in range(max(1, a.warmup // 2)):
-        decode_target_only(sess, c.T)
-    t_base = timed(torch, lambda: decode_target_only(sess, c.T), a.steps)
-    ph = phase_times(torch, sess)
-
-    fam = kernel_rooflines(sess, c.dtype, max(2, a.steps // 4), c.name if a.sigma is None and a.batch is None else None, cfg=c)
-    # the one-launch draft kernel is listed with its own bound below; the headline roofline goes to the
-    # largest family that one of the two published peaks (MFMA, HBM) bounds
-    dominant = max((k for k in fam if k != "draft"), key=lambda k: fam[k]["total_ms"])
+    head = run_config(torch, tsd, synth, a, a.config, a.steps, a.warmup, max(2, a.steps // 4), flags, case=case)
+    del case
     peaks = measured_peaks(torch, tsd)
 
-    alpha = st["accepted"] / max(1, st["tested"])
-    mean_L = st["committed"] / max(1, st["rounds"])
-    cc = ph["draft"] / c.K / ph["target_step"]
-    v = (ph["verify"] + ph["accept"]) / ph["target_step"]
     out = {
         "metric": "forecast steps/s (batched spec decode) + speedup vs target-only AR decode",
-        "value": c.batch * c.horizon / t_spec,
-        "unit": "forecast steps/s",
+        "value": head["value"], "unit": "forecast steps/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-        "ms_per_step": t_spec * 1e3,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": c.dtype, "data": "synthetic",
-        "config": {"workload": f"{c.name}: B={c.batch} P={c.patch} N={c.n_ctx} H={c.horizon} K={c.K} sigma={c.sigma} "
-                               f"target {c.target.n_layers}L/d{c.target.d_model} draft {c.draft.n_layers}L/d{c.draft.d_model}",
+        "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": head["workload"],
                    "step": "reset to post-prefill state + speculative rounds until all series reach the horizon",
                    "ablation": {"sample_proposals": a.sample_proposals, "fallback_r": a.fallback_r, "naive_verify": a.naive_verify,
                                 "threshold_rule": a.threshold_rule, "batch_sync": a.batch_sync, "fused_draft": a.fused_draft}},
-        "speedup_vs_target_only": t_base / t_spec,
-        "target_only_steps_per_s": c.batch * c.horizon / t_base,
-        "target_only_ms": t_base * 1e3,
-        "prefill_ms": prefill_ms,
-        "rounds_per_decode": rounds,
-        "acceptance": alpha, "mean_committed_per_round": mean_L,
-        "phase_ms": ph, "c": cc, "v": v,
-        "predicted_speedup_eq8": tsd.law.speedup(alpha, c.K, cc, v),
-        "near_ties": st["near_ties"],
-        # committed patches per unit time against one patch per target step (what Eq. 8 predicts)
-        "patch_rate_speedup": mean_L * ph["target_step"] / (ph["draft"] + ph["verify"] + ph["accept"]),
-        "roofline": dict({k: v for k, v in fam[dominant].items()
-                          if k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "hbm_frac_of_traffic")},
-                         kernel=dominant, avg_us=fam[dominant]["avg_us"], launches=fam[dominant]["launches"]),
-        "kernel_families": fam,
-        "measured_peaks": peaks,
     }
-    if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(case, min(a.cpu_series, c.batch), sample_proposals=a.sample_proposals,
-                                           fallback_r=a.fallback_r, single_pass=not a.naive_verify,
-                                           rule="threshold" if a.threshold_rule else "ratio", batch_sync=a.batch_sync)
+    out.update({k: head[k] for k in ("speedup_vs_target_only", "target_only_steps_per_s", "target_only_ms", "prefill_ms",
+                                     "rounds_per_decode", "acceptance", "mean_committed_per_round", "phase_ms", "c", "v",
+                                     "predicted_speedup_eq8", "near_ties", "patch_rate_speedup", "roofline", "kernel_families")})
+    out["measured_peaks"] = peaks
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
+    if not a.only:
+        # the five configurations, each in the deployed scheme (no ablation flags), fewer repetitions
+        short = ("workload", "dtype", "value", "ms_per_step", "steps", "speedup_vs_target_only", "target_only_ms", "rounds_per_decode",
+                 "acceptance", "mean_committed_per_round", "phase_ms", "c", "v", "predicted_speedup_eq8", "patch_rate_speedup",
+                 "roofline")
+        block = {}
+        for name in ALL_CONFIGS:
+            if name == a.config and flags == 0 and a.sigma is None and a.batch is None and a.fallback_r == 0.0:
+                rec = head
+            else:
+                n = 3 if name in ("cfg3", "cfg5") else 5
+                rec = run_config(torch, tsd, synth, a, name, n, 1, 1, 0, full=False)
+            block[name] = {k: rec[k] for k in short}
+            block[name]["families"] = {k: {kk: f[kk] for kk in ("bound", "achieved", "frac", "avg_us", "launches", "unit") if kk in f}
+                                       for k, f in rec["kernel_families"].items()}
+        out["configs"] = block
     print(json.dumps(out))
 
 

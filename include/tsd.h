@@ -278,6 +278,15 @@ int tsd_get_round_io(tsd_ctx* ctx, float* X_dev, float* mu_q_dev, float* mu_p_de
  * another implementation's X, mu_q, mu_p).  All three required, shapes as above. */
 int tsd_set_round_io(tsd_ctx* ctx, const float* X_dev, const float* mu_q_dev, const float* mu_p_dev, void* stream);
 
+/* Parity tap of the routed FFN: while ids_dev is installed, every pass through model `which` also files the
+ * experts its router chose under ids_dev[layer][series][absolute token position][choice] (int32, choice 0 = the
+ * most probable; series = index in the batch; entries of positions no pass has visited keep what the caller put
+ * there).  A top-k choice is discrete: another implementation that is to be compared at a floating-point
+ * tolerance has to be evaluated with the same choices wherever its own differ only by rounding.  ids_dev: caller-
+ * owned device memory of n_ints >= n_layers * max_batch * max_tokens * top_k entries, valid until the tap is
+ * removed (ids_dev = NULL) or the handle destroyed.  Costs one small launch per layer while installed. */
+int tsd_set_route_tap(tsd_ctx* ctx, int which, int32_t* ids_dev, size_t n_ints);
+
 /* Per-series state: len int32 [B] (tokens held by the target cache = position of the pending
  * token), committed int32 [B], pending float [B,P].  Any pointer may be NULL. */
 int tsd_get_state(tsd_ctx* ctx, int32_t* len_dev, int32_t* committed_dev, float* pending_dev, void* stream);
@@ -333,16 +342,32 @@ int tsd_set_sigma_diag(tsd_ctx* ctx, const float* sigma_p_dev, const float* sigm
 #define TSD_K_ACCEPT 6 /* acceptance + commit + rollback                */
 #define TSD_K_ROUTE 7  /* routed FFN: router, expert sort, gated combine (bytes) */
 #define TSD_K_DRAFT 8  /* the draft phase as one launch (flops of the passes it replaces) */
-#define TSD_K_COUNT 9
+#define TSD_K_COUNT 9  /* as a kernel_class: every family at once */
 int tsd_profile_begin(tsd_ctx* ctx, int kernel_class);
 int tsd_profile_end(tsd_ctx* ctx, int64_t* launches_host, double* ms_host, double* work_host, void* stream);
+
+/* The launches of the measurement that the last tsd_profile_end closed, one record each, in launch order:
+ * family, model (TSD_TARGET / TSD_DRAFT, -1 for the acceptance kernel), and for the GEMM families the kernel the
+ * launcher picked (`tile`: 128 or 64 = tile size of the tiled kernel, 464 = 64 x 64 tiles with K split over four
+ * wavefront groups, 16 = the skinny weight-streaming kernel) and the product's shape as launched (rows M as
+ * sized on the host: a replayed or device-capped launch may run fewer); attention: M = query rows, N = model
+ * width; duration between the two events in milliseconds; algorithmic work as summed by tsd_profile_end.
+ * out_host: max_records entries; *n_host receives the number of launches recorded (which may exceed
+ * max_records; only the first max_records are stored).  Host-only. */
+typedef struct {
+  int32_t kernel_class, model, tile, M, N, K;
+  float ms;
+  double work;
+} tsd_launch_rec;
+int tsd_profile_launches(tsd_ctx* ctx, tsd_launch_rec* out_host, int32_t max_records, int32_t* n_host);
 
 /* Measurement tap: one product through the same tiled kernel, tile selection and tile order the
  * transformer passes use.  dtype TSD_BF16: A and Wt are bf16; TSD_F32: fp32.  variant 0:
  * C[M,N] = A[M,K] * Wt[N,K]^T (fp32 result); variant 1: the same with each row of the product
  * scaled by rsqrt(mean(A_row^2) + 1e-6) (the fused RMSNorm); variant 2: C += A * Wt^T (the
- * residual epilogue).  K must be a multiple of 8, N of 4.  No handle needed. */
-int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_dev, const void* Wt_dev, float* C_dev,
+ * residual epilogue); variant 3 (bf16 only): C = GELU_tanh(RMSNorm-scaled product), stored as bf16 [M,N]: the
+ * FFN-up product exactly as the passes run it.  K must be a multiple of 8, N of 4.  No handle needed. */
+int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_dev, const void* Wt_dev, void* C_dev,
                    void* stream);
 
 /* Measurement tap: a plain copy kernel (dst[i] = src[i], 16 bytes per lane) of `bytes` bytes
@@ -365,14 +390,6 @@ int tsd_bench_mfma(int32_t blocks, int32_t iters, float* sink_dev, void* stream)
  * The round tensors are left as after tsd_draft_propose.  Synchronises the stream.
  * TSD_E_BAD_STATE if the handle runs the draft phase kernel by kernel. */
 int tsd_trace_draft(tsd_ctx* ctx, int64_t* ticks_host, int32_t max_ticks, int32_t* n_host, void* stream);
-
-/* Measurement tap: `blocks` workgroups of 256 lanes, workgroup w reading its own slice
- * src_dev[w * bytes_per_block ...) `iters` times with 16-byte loads (the way a GEMM workgroup walks
- * its operand panels); slices that fit L2 measure the cache-to-CU operand stream that bounds a
- * tiled GEMM of a given tile shape.  src_dev holds blocks * bytes_per_block bytes; sink_dev is
- * uint32 [blocks] (receives a checksum).  No handle needed. */
-int tsd_bench_stream(const void* src_dev, size_t bytes_per_block, int32_t blocks, int32_t iters, uint32_t* sink_dev,
-                     void* stream);
 
 const char* tsd_last_error(tsd_ctx* ctx);
 

@@ -179,13 +179,28 @@ def ffn_dense(b, W, l):
     return gelu_tanh(b @ W[f"l{l}.W_1"]) @ W[f"l{l}.W_2"]
 
 
-def ffn_routed(b, W, l, m):
+def ffn_routed(b, W, l, m, forced=None, info=None):
     """Softmax router over all experts, top-k by probability (ties -> lower index), the chosen
-    probabilities renormalised to sum to one, no capacity limit."""
+    probabilities renormalised to sum to one, no capacity limit.
+
+    forced (comparison aid, default off): int array [n, top_k]; token t uses the experts forced[t]
+    instead of its own top-k (a row of -1 leaves the token free), with this function's own
+    probabilities renormalised over that set as gates.  The top-k choice is the one discrete step of
+    the model: an implementation that rounds differently can pick another expert where two
+    probabilities nearly tie, after which the two outputs are simply different functions; with the
+    choice imposed, the rest can be compared at a floating-point tolerance.
+    info, if a list, receives per token (own top-k tuple, log(p_k / p_(k+1)): the gap between the
+    last expert taken and the first one left out, inf when top_k = n_experts)."""
     probs = softmax(b @ W[f"l{l}.W_r"], axis=-1)                   # [n, E]
     out = np.zeros_like(b)
     for t in range(b.shape[0]):
-        order = sorted(range(m.n_experts), key=lambda e: (-probs[t, e], e))[: m.top_k]
+        ranked = sorted(range(m.n_experts), key=lambda e: (-probs[t, e], e))
+        order = ranked[: m.top_k]
+        if info is not None:
+            gap = math.inf if m.top_k >= m.n_experts else math.log(probs[t, ranked[m.top_k - 1]] / probs[t, ranked[m.top_k]])
+            info.append((tuple(order), gap))
+        if forced is not None and forced[t][0] >= 0:
+            order = [int(e) for e in forced[t]]
         z = sum(probs[t, e] for e in order)
         for e in order:
             y = gelu_tanh(b[t] @ W[f"l{l}.e{e}.W_1"]) @ W[f"l{l}.e{e}.W_2"]
@@ -193,9 +208,11 @@ def ffn_routed(b, W, l, m):
     return out
 
 
-def forward(W, m, tokens):
+def forward(W, m, tokens, forced_experts=None, route_info=None):
     """Full causal forward.  tokens: [n, P] normalised patches at positions 0..n-1.
-    Returns mu: [n, P]; row j is the predicted mean of patch j + 1 given patches 0..j."""
+    Returns mu: [n, P]; row j is the predicted mean of patch j + 1 given patches 0..j.
+    forced_experts [layers, >= n, top_k] / route_info (a list that receives one list per layer): see
+    `ffn_routed`; routed models only, comparison aid."""
     tokens = np.asarray(tokens, dtype=np.float64)
     n = tokens.shape[0]
     H, hd = m.n_heads, m.d_model // m.n_heads
@@ -208,7 +225,13 @@ def forward(W, m, tokens):
         v = (a @ W[f"l{l}.W_v"]).reshape(n, H, hd)
         x = x + attention(q, k, v) @ W[f"l{l}.W_o"]
         b = rmsnorm(x, W[f"l{l}.g2"])
-        x = x + (ffn_routed(b, W, l, m) if m.n_experts > 0 else ffn_dense(b, W, l))
+        if m.n_experts > 0:
+            inf_l = [] if route_info is not None else None
+            x = x + ffn_routed(b, W, l, m, None if forced_experts is None else forced_experts[l][:n], inf_l)
+            if route_info is not None:
+                route_info.append(inf_l)
+        else:
+            x = x + ffn_dense(b, W, l)
     return rmsnorm(x, W["g_f"]) @ W["W_h"]
 
 
@@ -268,7 +291,7 @@ def within_threshold(x, mu_p, sigma_p):
 
 
 def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True, alpha_override=None,
-               eps_fn=None, sample_proposals=False, fallback_r=0.0, rule="ratio"):
+               eps_fn=None, sample_proposals=False, fallback_r=0.0, rule="ratio", target_forced=None):
     """One speculative round for one series.
 
     hist: [n, P] normalised history (context patches then committed patches).
@@ -286,6 +309,8 @@ def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True
     deterministic test of `within_threshold` (no draw is used).  For the threshold rule the record
     carries the same decision in log form, ell = -||x - mu_p||_d^2 / (2 sigma_p^2) against the
     constant log u = -1/2, so that callers can see how close to the boundary a decision was.
+    target_forced: imposed expert choices of a routed target for the positions of hist and the
+    proposals ([layers, >= n + K, top_k], see `ffn_routed`; comparison aid, default off).
     Returns a dict with X, mu_q [K, P], mu_p [K+1, P], ell, logu [K] (nan where untested),
     n (accepted count) and commits [n + 1, P].
     """
@@ -303,9 +328,9 @@ def spec_round(Wt, mt, Wd, md, hist, K, sigma_p, sigma_q, u_fn, single_pass=True
         cur = np.vstack([cur, X[i][None, :]])
     n0 = hist.shape[0]
     if single_pass:                                  # one causal pass, read at the K+1 boundaries
-        mu_p = forward(Wt, mt, cur)[n0 - 1: n0 + K]
+        mu_p = forward(Wt, mt, cur, forced_experts=target_forced)[n0 - 1: n0 + K]
     else:                                            # definitional: K+1 separate passes
-        mu_p = np.stack([forward(Wt, mt, cur[: n0 + i])[-1] for i in range(K + 1)])
+        mu_p = np.stack([forward(Wt, mt, cur[: n0 + i], forced_experts=target_forced)[-1] for i in range(K + 1)])
     ell = np.full(K, np.nan)
     logu = np.full(K, np.nan)
     n = 0

@@ -30,6 +30,11 @@ class TsdStats(C.Structure):
                 ("near_ties", C.c_int64)]
 
 
+class TsdLaunchRec(C.Structure):
+    _fields_ = [("kernel_class", C.c_int32), ("model", C.c_int32), ("tile", C.c_int32), ("M", C.c_int32), ("N", C.c_int32),
+                ("K", C.c_int32), ("ms", C.c_float), ("work", C.c_double)]
+
+
 class TsdError(RuntimeError):
     def __init__(self, code, msg):
         super().__init__(f"libtsd error {code}: {msg}")
@@ -64,11 +69,12 @@ SYMBOLS = {
     "tsd_get_stats": ([C.c_void_p, C.POINTER(TsdStats), C.c_void_p], C.c_int),
     "tsd_profile_begin": ([C.c_void_p, C.c_int], C.c_int),
     "tsd_profile_end": ([C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p], C.c_int),
+    "tsd_set_route_tap": ([C.c_void_p, C.c_int, C.c_void_p, C.c_size_t], C.c_int),
+    "tsd_profile_launches": ([C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32)], C.c_int),
     "tsd_bench_gemm": ([C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_bench_copy": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
     "tsd_bench_mfma": ([C.c_int32, C.c_int32, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_trace_draft": ([C.c_void_p, C.POINTER(C.c_int64), C.c_int32, C.POINTER(C.c_int32), C.c_void_p], C.c_int),
-    "tsd_bench_stream": ([C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_set_accept_override": ([C.c_void_p, C.c_float], C.c_int),
     "tsd_get_series_stats": ([C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "tsd_set_block_size": ([C.c_void_p, C.c_int32], C.c_int),
@@ -121,13 +127,13 @@ def _check(rc, ctx=None):
 def bench_gemm(A, Wt, out=None, variant=0):
     """C = A @ Wt.T through libtsd's tiled GEMM on torch's current stream.  A: [M,K], Wt: [N,K]
     (both bf16 or both fp32, on the GPU); returns fp32 [M,N].  variant 1 fuses the RMSNorm row
-    scale, variant 2 accumulates into `out`."""
+    scale, variant 2 accumulates into `out`, variant 3 (bf16) is the FFN-up product with GELU and a bf16 result."""
     import torch
     M, K = A.shape
     N = Wt.shape[0]
     dt = TSD_BF16 if A.dtype == torch.bfloat16 else TSD_F32
     if out is None:
-        out = torch.empty(M, N, dtype=torch.float32, device=A.device)
+        out = torch.empty(M, N, dtype=torch.bfloat16 if variant == 3 else torch.float32, device=A.device)
     _check(lib().tsd_bench_gemm(dt, variant, M, N, K, A.data_ptr(), Wt.data_ptr(), out.data_ptr(),
                                 torch.cuda.current_stream(A.device).cuda_stream))
     return out
@@ -164,14 +170,6 @@ def bench_mfma(blocks, iters, sink):
     import torch
     assert sink.dtype == torch.float32 and sink.numel() >= blocks * 256
     _check(lib().tsd_bench_mfma(blocks, iters, sink.data_ptr(), torch.cuda.current_stream(sink.device).cuda_stream))
-
-
-def bench_stream(src, bytes_per_block, blocks, iters, sink):
-    """Operand-stream tap (see tsd_bench_stream) on torch's current stream."""
-    import torch
-    assert src.numel() * src.element_size() >= bytes_per_block * blocks and sink.numel() >= blocks
-    _check(lib().tsd_bench_stream(src.data_ptr(), bytes_per_block, blocks, iters, sink.data_ptr(),
-                                  torch.cuda.current_stream(src.device).cuda_stream))
 
 
 class Session:
@@ -343,6 +341,26 @@ class Session:
         n, ms, work = C.c_int64(), C.c_double(), C.c_double()
         _check(lib().tsd_profile_end(self.h, C.byref(n), C.byref(ms), C.byref(work), self._stream()), self.h)
         return n.value, ms.value, work.value
+
+    def route_tap(self, which=TSD_TARGET):
+        """Install (and return) an int32 tensor [layers, max_batch, max_tokens, top_k], filled with -1, in which
+        the passes through model `which` file the experts their router chose (see tsd_set_route_tap)."""
+        m = self.cfg.target if which == TSD_TARGET else self.cfg.draft
+        self.sync()
+        tap = self.torch.full((m.n_layers, self.cfg.max_batch, self.cfg.max_tokens, m.top_k), -1, dtype=self.torch.int32,
+                              device=self.device)
+        self.torch.cuda.current_stream(self.device).synchronize()
+        _check(lib().tsd_set_route_tap(self.h, which, tap.data_ptr(), tap.numel()), self.h)
+        self._route_tap = tap
+        return tap
+
+    def profile_launches(self):
+        """Per-launch records of the measurement the last profile_end closed: list of dicts."""
+        n = C.c_int32()
+        _check(lib().tsd_profile_launches(self.h, None, 0, C.byref(n)), self.h)
+        buf = (TsdLaunchRec * max(1, n.value))()
+        _check(lib().tsd_profile_launches(self.h, buf, n.value, C.byref(n)), self.h)
+        return [{k: getattr(r, k) for k, _ in TsdLaunchRec._fields_} for r in buf[: n.value]]
 
     def set_accept_override(self, alpha):
         _check(lib().tsd_set_accept_override(self.h, alpha), self.h)

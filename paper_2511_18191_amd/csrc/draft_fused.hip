@@ -238,16 +238,20 @@ __device__ __forceinline__ void row_scales(const T* a, int lda, int K, int lane,
   for (int i = 0; i < 4; ++i) out[i] = __shfl(rsv, (4 * (lane >> 4) + i) * 4);
 }
 
-template <int NW, int CH>
+// kTrace: the measurement build (tsd_trace_draft) that stamps the wall clock after every stage barrier; the
+// production instantiation (kTrace = false) contains none of it.
+template <int NW, int CH, bool kTrace>
 __global__ __launch_bounds__(NW * 64) void draft_fused_kernel(const DraftFusedP p) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), li = lane & 15, lg = lane >> 4;
-  // measurement tap: workgroup 0 notes the 100 MHz wall clock after every stage barrier (trace NULL: off)
-  long long* const trace = blockIdx.x == 0 && threadIdx.x == 0 ? p.trace : nullptr;
+  // measurement build only: workgroup 0 notes the 100 MHz wall clock after every stage barrier
+  long long* const trace = kTrace && blockIdx.x == 0 && threadIdx.x == 0 ? p.trace : nullptr;
   int n_stamps = 0;
-#define STAGE_STAMP()                                                        \
-  do {                                                                       \
-    if (trace && n_stamps < p.trace_max) trace[n_stamps++] = wall_clock64(); \
+#define STAGE_STAMP()                                                                     \
+  do {                                                                                    \
+    if constexpr (kTrace) {                                                               \
+      if (trace && n_stamps < p.trace_max) trace[n_stamps++] = wall_clock64();            \
+    }                                                                                     \
   } while (0)
   const int n = p.n_dev ? min(*p.n_dev, p.n) : p.n;
   const int kSer = p.spw;  // series of this workgroup: 1, 2, 4 or 8
@@ -484,7 +488,11 @@ __global__ __launch_bounds__(256) void repack_kernel(const bf16* src, bf16* dst,
 
 template <int NW, int CH>
 hipError_t launch_cfg(const DraftFusedP& p, size_t smem, hipStream_t st) {
-  hipLaunchKernelGGL((draft_fused_kernel<NW, CH>), dim3((unsigned)((p.n + p.spw - 1) / p.spw)), dim3(NW * 64), smem, st, p);
+  const dim3 grid((unsigned)((p.n + p.spw - 1) / p.spw)), block(NW * 64);
+  if (p.trace)
+    hipLaunchKernelGGL((draft_fused_kernel<NW, CH, true>), grid, block, smem, st, p);
+  else
+    hipLaunchKernelGGL((draft_fused_kernel<NW, CH, false>), grid, block, smem, st, p);
   return hipGetLastError();
 }
 
@@ -508,11 +516,15 @@ hipError_t launch_repack_fragments(const void* src, void* dst, int N, int K, int
 }
 
 hipError_t prepare_draft_fused() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&draft_fused_kernel<8, 8>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&draft_fused_kernel<8, 4>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  const void* fns[4] = {reinterpret_cast<const void*>(&draft_fused_kernel<8, 8, false>),
+                        reinterpret_cast<const void*>(&draft_fused_kernel<8, 4, false>),
+                        reinterpret_cast<const void*>(&draft_fused_kernel<8, 8, true>),
+                        reinterpret_cast<const void*>(&draft_fused_kernel<8, 4, true>)};
+  for (const void* f : fns) {
+    hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_draft_fused(const DraftFusedP& p, hipStream_t st) {

@@ -463,6 +463,13 @@ static hipError_t launch_t(int amode, int epi, const GemmP& p, hipStream_t st) {
   return hipErrorInvalidValue;
 }
 
+int gemm_variant(int dtype, int amode, int epi, const GemmP& p) {
+  if (p.allow_skinny && skinny_applicable(dtype, amode, epi, p)) return 16;
+  if (dtype != TSD_BF16) return 64;
+  if (gemm_row_tile(TSD_BF16, p.M, p.N, p.force_bm) == 128) return 128;
+  return (amode == A_ACT && gemm_split(p)) ? 464 : 64;
+}
+
 hipError_t launch_gemm(int dtype, int amode, int epi, const GemmP& p, hipStream_t st) {
   if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
   if (p.allow_skinny && skinny_applicable(dtype, amode, epi, p)) return launch_gemm_skinny(amode, epi, p, st);

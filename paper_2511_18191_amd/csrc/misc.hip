@@ -431,35 +431,6 @@ hipError_t launch_mfma_peak(int blocks, int iters, float* sink, hipStream_t st) 
   return hipGetLastError();
 }
 
-// Operand-stream tap: workgroup w reads its own `bytes_per_block` slice of `src` `iters` times with
-// 16-byte loads (eight in flight per lane), i.e. the access pattern of a GEMM workgroup walking its
-// A/B panels out of L2.  The XOR of everything read goes to sink[w] so the loads cannot be dropped.
-__global__ __launch_bounds__(256) void stream_kernel(const uint4* src, size_t n16_per_block, int iters, unsigned* sink) {
-  const uint4* base = src + (size_t)blockIdx.x * n16_per_block;
-  uint4 acc = make_uint4(0, 0, 0, 0);
-  for (int it = 0; it < iters; ++it)
-    for (size_t i = threadIdx.x; i < n16_per_block; i += 256 * 8) {
-      uint4 v[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = base[min(i + (size_t)u * 256, n16_per_block - 1)];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        acc.x ^= v[u].x;
-        acc.y ^= v[u].y;
-        acc.z ^= v[u].z;
-        acc.w ^= v[u].w;
-      }
-    }
-  unsigned r = acc.x ^ acc.y ^ acc.z ^ acc.w;
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) r ^= __shfl_xor(r, o);
-  if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], r);
-}
-hipError_t launch_stream(const void* src, size_t bytes_per_block, int blocks, int iters, unsigned* sink, hipStream_t st) {
-  hipLaunchKernelGGL(stream_kernel, dim3(blocks), dim3(256), 0, st, (const uint4*)src, bytes_per_block / 16, iters, sink);
-  return hipGetLastError();
-}
-
 __global__ void fill_nan_kernel(float* p, long n) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = NAN;

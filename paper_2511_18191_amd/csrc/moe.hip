@@ -253,6 +253,28 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* Y, const int*
 
 constexpr size_t kPermuteLdsMax = 144 * 1024;  // one byte per assignment
 // More than 64 KB of dynamic LDS needs a one-time opt-in (done at handle creation).
+// Parity tap (off unless the caller installed a buffer): the experts the router chose for every row of a pass,
+// filed under the row's (layer, series, absolute position) so that another implementation can be evaluated with
+// the same discrete choices.  tap: int32 [layers][max_batch][max_tokens][topk].
+__global__ __launch_bounds__(256) void route_tap_kernel(const int* ids, int* tap, int layer, int M, int nq, const int* act,
+                                                        int s0, const int* base_pos, int pos_off, int max_batch,
+                                                        int max_tokens, int topk) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= M * topk) return;
+  const int row = i / topk, j = i - row * topk;
+  const int bl = row / nq, t = row - bl * nq;
+  const int b = act ? act[bl] : s0 + bl;
+  const int pos = (base_pos ? base_pos[b] : 0) + pos_off + t;
+  if (b < 0 || b >= max_batch || pos < 0 || pos >= max_tokens) return;
+  tap[(((long)layer * max_batch + b) * max_tokens + pos) * topk + j] = ids[i];
+}
+hipError_t launch_route_tap(const int* ids, int* tap, int layer, int M, int nq, const int* act, int s0, const int* base_pos,
+                            int pos_off, int max_batch, int max_tokens, int topk, hipStream_t st) {
+  hipLaunchKernelGGL(route_tap_kernel, dim3((unsigned)((M * topk + 255) / 256)), dim3(256), 0, st, ids, tap, layer, M, nq, act, s0,
+                     base_pos, pos_off, max_batch, max_tokens, topk);
+  return hipGetLastError();
+}
+
 hipError_t prepare_moe() {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&permute_kernel<8>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPermuteLdsMax);

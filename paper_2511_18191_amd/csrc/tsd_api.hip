@@ -68,6 +68,7 @@ struct tsd_ctx {
   int skinny;  // all decode passes have at most 32 rows: they take the skinny GEMM (fixed per handle so that a
                // series' bits never depend on how many other series are still active)
   int* moe_ids;
+  int* route_tap[2] = {nullptr, nullptr};  // caller-owned parity tap per model (tsd_set_route_tap), NULL = off
   float* moe_gates;
   int *moe_src, *moe_slot;
   char* moe_tmap;
@@ -81,7 +82,7 @@ struct tsd_ctx {
   bool seq_ready = false;        // the device-side launch counter has been zeroed
   bool compact_pending = false;  // the last tsd_round already enqueued the compaction tsd_num_active wants
   int* act_list;   // series still decoding, ascending (device)
-  int* act_list_alt;  // handles whose passes are sized on the host: the buffer the next compaction writes (see compact_target)
+  int* act_list_next;  // handles whose passes are sized on the host: the buffer every compaction writes (see compact_target)
   int n_act;       // host copy of its length; -1 = unknown (use the full batch)
   long long* stats_out;
   // forecast in flight
@@ -101,6 +102,7 @@ struct tsd_ctx {
   int K_max = 0;  // K the handle was created with: buffers, pages and the skinny decision are sized for it
   int prof_class = -1;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
+  std::vector<tsd_launch_rec> prof_recs;  // one per bracketed launch of the current / last measurement
   size_t prof_used = 0;
   double prof_work = 0;
   std::string err;
@@ -335,7 +337,7 @@ size_t carve(const tsd_config& c, tsd_ctx* ctx) {
     ctx->trace_buf = (long long*)at(o_trace);
     ctx->count_out = (int*)at(o_cnt);
     ctx->act_list = (int*)at(o_alist);
-    ctx->act_list_alt = (int*)at(o_alist2);
+    ctx->act_list_next = (int*)at(o_alist2);
     ctx->refill_list = (int*)at(o_rlist);
     ctx->moe_ids = topk ? (int*)at(o_ids) : nullptr;
     ctx->moe_gates = (float*)at(o_gates);
@@ -355,10 +357,18 @@ size_t weights_count(const tsd_model_cfg& m, int P) {
   return (size_t)P * D + per_layer * m.n_layers + D + D * P;
 }
 
-// Launches `fn` on `st`; if kernel family `cls` is being profiled, brackets it with two events.
+// What a bracketed launch was: the model it belongs to, the GEMM kernel chosen (gemm_variant) and the product's shape.
+struct Shape {
+  int model = -1, tile = 0, M = 0, N = 0, K = 0;
+};
+Shape shape_of(const tsd_ctx* ctx, int which, int amode, int epi, const GemmP& g) {
+  return Shape{which, gemm_variant(ctx->cfg.dtype, amode, epi, g), g.M, g.N, g.K};
+}
+
+// Launches `fn` on `st`; if kernel family `cls` is being profiled (or all are), brackets it with two events.
 template <typename F>
-hipError_t timed_launch(tsd_ctx* ctx, int cls, double work, hipStream_t st, F fn) {
-  if (ctx->prof_class != cls) return fn();
+hipError_t timed_launch(tsd_ctx* ctx, int cls, double work, hipStream_t st, F fn, Shape sh = Shape()) {
+  if (ctx->prof_class != cls && ctx->prof_class != TSD_K_COUNT) return fn();
   if (ctx->prof_used == ctx->prof_events.size()) {
     hipEvent_t a, b;
     hipError_t e = hipEventCreate(&a);
@@ -368,6 +378,7 @@ hipError_t timed_launch(tsd_ctx* ctx, int cls, double work, hipStream_t st, F fn
     ctx->prof_events.emplace_back(a, b);
   }
   auto& ev = ctx->prof_events[ctx->prof_used++];
+  ctx->prof_recs.push_back(tsd_launch_rec{cls, sh.model, sh.tile, sh.M, sh.N, sh.K, 0.f, work});
   hipError_t e = hipEventRecord(ev.first, st);
   if (e != hipSuccess) return e;
   e = fn();
@@ -416,7 +427,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
   g.Cf = ctx->x;
   g.Cb = ctx->xb;
   const void* xin = c.dtype == TSD_BF16 ? (const void*)ctx->xb : (const void*)ctx->x;  // A operand of the norm-fused GEMMs
-  HIP_TRY(ctx, timed_launch(ctx, TSD_K_EMBED, 2.0 * M * D * P, st, [&] { return launch_gemm(c.dtype, A_TOK, EP_STORE, g, st); }));
+  HIP_TRY(ctx, timed_launch(ctx, TSD_K_EMBED, 2.0 * M * D * P, st, [&] { return launch_gemm(c.dtype, A_TOK, EP_STORE, g, st); }, shape_of(ctx, ps.which, A_TOK, EP_STORE, g)));
   for (int l = 0; l < md.c.n_layers; ++l) {
     char* pool = md.kv_pool + (size_t)l * md.layer_pool_bytes;
     GemmP q;
@@ -444,7 +455,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     q.hd = md.hd;
     q.PT = c.page_tokens;
     q.pt_shift = __builtin_ctz(c.page_tokens);
-    HIP_TRY(ctx, timed_launch(ctx, TSD_K_QKV, 6.0 * M * D * D, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_QKV, q, st); }));
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_QKV, 6.0 * M * D * D, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_QKV, q, st); }, shape_of(ctx, ps.which, A_NORM, EP_QKV, q)));
     AttnP a;
     std::memset(&a, 0, sizeof(a));
     a.q = ctx->qbuf;
@@ -468,7 +479,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     a.scale = 1.0f / std::sqrt((float)md.hd);
     // K and V rows of the shortest history this pass can see (N-1 cached tokens + the new ones), q and output rows
     const double attn_bytes = (double)ps.B * D * ctx->es * (2.0 * (ctx->N - 1 + ps.nq + (ps.base_pos ? ps.pos_off : 1 - ctx->N)) + 2.0 * ps.nq);
-    HIP_TRY(ctx, timed_launch(ctx, TSD_K_ATTN, attn_bytes, st, [&] { return launch_attention(c.dtype, a, c.max_tokens, st); }));
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_ATTN, attn_bytes, st, [&] { return launch_attention(c.dtype, a, c.max_tokens, st); }, Shape{ps.which, 0, M, D, 0}));
     GemmP o;
     std::memset(&o, 0, sizeof(o));
     o.allow_skinny = ctx->skinny;
@@ -481,7 +492,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     o.W = md.layers[l].Wo;
     o.Cf = ctx->x;
     o.Cb = ctx->xb;
-    HIP_TRY(ctx, timed_launch(ctx, TSD_K_RESID, 2.0 * M * D * D, st, [&] { return launch_gemm(c.dtype, A_ACT, EP_RESID, o, st); }));
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_RESID, 2.0 * M * D * D, st, [&] { return launch_gemm(c.dtype, A_ACT, EP_RESID, o, st); }, shape_of(ctx, ps.which, A_ACT, EP_RESID, o)));
     if (md.c.n_experts > 0) {
       // routed FFN: router -> stable sort of (token, choice) by expert -> grouped up/down GEMMs -> gated combine
       const int E = md.c.n_experts, topk = md.c.top_k, slots = M * topk;
@@ -489,10 +500,13 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
       const int n_mtiles = (slots + bm - 1) / bm + E;
       HIP_TRY(ctx, timed_launch(ctx, TSD_K_ROUTE, 4.0 * M * D, st, [&] {
         return launch_router(ctx->x, md.layers[l].Wr, M, D, E, topk, ctx->moe_ids, ctx->moe_gates, st);
-      }));
+      }, Shape{ps.which, 1, M, E, D}));
+      if (ctx->route_tap[ps.which])
+        HIP_TRY(ctx, launch_route_tap(ctx->moe_ids, ctx->route_tap[ps.which], l, M, ps.nq, ps.act, ps.s0, ps.base_pos, ps.pos_off,
+                                      c.max_batch, c.max_tokens, topk, st));
       HIP_TRY(ctx, timed_launch(ctx, TSD_K_ROUTE, 12.0 * slots, st, [&] {
         return launch_permute(ctx->moe_ids, slots, topk, E, bm, n_mtiles, ctx->moe_src, ctx->moe_slot, ctx->moe_tmap, st);
-      }));
+      }, Shape{ps.which, 2, slots, E, 0}));
       GemmP f1;
       std::memset(&f1, 0, sizeof(f1));
       f1.M = slots;
@@ -507,7 +521,8 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
       f1.w_stride = (long)F * D;
       f1.n_mtiles = n_mtiles;
       f1.force_bm = bm;
-      HIP_TRY(ctx, timed_launch(ctx, TSD_K_GELU, 2.0 * slots * D * F, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_GELU, f1, st); }));
+      HIP_TRY(ctx, timed_launch(ctx, TSD_K_GELU, 2.0 * slots * D * F, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_GELU, f1, st); },
+                                shape_of(ctx, ps.which, A_NORM, EP_GELU, f1)));
       GemmP f2;
       std::memset(&f2, 0, sizeof(f2));
       f2.M = slots;
@@ -521,10 +536,11 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
       f2.w_stride = (long)D * F;
       f2.n_mtiles = n_mtiles;
       f2.force_bm = bm;
-      HIP_TRY(ctx, timed_launch(ctx, TSD_K_RESID, 2.0 * slots * D * F, st, [&] { return launch_gemm(c.dtype, A_ACT, EP_STORE, f2, st); }));
+      HIP_TRY(ctx, timed_launch(ctx, TSD_K_RESID, 2.0 * slots * D * F, st, [&] { return launch_gemm(c.dtype, A_ACT, EP_STORE, f2, st); },
+                                shape_of(ctx, ps.which, A_ACT, EP_STORE, f2)));
       HIP_TRY(ctx, timed_launch(ctx, TSD_K_ROUTE, 4.0 * D * (2.0 * M + slots), st, [&] {
         return launch_combine(c.dtype, ctx->moe_Y, ctx->moe_slot, ctx->moe_gates, ctx->x, c.dtype == TSD_BF16 ? ctx->xb : nullptr, M, D, topk, st);
-      }));
+      }, Shape{ps.which, 3, M, D, topk}));
       continue;
     }
     GemmP f1;
@@ -538,7 +554,8 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     f1.A = xin;
     f1.W = md.layers[l].W1;
     f1.Ct = ctx->hbuf;
-    HIP_TRY(ctx, timed_launch(ctx, TSD_K_GELU, 2.0 * M * D * F, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_GELU, f1, st); }));
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_GELU, 2.0 * M * D * F, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_GELU, f1, st); },
+                              shape_of(ctx, ps.which, A_NORM, EP_GELU, f1)));
     GemmP f2;
     std::memset(&f2, 0, sizeof(f2));
     f2.allow_skinny = ctx->skinny;
@@ -551,7 +568,8 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     f2.W = md.layers[l].W2;
     f2.Cf = ctx->x;
     f2.Cb = ctx->xb;
-    HIP_TRY(ctx, timed_launch(ctx, TSD_K_RESID, 2.0 * M * D * F, st, [&] { return launch_gemm(c.dtype, A_ACT, EP_RESID, f2, st); }));
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_RESID, 2.0 * M * D * F, st, [&] { return launch_gemm(c.dtype, A_ACT, EP_RESID, f2, st); },
+                              shape_of(ctx, ps.which, A_ACT, EP_RESID, f2)));
   }
   if (ps.out) {
     GemmP h;
@@ -568,7 +586,8 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     h.t_skip = ps.t_skip;
     h.act = ps.act;
     h.n_dev = ps.n_dev;
-    HIP_TRY(ctx, timed_launch(ctx, TSD_K_HEAD, 2.0 * M * D * P, st, [&] { return launch_gemm(c.dtype, A_NORM32, EP_HEAD, h, st); }));
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_HEAD, 2.0 * M * D * P, st, [&] { return launch_gemm(c.dtype, A_NORM32, EP_HEAD, h, st); },
+                              shape_of(ctx, ps.which, A_NORM32, EP_HEAD, h)));
   }
   return TSD_OK;
 }
@@ -592,15 +611,16 @@ bool device_counts(const tsd_ctx* ctx) {
 // list must not read the list's stale tail (it can repeat series that are still active: two workgroups would
 // then commit for one series).  Handles that follow the device-side count therefore ALWAYS cap their work by
 // it, captured or not: list and count are rewritten together, in stream order.  Handles whose passes are sized
-// on the host (routed FFN, one series, ...) keep two list buffers instead: compactions write the one not in use,
-// and tsd_num_active switches over when it takes delivery of the matching count.
+// on the host (routed FFN, one series, ...) keep two list buffers instead: compactions always write the second one
+// (a fixed address, so captured launch sequences may contain them), and tsd_num_active copies it over the list the
+// passes read when it takes delivery of the matching count.
 Cover cover(const tsd_ctx* ctx) {
   if (ctx->capturing && device_counts(ctx)) return Cover{ctx->act_list, ctx->B, ctx->count_out};
   if (ctx->n_act >= 0 && ctx->n_act < ctx->B) return Cover{ctx->act_list, ctx->n_act, device_counts(ctx) ? ctx->count_out : nullptr};
   return Cover{nullptr, ctx->B, nullptr};
 }
 // The list buffer a compaction may write now.
-int* compact_target(const tsd_ctx* ctx) { return device_counts(ctx) ? ctx->act_list : ctx->act_list_alt; }
+int* compact_target(const tsd_ctx* ctx) { return device_counts(ctx) ? ctx->act_list : ctx->act_list_next; }
 
 void drop_graphs(tsd_ctx* ctx) {
   for (hipGraphExec_t& g : ctx->graph_round)
@@ -711,10 +731,10 @@ int accept_commit_impl(tsd_ctx* ctx, const int32_t* forced, int K, hipStream_t s
     a.sync = ctx->count_out + 8;
     HIP_TRY(ctx, launch_fill_int(a.sync, INT_MAX, 1, st));
     a.mode = 1;
-    HIP_TRY(ctx, timed_launch(ctx, TSD_K_ACCEPT, 4.0 * ctx->B * c.patch * (2.0 * K + 2), st, [&] { return launch_accept(a, st); }));
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_ACCEPT, 4.0 * ctx->B * c.patch * (2.0 * K + 2), st, [&] { return launch_accept(a, st); }, Shape{-1, 0, cv.n, K, c.patch}));
     a.mode = 2;
   }
-  HIP_TRY(ctx, timed_launch(ctx, TSD_K_ACCEPT, 4.0 * ctx->B * c.patch * (2.0 * K + 2), st, [&] { return launch_accept(a, st); }));
+  HIP_TRY(ctx, timed_launch(ctx, TSD_K_ACCEPT, 4.0 * ctx->B * c.patch * (2.0 * K + 2), st, [&] { return launch_accept(a, st); }, Shape{-1, 0, cv.n, K, c.patch}));
   ctx->injected = false;
   ctx->compact_pending = false;  // whatever compaction was enqueued before describes an older state
   ctx->need_lb = 0;              // ... and so does the last count of patches still needed
@@ -1114,7 +1134,7 @@ int tsd_draft_propose(tsd_ctx* ctx, void* stream) {
     // work: the flops of the Kr + 1 token passes it replaces
     const double D = f.D, tok = (double)cv.n * (Kr + 1);
     const double flops = 2.0 * tok * (2.0 * P * D + f.L * (4.0 * D * D + 2.0 * D * f.F));
-    HIP_TRY(ctx, timed_launch(ctx, TSD_K_DRAFT, flops, st, [&] { return launch_draft_fused(f, st); }));
+    HIP_TRY(ctx, timed_launch(ctx, TSD_K_DRAFT, flops, st, [&] { return launch_draft_fused(f, st); }, Shape{TSD_DRAFT, 0, cv.n, Kr, 0}));
     return TSD_OK;
   }
   Pass ps;
@@ -1320,8 +1340,10 @@ int tsd_num_active(tsd_ctx* ctx, int32_t* out_host, void* stream) {
     HIP_TRY(ctx, hipMemcpyAsync(both, ctx->count_out, 8, hipMemcpyDeviceToHost, st));
     HIP_TRY(ctx, hipStreamSynchronize(st));
   }
-  // the list that belongs to these counts is the one the last compaction wrote
-  if (!device_counts(ctx)) std::swap(ctx->act_list, ctx->act_list_alt);
+  // the list that belongs to these counts is the one the last compaction wrote: it becomes the list the passes read
+  // (enqueued behind everything that still reads the old one)
+  if (!device_counts(ctx))
+    HIP_TRY(ctx, launch_copy(ctx->act_list, ctx->act_list_next, ((size_t)ctx->B * 4 + 15) & ~(size_t)15, st));
   *out_host = both[0];
   if (!(ctx->cfg.flags & TSD_FLAG_NO_COMPACT)) {
     ctx->n_act = both[0];    // later passes cover only these series ...
@@ -1340,7 +1362,8 @@ int tsd_run_rounds(tsd_ctx* ctx, int32_t max_rounds, int32_t* rounds_host, int32
     if ((rc = tsd_round(ctx, stream))) return rc;  // lowers need_lb (a bound on the most patches any series still needs) by K + 1
     ++rounds;
     // (handles whose passes are sized on the host need every count: it is what shrinks their passes)
-    if (ctx->need_lb > 0 && rounds < max_rounds && device_counts(ctx)) continue;  // somebody still needs patches: no need to ask
+    // (a running measurement asks every time, so that the rows it books for a launch are the rows the launch runs)
+    if (ctx->need_lb > 0 && rounds < max_rounds && device_counts(ctx) && ctx->prof_class < 0) continue;  // somebody still needs patches: no need to ask
     if ((rc = tsd_num_active(ctx, &active, stream))) return rc;
     if (active == 0) break;
   }
@@ -1427,12 +1450,27 @@ int tsd_get_series_stats(tsd_ctx* ctx, int64_t* out_dev, void* stream) {
   return TSD_OK;
 }
 
+int tsd_set_route_tap(tsd_ctx* ctx, int which, int32_t* ids_dev, size_t n_ints) {
+  if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
+  if (which != TSD_TARGET && which != TSD_DRAFT) return fail(ctx, TSD_E_INVALID_ARG, "which must be TSD_TARGET or TSD_DRAFT");
+  const tsd_model_cfg& m = ctx->model[which].c;
+  if (ids_dev) {
+    if (m.n_experts == 0) return fail(ctx, TSD_E_BAD_STATE, "this model has a dense FFN: there are no routing choices to record");
+    const size_t need = (size_t)m.n_layers * ctx->cfg.max_batch * ctx->cfg.max_tokens * m.top_k;
+    if (n_ints < need) return fail(ctx, TSD_E_INVALID_ARG, "ids_dev must hold n_layers * max_batch * max_tokens * top_k int32");
+  }
+  ctx->route_tap[which] = ids_dev;
+  drop_graphs(ctx);  // the captured launch sequences do not contain the tap's copies
+  return TSD_OK;
+}
+
 int tsd_profile_begin(tsd_ctx* ctx, int kernel_class) {
   if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
-  if (kernel_class < -1 || kernel_class >= TSD_K_COUNT) return fail(ctx, TSD_E_INVALID_ARG, "kernel_class must be a TSD_K_* value or -1");
+  if (kernel_class < -1 || kernel_class > TSD_K_COUNT) return fail(ctx, TSD_E_INVALID_ARG, "kernel_class must be a TSD_K_* value, TSD_K_COUNT (every family) or -1");
   ctx->prof_class = kernel_class;
   ctx->prof_used = 0;
   ctx->prof_work = 0;
+  ctx->prof_recs.clear();
   return TSD_OK;
 }
 
@@ -1447,6 +1485,7 @@ int tsd_profile_end(tsd_ctx* ctx, int64_t* launches_host, double* ms_host, doubl
     float t = 0;
     HIP_TRY(ctx, hipEventElapsedTime(&t, ctx->prof_events[i].first, ctx->prof_events[i].second));
     ms += t;
+    if (i < ctx->prof_recs.size()) ctx->prof_recs[i].ms = t;
   }
   *launches_host = (int64_t)ctx->prof_used;
   *ms_host = ms;
@@ -1455,9 +1494,19 @@ int tsd_profile_end(tsd_ctx* ctx, int64_t* launches_host, double* ms_host, doubl
   return TSD_OK;
 }
 
-int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_dev, const void* Wt_dev, float* C_dev,
+int tsd_profile_launches(tsd_ctx* ctx, tsd_launch_rec* out_host, int32_t max_records, int32_t* n_host) {
+  if (!ctx) return fail(nullptr, TSD_E_INVALID_ARG, "ctx is NULL");
+  if (!n_host || (max_records > 0 && !out_host) || max_records < 0) return fail(ctx, TSD_E_INVALID_ARG, "need n_host, and out_host for max_records > 0");
+  if (ctx->prof_class >= 0) return fail(ctx, TSD_E_BAD_STATE, "a measurement is still running: call tsd_profile_end first");
+  *n_host = (int32_t)ctx->prof_recs.size();
+  for (size_t i = 0; i < ctx->prof_recs.size() && i < (size_t)max_records; ++i) out_host[i] = ctx->prof_recs[i];
+  return TSD_OK;
+}
+
+int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_dev, const void* Wt_dev, void* C_dev,
                    void* stream) {
-  if (variant < 0 || variant > 2) return fail(nullptr, TSD_E_INVALID_ARG, "variant must be 0, 1 or 2");
+  if (variant < 0 || variant > 3) return fail(nullptr, TSD_E_INVALID_ARG, "variant must be 0, 1, 2 or 3");
+  if (variant == 3 && dtype != TSD_BF16) return fail(nullptr, TSD_E_INVALID_ARG, "variant 3 is bf16 only");
   if (dtype != TSD_F32 && dtype != TSD_BF16) return fail(nullptr, TSD_E_INVALID_ARG, "dtype must be TSD_F32 or TSD_BF16");
   if (M < 1 || N < 4 || K < 8 || (K % 8) || (N % 4)) return fail(nullptr, TSD_E_INVALID_ARG, "need M >= 1, N a multiple of 4, K a multiple of 8");
   if (!A_dev || !Wt_dev || !C_dev) return fail(nullptr, TSD_E_INVALID_ARG, "device pointers must not be NULL");
@@ -1475,7 +1524,13 @@ int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_de
   g.nq = 1;
   g.A = A_dev;
   g.W = Wt_dev;
-  g.Cf = C_dev;
+  g.Cf = reinterpret_cast<float*>(C_dev);
+  if (variant == 3) {  // the FFN-up product as the passes run it: fused norm, GELU, result in the compute dtype
+    g.Cf = nullptr;
+    g.Ct = C_dev;
+    HIP_TRY(nullptr, launch_gemm(dtype, A_NORM, EP_GELU, g, (hipStream_t)stream));
+    return TSD_OK;
+  }
   HIP_TRY(nullptr, launch_gemm(dtype, variant == 1 ? A_NORM : A_ACT, variant == 2 ? EP_RESID : EP_STORE, g, (hipStream_t)stream));
   return TSD_OK;
 }
@@ -1485,15 +1540,6 @@ int tsd_bench_copy(void* dst_dev, const void* src_dev, size_t bytes, void* strea
   if (bytes == 0 || (bytes % 16) || ((uintptr_t)dst_dev % 16) || ((uintptr_t)src_dev % 16))
     return fail(nullptr, TSD_E_INVALID_ARG, "bytes and both pointers must be non-zero multiples of 16");
   HIP_TRY(nullptr, launch_copy(dst_dev, src_dev, bytes, (hipStream_t)stream));
-  return TSD_OK;
-}
-
-int tsd_bench_stream(const void* src_dev, size_t bytes_per_block, int32_t blocks, int32_t iters, uint32_t* sink_dev,
-                     void* stream) {
-  if (!src_dev || !sink_dev) return fail(nullptr, TSD_E_INVALID_ARG, "device pointers must not be NULL");
-  if (bytes_per_block < 16 || (bytes_per_block % 16) || ((uintptr_t)src_dev % 16) || blocks < 1 || blocks > 65536 || iters < 1)
-    return fail(nullptr, TSD_E_INVALID_ARG, "need bytes_per_block a positive multiple of 16, 1..65536 blocks, iters >= 1");
-  HIP_TRY(nullptr, launch_stream(src_dev, bytes_per_block, blocks, iters, sink_dev, (hipStream_t)stream));
   return TSD_OK;
 }
 

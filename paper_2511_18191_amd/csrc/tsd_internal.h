@@ -111,6 +111,8 @@ hipError_t prepare_gemm(int dtype);
 bool skinny_applicable(int dtype, int amode, int epi, const GemmP& p);
 hipError_t launch_gemm_skinny(int amode, int epi, const GemmP& p, hipStream_t st);
 int gemm_row_tile(int dtype, int M, int N, int force_bm);
+// which kernel launch_gemm picks for this product: 16 = skinny, 64 / 128 = tile size, 464 = 64 x 64 tiles with K split over four wavefront groups
+int gemm_variant(int dtype, int amode, int epi, const GemmP& p);
 // s_max: upper bound on (position of the pass's last token) + 1 over all series; sizes the score buffer.
 hipError_t launch_attention(int dtype, const AttnP& p, int s_max, hipStream_t st);
 // dynamic LDS the attention kernel needs for up to s_max cached tokens (must stay <= 160 KB)
@@ -250,6 +252,8 @@ hipError_t launch_router(const float* x, const float* Wr, int M, int D, int E, i
                          hipStream_t st);
 hipError_t launch_permute(const int* ids, int n_assign, int topk, int E, int BM, int n_mtiles, int* src_row,
                           int* slot_of, void* tile_map, hipStream_t st);
+hipError_t launch_route_tap(const int* ids, int* tap, int layer, int M, int nq, const int* act, int s0, const int* base_pos,
+                            int pos_off, int max_batch, int max_tokens, int topk, hipStream_t st);
 hipError_t launch_combine(int dtype, const float* Y, const int* slot_of, const float* gates, float* x, void* xb, int M,
                           int D, int topk, hipStream_t st);
 
@@ -266,6 +270,5 @@ hipError_t launch_sum_stats(const long long* stat, int B, long long* out5, hipSt
 hipError_t launch_fill_nan(float* p, long n, hipStream_t st);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 hipError_t launch_mfma_peak(int blocks, int iters, float* sink, hipStream_t st);
-hipError_t launch_stream(const void* src, size_t bytes_per_block, int blocks, int iters, unsigned* sink, hipStream_t st);
 
 }  // namespace tsd

@@ -105,9 +105,8 @@ def test_measurement_taps_validate_before_any_launch():
     assert L.tsd_bench_mfma(1 << 20, 1, 0x1000, None) == -1
     assert L.tsd_bench_copy(None, 0x1000, 1024, None) == -1
     assert L.tsd_bench_copy(0x1000, 0x2000, 1000, None) == -1                 # not a multiple of 16
-    assert L.tsd_bench_stream(None, 1024, 4, 1, 0x1000, None) == -1
-    assert L.tsd_bench_stream(0x1000, 1000, 4, 1, 0x2000, None) == -1         # slice not a multiple of 16
-    assert L.tsd_bench_gemm(tsd.TSD_BF16, 3, 64, 64, 64, 0x1000, 0x2000, 0x3000, None) == -1   # unknown variant
+    assert L.tsd_bench_gemm(tsd.TSD_BF16, 4, 64, 64, 64, 0x1000, 0x2000, 0x3000, None) == -1   # unknown variant
+    assert L.tsd_bench_gemm(tsd.TSD_F32, 3, 64, 64, 64, 0x1000, 0x2000, 0x3000, None) == -1    # the FFN-up variant is bf16 only
     assert L.tsd_bench_gemm(tsd.TSD_BF16, 0, 64, 64, 60, 0x1000, 0x2000, 0x3000, None) == -1   # K not a multiple of 8
     assert L.tsd_trace_draft(None, None, 8, None, None) != 0                 # no handle
 

@@ -10,7 +10,7 @@ import torch
 from scipy import stats
 
 import synth
-from harness import TOL, Case, lockstep, rel_err
+from harness import PASS_TOL, TOL, Case, lockstep, rel_err
 from oracle import tsd_oracle as orc
 
 pytestmark = pytest.mark.gpu
@@ -36,23 +36,30 @@ def _decode_target_only(sess, T):
 def test_round_lockstep(name, sigma):
     case = Case(name, sigma=sigma)
     sess = case.session()
-    # bf16 + routed FFN: top-k routing is discontinuous, so the small drift between the two
-    # histories can flip an expert choice and move a patch by O(1); that case is held to the
-    # per-pass comparison (oracle evaluated on the GPU's own tokens), where routing agrees.
+    # bf16 + routed FFN: top-k routing is discrete, so operand rounding can flip an expert choice where the
+    # router nearly ties, and a flipped choice moves a patch by O(1).  The comparison is therefore routing-
+    # aligned: the oracle's target runs with the experts the GPU chose (filed per layer, series and position),
+    # every choice that differs from the oracle's own is counted and must sit inside the stated near-tie
+    # window, and the flat tolerances then apply to the routed path as to every other.
     routed_bf16 = case.cfg.dtype == "bf16" and case.cfg.target.n_experts > 0
-    rep = lockstep(case, sess, tol=float("inf") if routed_bf16 else None)
+    rep = lockstep(case, sess, route_aligned=routed_bf16)
     c = case.cfg
     print(f"\n{name} sigma={sigma}: rel X {rep['max_rel_X']:.2e} mu_p {rep['max_rel_mu_p']:.2e} "
           f"per-pass q {rep['pass_rel_q']:.2e} p {rep['pass_rel_p']:.2e} "
-          f"mismatched {rep['mismatched']} near-ties {rep['near_ties']} accept {rep['accepted']}/{rep['tested']}")
-    if not routed_bf16:
-        assert rep["max_rel_X"] <= TOL[c.dtype] and rep["max_rel_mu_p"] <= TOL[c.dtype]
+          f"mismatched {rep['mismatched']} (outside the window {rep['mismatched_outside_window']}) near-ties {rep['near_ties']} "
+          f"accept {rep['accepted']}/{rep['tested']} ell excess {rep['ell_excess']:.2e}"
+          + (f" routing: {rep['route_flips']} of {rep['route_choices']} choices differ, largest gap {rep['route_flip_max_gap']:.3f}"
+             if routed_bf16 else ""))
+    assert rep["max_rel_X"] <= TOL[c.dtype] and rep["max_rel_mu_p"] <= TOL[c.dtype]
+    assert rep["mismatched_outside_window"] == 0
+    if routed_bf16:
+        assert rep["route_choices"] > 0 and rep["route_flips"] <= 0.05 * rep["route_choices"]
     if c.dtype == "fp32":
         assert rep["mismatched"] <= rep["near_ties"]
         assert rep["max_abs_ell"] < 1e-5
     # committed state after forced lock-step equals the oracle's
     fc = sess.get_forecast().cpu().numpy()
-    for b in range(0 if not routed_bf16 else c.batch, c.batch):
+    for b in range(c.batch):
         _, m, s = case.oracle_hist(b)
         ref = (rep["Y"][b].reshape(-1) * s + m)[: c.horizon]
         scale = np.abs(ref).max()
@@ -89,20 +96,24 @@ def test_free_running_fp32_matches_oracle(name, sigma):
     _decode_spec(sess)
     fc = sess.get_forecast().cpu().numpy()
     st = sess.get_stats()
-    tested = accepted = rounds = near = 0
+    per = sess.get_series_stats().cpu().numpy()                  # rounds, tested, accepted, committed, near ties
+    near_total = clean = 0
     for b in range(c.batch):
         trace = []
         ref, s = orc.forecast_spec(case.Wt, c.target, case.Wd, c.draft, case.context[b], c.patch, c.horizon, c.K,
                                    c.sigma, c.sigma, case.seed, b, trace=trace)
+        near = 0                                                 # this series' own near ties: nobody else's excuse it
         for r in trace:
             t = r["n"] + (r["n"] < r["X"].shape[0])      # positions of that round (fewer near the horizon)
             near += int(np.any(np.abs(np.minimum(0, r["ell"][:t]) - r["logu"][:t]) < 1e-4))
-        tested, accepted, rounds = tested + s["tested"], accepted + s["accepted"], rounds + s["rounds"]
+        near_total += near
         if near == 0:
+            clean += 1
             np.testing.assert_allclose(fc[b], ref, rtol=0, atol=1e-4 * np.abs(ref).max())
-    if near == 0:
-        assert (st["tested"], st["accepted"], st["rounds"]) == (tested, accepted, rounds)
-    assert st["near_ties"] <= near + 1
+            assert (per[b, 0], per[b, 1], per[b, 2], per[b, 3]) == (s["rounds"], s["tested"], s["accepted"], s["committed"]), f"series {b}"
+    assert clean >= c.batch - near_total and clean > 0
+    assert st["near_ties"] <= near_total + 1
+    assert st["rounds"] == per[:, 0].sum() and st["tested"] == per[:, 1].sum() and st["accepted"] == per[:, 2].sum()
 
 
 @pytest.mark.parametrize("name", ["cfg1", "mini2", "mini3"])
@@ -309,19 +320,21 @@ def test_full_size_sampled_series(name, dtype, subset, rounds):
     # few sampled series (series are independent) for the first rounds.
     # Routed FFN: the fp32 run pins the implementation at 1e-4.  In bf16 the discrete top-k choice
     # flips for some tokens under operand rounding (about 2000 routing decisions feed one pass of
-    # one series, and with random-init weights an expert's output is as large as the residual
-    # stream), so there the comparison is reported, not asserted.
+    # one series), so there the comparison is routing-aligned (see test_round_lockstep) and then held
+    # to the same tolerances as the dense configurations.
     case = Case(name, dtype=dtype)
     c = case.cfg
     sess = case.session()
     routed_bf16 = c.target.n_experts > 0 and dtype == "bf16"
-    rep = lockstep(case, sess, max_rounds=rounds, subset=subset, tol=float("inf"), check=not routed_bf16)
+    rep = lockstep(case, sess, max_rounds=rounds, subset=subset, route_aligned=routed_bf16)
     print(f"\n{name} {dtype} full size: per-pass q {rep['pass_rel_q']:.2e} p {rep['pass_rel_p']:.2e}; chained X {rep['max_rel_X']:.2e} "
-          f"mu_p {rep['max_rel_mu_p']:.2e}; lengths {rep['lengths']} mismatched {rep['mismatched']}")
-    if not routed_bf16:
-        assert rep["max_rel_X"] <= TOL[c.dtype] and rep["max_rel_mu_p"] <= TOL[c.dtype]
-    else:
-        assert rep["pass_rel_q"] <= 8e-3          # the dense draft is unaffected by routing
+          f"mu_p {rep['max_rel_mu_p']:.2e}; lengths {rep['lengths']} mismatched {rep['mismatched']} "
+          f"(outside the window {rep['mismatched_outside_window']}) ell excess {rep['ell_excess']:.2e}"
+          + (f"; routing: {rep['route_flips']} of {rep['route_choices']} choices differ, largest gap {rep['route_flip_max_gap']:.3f}"
+             if routed_bf16 else ""))
+    assert rep["max_rel_X"] <= TOL[c.dtype] and rep["max_rel_mu_p"] <= TOL[c.dtype]
+    assert rep["pass_rel_q"] <= PASS_TOL[c.dtype] and rep["pass_rel_p"] <= PASS_TOL[c.dtype]
+    assert rep["mismatched_outside_window"] == 0
     # properties that hold at any size: finish the decode free-running and check the books
     while sess.num_active() > 0:
         sess.round()
@@ -331,6 +344,74 @@ def test_full_size_sampled_series(name, dtype, subset, rounds):
     assert int(state["committed"].min()) == c.T and int(state["len"].max()) == c.n_ctx - 1 + c.T
     assert st["tested"] - st["accepted"] <= st["rounds"] and st["accepted"] <= st["tested"]
     assert torch.isfinite(sess.get_forecast()).all()
+
+
+@pytest.mark.parametrize("K", [1, 4, 8])
+def test_cfg4_full_size_lockstep(K):
+    # The latency regime at its full size: one series, the 24-layer d = 1024 target through the skinny
+    # weight-streaming products (at most 9 rows, K split over 16 wavefronts), the block size set with
+    # tsd_set_block_size on a handle created for K = 8 as the K sweep does, two rounds in lock-step with the
+    # oracle, then the free-running tail through tsd_round and the books.
+    case = Case("cfg4", K=8, horizon=96 * 12, sigma=1.5)          # T = 12: room for two rounds at K = 8 (the second may be cut short)
+    c = case.cfg
+    sess = case.session()
+    if K != 8:
+        import dataclasses
+        sess.set_block_size(K)
+        case.cfg = dataclasses.replace(c, K=K)
+        c = case.cfg
+    rep = lockstep(case, sess, max_rounds=2)
+    print(f"\ncfg4 K={K}: per-pass q {rep['pass_rel_q']:.2e} p {rep['pass_rel_p']:.2e}; chained X {rep['max_rel_X']:.2e} "
+          f"mu_p {rep['max_rel_mu_p']:.2e}; lengths {rep['lengths']} mismatched {rep['mismatched']} "
+          f"(outside the window {rep['mismatched_outside_window']}) ell excess {rep['ell_excess']:.2e}")
+    assert rep["max_rel_X"] <= TOL["bf16"] and rep["max_rel_mu_p"] <= TOL["bf16"]
+    assert rep["pass_rel_q"] <= PASS_TOL["bf16"] and rep["pass_rel_p"] <= PASS_TOL["bf16"]
+    assert rep["mismatched_outside_window"] == 0 and all(1 <= L <= K + 1 for L in rep["lengths"])
+    while sess.num_active() > 0:
+        sess.round()
+    st, state = sess.get_stats(), sess.get_state()
+    assert st["committed"] == c.T and int(state["len"][0]) == c.n_ctx - 1 + c.T
+    assert torch.isfinite(sess.get_forecast()).all()
+
+
+def test_cfg4_block_size_sweep_follows_the_law():
+    # Configuration 4's K sweep as a checked result.  Under an injected i.i.d. acceptance rate (every tested
+    # position accepted with probability alpha, Eq. 7's premise) the committed patches per round must follow
+    # E[L] = (1 - alpha^(K+1)) / (1 - alpha) for every K = 1..8; with the rule itself, where acceptance depends
+    # on the position, the mean must lie inside the dependence sandwich E[L](alpha_min) <= mean <= E[L](alpha_max)
+    # over the per-position rates measured in the same run (Proposition "Dependence bounds").
+    import paper_2511_18191_amd as tsd
+    case = Case("cfg4", K=8, B=32, horizon=96 * 30, sigma=0.6)   # 32 series of the generator, each decoded as in cfg 4
+    c = case.cfg
+    sess = case.session(flags=tsd.TSD_FLAG_NO_SKINNY)             # (32 series: the tiled products; the skinny path is tested above)
+    alpha = 0.8
+    for K in range(1, 9):
+        sess.set_block_size(K)
+        sess.set_accept_override(alpha)
+        sess.prefill(case.context, c.n_ctx, c.horizon)
+        counts = np.zeros(K + 2)
+        for _ in range(3):                                        # three rounds: at most 27 of the 30 patches
+            sess.round()
+            counts += np.bincount(sess.get_round_io()["n_acc"].cpu().numpy() + 1, minlength=K + 2)
+        mean_L = (np.arange(K + 2) * counts).sum() / counts.sum()
+        want = orc.expected_block_length(alpha, K)
+        sd = np.sqrt(((np.arange(1, K + 2) - want) ** 2 * orc.block_length_pmf(alpha, K)).sum() / counts.sum())
+        assert abs(mean_L - want) < 4.5 * sd, f"K={K}: mean committed {mean_L:.3f} vs Eq. 7 {want:.3f} (sd {sd:.3f})"
+    sess.set_accept_override(-1.0)
+    for K in (2, 4, 8):
+        sess.set_block_size(K)
+        sess.prefill(case.context, c.n_ctx, c.horizon)
+        acc, tst, L = np.zeros(K), np.zeros(K), []
+        for _ in range(3):
+            sess.round()
+            n = sess.get_round_io()["n_acc"].cpu().numpy()
+            L += list(n + 1)
+            for i in range(K):
+                tst[i] += (n >= i).sum()                          # position i+1 was tested iff the first i were accepted
+                acc[i] += (n > i).sum()
+        rates = acc[tst > 0] / tst[tst > 0]
+        lo, hi = orc.expected_block_length(rates.min(), K), orc.expected_block_length(rates.max(), K)
+        assert lo - 1e-9 <= np.mean(L) <= hi + 1e-9, f"K={K}: mean {np.mean(L):.3f} outside [{lo:.3f}, {hi:.3f}]"
 
 
 @pytest.mark.parametrize("M,N,K", [(40, 96, 16), (77, 200, 264), (1280, 1536, 512), (300, 512, 2048), (2304, 1024, 1024),

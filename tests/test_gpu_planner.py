@@ -80,20 +80,28 @@ def test_plan_follows_the_law_and_the_measured_optimum():
     S = p["S_table"]
     assert p["k_table"] == max(S, key=S.get)
     assert p["k_rule"] == law.best_block_size(0.8, costs[4]["c"], costs[4]["v"], k_max=8)
-    # measured committed-patch rate at the planned K is within 25 % of the best measured one (Eq. 8 is
-    # flat within a few per cent over K = 1..5 here, so launch-time noise moves its argmax between
-    # 2 and 5, and the 192 series-rounds behind each measured block length, all from the same draws,
-    # sit 3-8 % below Eq. 7)
-    rate = {}
+    # What the plan rests on, checked without racing two timings against each other: at every K the measured
+    # committed patches per round follow Eq. 7 (192 series-rounds each, within 4.5 standard errors of the law's
+    # own spread), so the measured rate L(K) / (c(K) K + v(K)) over the SAME cost table differs from Eq. 8 only
+    # by that sampling error, and at the planned K it is within that error of the best one.
+    from oracle import tsd_oracle as orc
+    rate, slack = {}, {}
     for K in range(1, 9):
         s.set_block_size(K)
         s.reset_decode()
         for _ in range(3):
             s.round()
         st = s.get_stats()
+        L = st["committed"] / st["rounds"]
+        want = law.mean_block_length(0.8, K)
+        se = np.sqrt(((np.arange(1, K + 2) - want) ** 2 * orc.block_length_pmf(0.8, K)).sum() / st["rounds"])
+        assert abs(L - want) <= 4.5 * se, f"K={K}: {L:.3f} patches per round vs Eq. 7 {want:.3f} (standard error {se:.3f})"
         t = costs[K]
-        rate[K] = st["committed"] / st["rounds"] / (t["draft"] + t["verify"] + t["accept"])
-    assert rate[p["k_table"]] >= 0.75 * max(rate.values()), (p["k_table"], rate)
+        rate[K] = L / (t["c"] * K + t["v"])
+        slack[K] = 4.5 * se / (t["c"] * K + t["v"])
+        assert abs(rate[K] - S[K]) <= slack[K]
+    best = max(rate, key=rate.get)
+    assert rate[p["k_table"]] >= rate[best] - slack[best] - slack[p["k_table"]], (p["k_table"], rate)
 
 
 def test_calibrated_temperature_hits_the_rate_and_the_oracle_agrees():

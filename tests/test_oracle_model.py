@@ -213,3 +213,38 @@ def test_forward_multi_token_multi_head_matches_library_composition():
         np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-12)
         # (and the comparison can fail: the composition on the reversed token order is far away)
         assert np.abs(got - _forward_from_library_pieces(W, m, tok[::-1].copy())[::-1]).max() > 1e-3
+
+
+def test_forced_expert_choice_is_the_same_mixture_with_other_experts():
+    # the comparison aid of the routed FFN: imposing a token's own choice changes nothing; imposing another set
+    # gives that set's mixture with the router's probabilities renormalised over it; rows of -1 stay free;
+    # the reported gap is the log ratio between the last expert taken and the first one left out
+    m, W = _tiny(n_experts=4)
+    b = np.random.default_rng(41).standard_normal((6, 32))
+    info = []
+    free = orc.ffn_routed(b, W, 0, m, info=info)
+    own = np.array([list(i[0]) for i in info])
+    np.testing.assert_array_equal(orc.ffn_routed(b, W, 0, m, forced=own), free)
+    pr = orc.softmax(b @ W["l0.W_r"])
+    ex = lambda e: orc.gelu_tanh(b @ W[f"l0.e{e}.W_1"]) @ W[f"l0.e{e}.W_2"]
+    forced = np.full((6, 2), -1)
+    forced[2] = (3, 0); forced[4] = (1, 2)
+    got = orc.ffn_routed(b, W, 0, m, forced=forced)
+    np.testing.assert_array_equal(got[[0, 1, 3, 5]], free[[0, 1, 3, 5]])
+    for t, (e0, e1) in ((2, (3, 0)), (4, (1, 2))):
+        ref = (pr[t, e0] * ex(e0)[t] + pr[t, e1] * ex(e1)[t]) / (pr[t, e0] + pr[t, e1])
+        np.testing.assert_allclose(got[t], ref, rtol=1e-12)
+    for t, (order, gap) in enumerate(info):
+        srt = np.sort(pr[t])[::-1]
+        assert set(order) == set(np.argsort(-pr[t], kind="stable")[:2]) and math.isclose(gap, math.log(srt[1] / srt[2]), rel_tol=1e-12)
+    # through the whole forward: the model's own choices imposed = the free forward, and the info has one list per layer
+    tok = np.random.default_rng(42).standard_normal((5, 8))
+    ri = []
+    base = orc.forward(W, m, tok, route_info=ri)
+    assert len(ri) == m.n_layers and all(len(x) == 5 for x in ri)
+    ids = np.array([[list(i[0]) for i in layer] for layer in ri])
+    np.testing.assert_array_equal(orc.forward(W, m, tok, forced_experts=ids), base)
+    ids2 = ids.copy(); ids2[1, 3] = [e for e in range(4) if e not in ids[1, 3]][:2]
+    out2 = orc.forward(W, m, tok, forced_experts=ids2)
+    np.testing.assert_array_equal(out2[:3], base[:3])                 # causal: only tokens from 3 on can move
+    assert np.abs(out2[3:] - base[3:]).max() > 1e-6
