@@ -41,6 +41,7 @@ def parse():
     ap.add_argument("--batch-sync", action="store_true", help="variant: all series keep the batch's smallest accepted count")
     ap.add_argument("--fused-draft", choices=["auto", "on", "off"], default="auto",
                     help="the draft phase as one launch: where the library picks it (auto), wherever supported (on), never (off)")
+    ap.add_argument("--no-wide", action="store_true", help="A/B: never the wide-tile direct-to-LDS GEMM kernels (same bits)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-workers", type=int, default=0, help="oracle worker processes (default: the CPUs this process may use, at most 16)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="the oracle keeps taking series until about this much wall time has passed")
@@ -121,7 +122,7 @@ def measured_traffic(workload):
     return out, os.path.relpath(path, ROOT)
 
 
-TILE_LABEL = {128: "128x128", 64: "64x64", 464: "64x64k4", 16: "skinny"}
+TILE_LABEL = {128: "128x128", 64: "64x64", 464: "64x64k4", 16: "skinny", 2256: "w256x128", 2128: "w128x128"}
 
 
 def kernel_rooflines(sess, dtype, steps, traffic, cfg=None):
@@ -332,6 +333,7 @@ def main():
     flags = (tsd.TSD_FLAG_SAMPLE_PROPOSALS if a.sample_proposals else 0) | (tsd.TSD_FLAG_NAIVE_VERIFY if a.naive_verify else 0)
     flags |= (tsd.TSD_FLAG_THRESHOLD_RULE if a.threshold_rule else 0) | (tsd.TSD_FLAG_BATCH_SYNC if a.batch_sync else 0)
     flags |= {"auto": 0, "on": tsd.TSD_FLAG_FUSED_DRAFT, "off": tsd.TSD_FLAG_NO_FUSED_DRAFT}[a.fused_draft]
+    flags |= tsd.TSD_FLAG_NO_WIDE_GEMM if a.no_wide else 0
     head = run_config(torch, tsd, synth, a, a.config, a.steps, a.warmup, max(2, a.steps // 4), flags, case=case)
     del case
     peaks = measured_peaks(torch, tsd)
@@ -346,7 +348,8 @@ def main():
         "config": {"workload": head["workload"],
                    "step": "reset to post-prefill state + speculative rounds until all series reach the horizon",
                    "ablation": {"sample_proposals": a.sample_proposals, "fallback_r": a.fallback_r, "naive_verify": a.naive_verify,
-                                "threshold_rule": a.threshold_rule, "batch_sync": a.batch_sync, "fused_draft": a.fused_draft}},
+                                "threshold_rule": a.threshold_rule, "batch_sync": a.batch_sync, "fused_draft": a.fused_draft,
+                                "no_wide_gemm": a.no_wide}},
     }
     out.update({k: head[k] for k in ("speedup_vs_target_only", "target_only_steps_per_s", "target_only_ms", "prefill_ms",
                                      "rounds_per_decode", "acceptance", "mean_committed_per_round", "phase_ms", "c", "v",

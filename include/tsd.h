@@ -73,6 +73,7 @@ extern "C" {
 #define TSD_FLAG_NO_PINNED_COUNTS 512u /* tsd_num_active copies the counts back and waits on the stream */
 #define TSD_FLAG_NO_FUSED_DRAFT 1024u /* always run the draft phase kernel by kernel                       */
 #define TSD_FLAG_FUSED_DRAFT 2048u /* run the draft phase as one launch wherever that kernel is supported */
+#define TSD_FLAG_NO_WIDE_GEMM 4096u /* never use the wide-tile direct-to-LDS GEMM kernels (same bits, for A/B timing) */
 
 typedef struct tsd_ctx tsd_ctx; /* opaque */
 
@@ -366,7 +367,8 @@ int tsd_profile_launches(tsd_ctx* ctx, tsd_launch_rec* out_host, int32_t max_rec
  * C[M,N] = A[M,K] * Wt[N,K]^T (fp32 result); variant 1: the same with each row of the product
  * scaled by rsqrt(mean(A_row^2) + 1e-6) (the fused RMSNorm); variant 2: C += A * Wt^T (the
  * residual epilogue); variant 3 (bf16 only): C = GELU_tanh(RMSNorm-scaled product), stored as bf16 [M,N]: the
- * FFN-up product exactly as the passes run it.  K must be a multiple of 8, N of 4.  No handle needed. */
+ * FFN-up product exactly as the passes run it; variant + 8: the same without the wide-tile kernels.  K must be a
+ * multiple of 8, N of 4.  No handle needed. */
 int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_dev, const void* Wt_dev, void* C_dev,
                    void* stream);
 

@@ -10,6 +10,7 @@ TSD_F32, TSD_BF16 = 0, 1
 TSD_TARGET, TSD_DRAFT = 0, 1
 TSD_FLAG_SCRAMBLE_PAGES, TSD_FLAG_NO_TEMPERING, TSD_FLAG_NO_GRAPH, TSD_FLAG_NO_COMPACT, TSD_FLAG_NO_SKINNY, TSD_FLAG_SAMPLE_PROPOSALS, TSD_FLAG_NAIVE_VERIFY = 1, 2, 4, 8, 16, 32, 64
 TSD_FLAG_THRESHOLD_RULE, TSD_FLAG_BATCH_SYNC, TSD_FLAG_NO_PINNED_COUNTS, TSD_FLAG_NO_FUSED_DRAFT, TSD_FLAG_FUSED_DRAFT = 128, 256, 512, 1024, 2048
+TSD_FLAG_NO_WIDE_GEMM = 4096
 KERNEL_CLASSES = ["embed", "qkv", "attn", "resid", "gelu", "head", "accept", "route", "draft"]   # TSD_K_* order
 
 
@@ -133,7 +134,7 @@ def bench_gemm(A, Wt, out=None, variant=0):
     N = Wt.shape[0]
     dt = TSD_BF16 if A.dtype == torch.bfloat16 else TSD_F32
     if out is None:
-        out = torch.empty(M, N, dtype=torch.bfloat16 if variant == 3 else torch.float32, device=A.device)
+        out = torch.empty(M, N, dtype=torch.bfloat16 if (variant & 7) == 3 else torch.float32, device=A.device)
     _check(lib().tsd_bench_gemm(dt, variant, M, N, K, A.data_ptr(), Wt.data_ptr(), out.data_ptr(),
                                 torch.cuda.current_stream(A.device).cuda_stream))
     return out

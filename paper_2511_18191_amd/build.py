@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libtsd.so")
-SOURCES = ["tsd_api.hip", "gemm.hip", "gemm_skinny.hip", "attn.hip", "misc.hip", "moe.hip", "draft_fused.hip", "accept_static.hip"]
+SOURCES = ["tsd_api.hip", "gemm.hip", "gemm_skinny.hip", "attn.hip", "misc.hip", "moe.hip", "draft_fused.hip", "accept_static.hip", "gemm_wide.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
          # packed-fp32 instruction selection is switched off on purpose for the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -163,11 +163,14 @@ __global__ __launch_bounds__(256 * G) void gemm_kernel(const GemmP p) {
         }
       } else {
         if constexpr (kNorm) {
+          // a chain of packed bf16 dot products per 16-byte chunk position: the wide-tile kernel (gemm_wide.hip)
+          // forms the same chains from its MFMA fragments, so either kernel gives a row the same scale
+          typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
           const bf16x8 v = *reinterpret_cast<const bf16x8*>(&ra[i]);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const float f = (float)v[e];
-            ss[i] = fmaf(f, f, ss[i]);
+          for (int e = 0; e < 4; ++e) {
+            const bf16x2 pr = {v[2 * e], v[2 * e + 1]};
+            ss[i] = __builtin_amdgcn_fdot2_f32_bf16(pr, pr, ss[i], false);
           }
         }
         *reinterpret_cast<uint4*>(dst) = ra[i];
@@ -442,6 +445,7 @@ static hipError_t raise_cfg() {
 hipError_t prepare_gemm(int dtype) {
   if (dtype != TSD_BF16) return hipSuccess;
   hipError_t e;
+  if ((e = prepare_gemm_wide()) != hipSuccess) return e;
   if ((e = raise_cfg<bf16, A_TOK, EP_STORE>()) != hipSuccess) return e;
   if ((e = raise_cfg<bf16, A_NORM, EP_QKV>()) != hipSuccess) return e;
   if ((e = raise_cfg<bf16, A_ACT, EP_RESID>()) != hipSuccess) return e;
@@ -466,6 +470,7 @@ static hipError_t launch_t(int amode, int epi, const GemmP& p, hipStream_t st) {
 int gemm_variant(int dtype, int amode, int epi, const GemmP& p) {
   if (p.allow_skinny && skinny_applicable(dtype, amode, epi, p)) return 16;
   if (dtype != TSD_BF16) return 64;
+  if (const int bm = gemm_wide_bm(dtype, amode, epi, p)) return 2000 + bm;
   if (gemm_row_tile(TSD_BF16, p.M, p.N, p.force_bm) == 128) return 128;
   return (amode == A_ACT && gemm_split(p)) ? 464 : 64;
 }
@@ -473,6 +478,7 @@ int gemm_variant(int dtype, int amode, int epi, const GemmP& p) {
 hipError_t launch_gemm(int dtype, int amode, int epi, const GemmP& p, hipStream_t st) {
   if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
   if (p.allow_skinny && skinny_applicable(dtype, amode, epi, p)) return launch_gemm_skinny(amode, epi, p, st);
+  if (const int bm = gemm_wide_bm(dtype, amode, epi, p)) return launch_gemm_wide(amode, epi, bm, p, st);
   return dtype == TSD_BF16 ? launch_t<bf16>(amode, epi, p, st) : launch_t<float>(amode, epi, p, st);
 }
 

@@ -92,8 +92,12 @@ struct tsd_ctx {
   float alpha_override;
   std::vector<int> host_pt;
   // captured launch sequences of tsd_round / tsd_target_step (rebuilt when anything they bake in changes)
-  hipGraphExec_t graph_round[17] = {}, graph_step = nullptr;  // one round graph per number of positions
+  // one round graph per number of positions and per size class of the active list (the launches of a graph are
+  // sized, and their kernels chosen, for a fixed number of series; the device-side count caps the work below that)
+  hipGraphExec_t graph_round[17][8] = {}, graph_step = nullptr;
   bool capturing = false;  // a graph capture of this handle's launches is in progress
+  int capture_rows = 0;    // series the launches being captured are sized for
+  int seq_floor = 0;       // deliveries of the counts up to this launch number describe an earlier decode
   int k_round = 0;  // positions the next round proposes: min(K, most patches any active series still needs)
   int need_lb = 0;  // lower bound on the most patches any series still needs (0 = unknown)
   // measurement tap: event pairs around every launch of one kernel family
@@ -168,7 +172,7 @@ int check_config(const tsd_config* c, std::string& why) {
   if (!(c->fallback_r >= 0.f) || c->fallback_r > c->sigma_p) return bad("fallback_r must lie in [0, sigma_p]");
   if (c->flags & ~(TSD_FLAG_SCRAMBLE_PAGES | TSD_FLAG_NO_TEMPERING | TSD_FLAG_NO_GRAPH | TSD_FLAG_NO_COMPACT | TSD_FLAG_NO_SKINNY | TSD_FLAG_SAMPLE_PROPOSALS |
                    TSD_FLAG_NAIVE_VERIFY | TSD_FLAG_THRESHOLD_RULE | TSD_FLAG_BATCH_SYNC | TSD_FLAG_NO_PINNED_COUNTS |
-                   TSD_FLAG_NO_FUSED_DRAFT | TSD_FLAG_FUSED_DRAFT))
+                   TSD_FLAG_NO_FUSED_DRAFT | TSD_FLAG_FUSED_DRAFT | TSD_FLAG_NO_WIDE_GEMM))
     return bad("unknown flag bits");
   if ((c->flags & TSD_FLAG_NO_FUSED_DRAFT) && (c->flags & TSD_FLAG_FUSED_DRAFT))
     return bad("TSD_FLAG_FUSED_DRAFT and TSD_FLAG_NO_FUSED_DRAFT exclude each other");
@@ -411,6 +415,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
   GemmP g;
   std::memset(&g, 0, sizeof(g));
   g.allow_skinny = ctx->skinny;
+  g.no_wide = (c.flags & TSD_FLAG_NO_WIDE_GEMM) ? 1 : 0;
   g.M = M;
   g.nq = ps.nq;
   // patch embedding
@@ -433,6 +438,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     GemmP q;
     std::memset(&q, 0, sizeof(q));
     q.allow_skinny = ctx->skinny;
+    q.no_wide = (c.flags & TSD_FLAG_NO_WIDE_GEMM) ? 1 : 0;
     q.M = M;
     q.nq = ps.nq;
     q.N = 3 * D;
@@ -483,6 +489,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     GemmP o;
     std::memset(&o, 0, sizeof(o));
     o.allow_skinny = ctx->skinny;
+    o.no_wide = (c.flags & TSD_FLAG_NO_WIDE_GEMM) ? 1 : 0;
     o.M = M;
     o.nq = ps.nq;
     o.n_dev = ps.n_dev;
@@ -546,6 +553,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     GemmP f1;
     std::memset(&f1, 0, sizeof(f1));
     f1.allow_skinny = ctx->skinny;
+    f1.no_wide = (c.flags & TSD_FLAG_NO_WIDE_GEMM) ? 1 : 0;
     f1.M = M;
     f1.nq = ps.nq;
     f1.n_dev = ps.n_dev;
@@ -559,6 +567,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     GemmP f2;
     std::memset(&f2, 0, sizeof(f2));
     f2.allow_skinny = ctx->skinny;
+    f2.no_wide = (c.flags & TSD_FLAG_NO_WIDE_GEMM) ? 1 : 0;
     f2.M = M;
     f2.nq = ps.nq;
     f2.n_dev = ps.n_dev;
@@ -575,6 +584,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     GemmP h;
     std::memset(&h, 0, sizeof(h));
     h.allow_skinny = ctx->skinny;
+    h.no_wide = (c.flags & TSD_FLAG_NO_WIDE_GEMM) ? 1 : 0;
     h.M = M;
     h.nq = ps.nq;
     h.N = P;
@@ -615,7 +625,7 @@ bool device_counts(const tsd_ctx* ctx) {
 // (a fixed address, so captured launch sequences may contain them), and tsd_num_active copies it over the list the
 // passes read when it takes delivery of the matching count.
 Cover cover(const tsd_ctx* ctx) {
-  if (ctx->capturing && device_counts(ctx)) return Cover{ctx->act_list, ctx->B, ctx->count_out};
+  if (ctx->capturing && device_counts(ctx)) return Cover{ctx->act_list, ctx->capture_rows, ctx->count_out};
   if (ctx->n_act >= 0 && ctx->n_act < ctx->B) return Cover{ctx->act_list, ctx->n_act, device_counts(ctx) ? ctx->count_out : nullptr};
   return Cover{nullptr, ctx->B, nullptr};
 }
@@ -623,15 +633,45 @@ Cover cover(const tsd_ctx* ctx) {
 int* compact_target(const tsd_ctx* ctx) { return device_counts(ctx) ? ctx->act_list : ctx->act_list_next; }
 
 void drop_graphs(tsd_ctx* ctx) {
-  for (hipGraphExec_t& g : ctx->graph_round)
-    if (g) {
-      (void)hipGraphExecDestroy(g);
-      g = nullptr;
-    }
+  for (auto& row : ctx->graph_round)
+    for (hipGraphExec_t& g : row)
+      if (g) {
+        (void)hipGraphExecDestroy(g);
+        g = nullptr;
+      }
   if (ctx->graph_step) {
     (void)hipGraphExecDestroy(ctx->graph_step);
     ctx->graph_step = nullptr;
   }
+}
+
+// Size classes of the active list for graph replay: the launches of a captured round are sized for class_rows(i)
+// series, the smallest class that still holds every series the host knows to be active.  (The kernels a launch
+// picks give the same bits whatever the class, so the class only decides how much of the chip a late round wastes.)
+constexpr int kSizeClasses = 8;
+int class_rows(const tsd_ctx* ctx, int i) {
+  static const int num[kSizeClasses] = {32, 24, 16, 12, 8, 4, 2, 1};  // 32nds of the batch
+  return std::max(1, (int)(((long)ctx->B * num[i] + 31) / 32));
+}
+int size_class(const tsd_ctx* ctx) {
+  const int n = (ctx->n_act >= 0 && ctx->n_act < ctx->B) ? ctx->n_act : ctx->B;
+  int i = 0;
+  while (i + 1 < kSizeClasses && class_rows(ctx, i + 1) >= n) ++i;
+  return i;
+}
+
+// A look at the pinned count words without waiting: if a compaction of the current decode has delivered since the
+// last look, the host's upper bounds on the active series and on the patches still needed follow it.  Counts only
+// fall during a decode, so a delivery that is not the latest is still a valid bound.
+void peek_counts(tsd_ctx* ctx) {
+  if (!ctx->host_counts || !ctx->seq_ready || !device_counts(ctx)) return;
+  const int s1 = __atomic_load_n(&ctx->host_counts[2], __ATOMIC_ACQUIRE);
+  if (s1 <= ctx->seq_floor) return;
+  const int c0 = __atomic_load_n(&ctx->host_counts[0], __ATOMIC_RELAXED), c1 = __atomic_load_n(&ctx->host_counts[1], __ATOMIC_RELAXED);
+  if (__atomic_load_n(&ctx->host_counts[2], __ATOMIC_ACQUIRE) != s1) return;  // a delivery in progress: next time
+  if (c0 < 0 || c0 > ctx->B || c1 < 0) return;
+  if (ctx->n_act < 0 || c0 < ctx->n_act) ctx->n_act = c0;
+  if (c1 >= 1 && (ctx->k_round < 1 || c1 < ctx->k_round)) ctx->k_round = c1;
 }
 
 // Runs `body` (a sequence of kernel launches on `st`) through a HIP graph: captured on first use,
@@ -955,6 +995,7 @@ int tsd_prefill(tsd_ctx* ctx, const float* series_dev, int32_t B, int32_t n_ctx_
   hipStream_t st = (hipStream_t)stream;
   ctx->prefilled = false;
   ctx->n_act = -1;
+  ctx->seq_floor = ctx->seq_launched;
   ctx->compact_pending = false;
   ctx->k_round = 0;
   ctx->need_lb = T;  // every series needs all T patches
@@ -1048,6 +1089,7 @@ int tsd_refill(tsd_ctx* ctx, const int32_t* slots_host, int32_t n, const float* 
       if ((rc = run_pass(ctx, ps, st))) return rc;
     }
   ctx->n_act = -1;  // the active list is stale until the next tsd_num_active
+  ctx->seq_floor = ctx->seq_launched;
   ctx->compact_pending = false;
   ctx->k_round = 0;
   ctx->need_lb = 0;
@@ -1062,6 +1104,7 @@ int tsd_reset_decode(tsd_ctx* ctx, void* stream) {
               ctx->count_out, ctx->B, ctx->T};
   HIP_TRY(ctx, launch_reset(pp, (hipStream_t)stream));
   ctx->n_act = -1;  // every series is active again
+  ctx->seq_floor = ctx->seq_launched;
   ctx->compact_pending = false;
   ctx->k_round = 0;
   ctx->need_lb = ctx->T;  // every series needs all T patches again
@@ -1254,7 +1297,10 @@ int tsd_round(tsd_ctx* ctx, void* stream) {
   // launch, copy back and wait for: the caller's next tsd_num_active only watches the host words.
   const bool deliver = ctx->host_counts && ctx->seq_ready;
   const int need_before = ctx->need_lb;  // a round commits at most K + 1 patches per series
-  rc = run_graphed(ctx, &ctx->graph_round[round_positions(ctx)], (hipStream_t)stream, [&]() {
+  if (!(ctx->cfg.flags & TSD_FLAG_NO_COMPACT)) peek_counts(ctx);
+  const int cls = device_counts(ctx) ? size_class(ctx) : 0;
+  ctx->capture_rows = class_rows(ctx, cls);
+  rc = run_graphed(ctx, &ctx->graph_round[round_positions(ctx)][cls], (hipStream_t)stream, [&]() {
     int r;
     if ((r = tsd_draft_propose(ctx, stream))) return r;
     if ((r = tsd_target_verify(ctx, stream))) return r;
@@ -1505,7 +1551,9 @@ int tsd_profile_launches(tsd_ctx* ctx, tsd_launch_rec* out_host, int32_t max_rec
 
 int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_dev, const void* Wt_dev, void* C_dev,
                    void* stream) {
-  if (variant < 0 || variant > 3) return fail(nullptr, TSD_E_INVALID_ARG, "variant must be 0, 1, 2 or 3");
+  const int no_wide = (variant & 8) ? 1 : 0;  // + 8: never the wide-tile kernels
+  variant &= ~8;
+  if (variant < 0 || variant > 3) return fail(nullptr, TSD_E_INVALID_ARG, "variant must be 0, 1, 2 or 3 (+ 8)");
   if (variant == 3 && dtype != TSD_BF16) return fail(nullptr, TSD_E_INVALID_ARG, "variant 3 is bf16 only");
   if (dtype != TSD_F32 && dtype != TSD_BF16) return fail(nullptr, TSD_E_INVALID_ARG, "dtype must be TSD_F32 or TSD_BF16");
   if (M < 1 || N < 4 || K < 8 || (K % 8) || (N % 4)) return fail(nullptr, TSD_E_INVALID_ARG, "need M >= 1, N a multiple of 4, K a multiple of 8");
@@ -1518,6 +1566,7 @@ int tsd_bench_gemm(int dtype, int variant, int M, int N, int K, const void* A_de
   GemmP g;
   std::memset(&g, 0, sizeof(g));
   g.allow_skinny = 1;  // products of at most 32 rows take the skinny kernel, as in a small-batch handle
+  g.no_wide = no_wide;
   g.M = M;
   g.N = N;
   g.K = K;

@@ -81,6 +81,7 @@ struct GemmP {
   int n_mtiles;          // entries of tile_map
   int force_bm;          // row-tile size the map was built for (0 = pick by problem size)
   int allow_skinny;      // the handle runs its <= 32-row passes through the skinny kernel
+  int no_wide;           // never pick the direct-to-LDS wide-tile kernels (gemm_wide.hip)
   // EP_HEAD
   float* out;
   long out_stride_b;
@@ -111,7 +112,12 @@ hipError_t prepare_gemm(int dtype);
 bool skinny_applicable(int dtype, int amode, int epi, const GemmP& p);
 hipError_t launch_gemm_skinny(int amode, int epi, const GemmP& p, hipStream_t st);
 int gemm_row_tile(int dtype, int M, int N, int force_bm);
-// which kernel launch_gemm picks for this product: 16 = skinny, 64 / 128 = tile size, 464 = 64 x 64 tiles with K split over four wavefront groups
+// wide-tile kernels (gemm_wide.hip): row-tile size for this product (256 or 128), or 0 for the register-staged kernels
+int gemm_wide_bm(int dtype, int amode, int epi, const GemmP& p);
+hipError_t launch_gemm_wide(int amode, int epi, int bm, const GemmP& p, hipStream_t st);
+hipError_t prepare_gemm_wide();
+// which kernel launch_gemm picks for this product: 16 = skinny, 64 / 128 = tile size, 464 = 64 x 64 tiles with K split over four wavefront groups,
+// 2256 / 2128 = the wide-tile kernels with 256 / 128-row tiles
 int gemm_variant(int dtype, int amode, int epi, const GemmP& p);
 // s_max: upper bound on (position of the pass's last token) + 1 over all series; sizes the score buffer.
 hipError_t launch_attention(int dtype, const AttnP& p, int s_max, hipStream_t st);

@@ -55,7 +55,7 @@ def test_workspace_and_weight_counts():
     ("K", 0, "K must"), ("K", 17, "K must"), ("patch", 50, "patch"), ("dtype", 3, "dtype"),
     ("page_tokens", 12, "page_tokens"), ("sigma_p", 0.0, "sigma"), ("sigma_q", float("nan"), "sigma"),
     ("fallback_r", -0.1, "fallback_r"), ("fallback_r", 1e3, "fallback_r"), ("fallback_r", float("nan"), "fallback_r"), ("max_tokens", 5, "max_tokens"), ("max_batch", 0, "max_batch"),
-    ("flags", 4096, "flag"),
+    ("flags", 8192, "flag"),
     ("flags", 1024 | 2048, "exclude"),
 ])
 def test_config_validation(field, value, fragment):
