@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--fused-draft", choices=["auto", "on", "off"], default="auto",
                     help="the draft phase as one launch: where the library picks it (auto), wherever supported (on), never (off)")
     ap.add_argument("--no-wide", action="store_true", help="A/B: never the wide-tile direct-to-LDS GEMM kernels (same bits)")
+    ap.add_argument("--drain-every", type=int, default=0,
+                    help="wait for the stream after this many target-only steps (for runs under a counter-collecting profiler, "
+                         "which stalls when thousands of launches are queued without a host wait)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-workers", type=int, default=0, help="oracle worker processes (default: the CPUs this process may use, at most 16)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="the oracle keeps taking series until about this much wall time has passed")
@@ -50,15 +53,25 @@ def parse():
     return ap.parse_args()
 
 
+def log(msg):
+    """Progress on stderr (the JSON line on stdout stays alone): long runs under a profiler show where they are."""
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
 def decode_spec(sess):
     sess.reset_decode()
     return sess.run_rounds()[0]   # rounds until every series has its horizon (the loop lives in the library)
 
 
+DRAIN_EVERY = 0   # --drain-every: wait for the stream after this many target-only steps (0: never)
+
+
 def decode_target_only(sess, T):
     sess.reset_decode()
-    for _ in range(T):
+    for i in range(T):
         sess.target_step()
+        if DRAIN_EVERY and (i + 1) % DRAIN_EVERY == 0:
+            sess.sync()
 
 
 def timed(torch, fn, steps):
@@ -122,6 +135,35 @@ def measured_traffic(workload):
     return out, os.path.relpath(path, ROOT)
 
 
+def attention_bytes_per_decode(sess, c, fused_draft):
+    """The K and V rows every attention launch of one speculative decode has to read, exactly, in launch order: one
+    more decode, round by round, reading every series' committed count before each round.  A series with `len` cached
+    tokens reads len + nq rows of K and of V in a pass of nq new tokens (the verification: nq = positions + 1; the
+    draft, unless it runs as one fused launch: 2 tokens from position len - 1, then one per step), plus its q rows and
+    output rows.  (The library's own tally books every launch at the shortest history a series can have.)
+    Returns a list of (model, bytes) per launch."""
+    import numpy as np
+    es = 2 if c.dtype == "bf16" else 4
+    sess.reset_decode()
+    out = []
+    active = c.batch
+    while active > 0:
+        committed = sess.get_state()["committed"].cpu().numpy().astype(np.int64)
+        on = committed < c.T
+        ln = (c.n_ctx - 1 + committed)[on].astype(np.float64)
+        kr = int(min(c.K, (c.T - committed[on]).max()))
+        n = float(on.sum())
+        t, d = c.target, c.draft
+        if not fused_draft:
+            for i in range(1, kr + 1):          # step 1 reads len + 1 rows (two new tokens from len - 1), step i >= 2 len + i
+                rows, nq = (ln + i).sum(), (2 if i == 1 else 1)
+                out += [(1, d.d_model * es * (2.0 * rows + 2.0 * nq * n))] * d.n_layers
+        out += [(0, t.d_model * es * (2.0 * (ln + kr + 1).sum() + 2.0 * (kr + 1) * n))] * t.n_layers
+        sess.round()
+        active = sess.num_active()
+    return out
+
+
 TILE_LABEL = {128: "128x128", 64: "64x64", 464: "64x64k4", 16: "skinny", 2256: "w256x128", 2128: "w128x128"}
 
 
@@ -134,12 +176,29 @@ def kernel_rooflines(sess, dtype, steps, traffic, cfg=None):
     for _ in range(steps):
         decode_spec(sess)
     sess.profile_end()
+    launches = sess.profile_launches()
+    fused = any(KERNEL_CLASSES[r["kernel_class"]] == "draft" for r in launches)
+    exact = attention_bytes_per_decode(sess, cfg, fused) if cfg is not None else []
+    attn_recs = [r for r in launches if KERNEL_CLASSES[r["kernel_class"]] == "attn"]
+    if exact and len(attn_recs) == steps * len(exact) and all(r["model"] == m for r, (m, _) in zip(attn_recs, exact * steps)):
+        for r, (_, nbytes) in zip(attn_recs, exact * steps):
+            r["floor_work"], r["work"] = r["work"], nbytes    # the rows actually cached, not the shortest possible history
     groups = {}
-    for r in sess.profile_launches():
+    for r in launches:
         name = KERNEL_CLASSES[r["kernel_class"]]
-        key = f"{name}[{TILE_LABEL[r['tile']]}]" if r["tile"] in TILE_LABEL and name not in ("attn", "accept", "route", "draft") else name
-        g = groups.setdefault(key, dict(family=name, n=0, ms=0.0, work=0.0, rows=0))
-        g["n"] += 1; g["ms"] += r["ms"]; g["work"] += r["work"]; g["rows"] += r["M"]
+        if name == "attn":
+            key = "attn[%s]" % {0: "target", 1: "draft"}.get(r["model"], "?")
+        elif r["tile"] in TILE_LABEL and name not in ("accept", "route", "draft"):
+            key = f"{name}[{TILE_LABEL[r['tile']]}]"
+        else:
+            key = name
+        g = groups.setdefault(key, dict(family=name, n=0, ms=0.0, work=0.0, rows=0, floor=0.0, big=None))
+        g["n"] += 1; g["ms"] += r["ms"]; g["work"] += r["work"]; g["rows"] += r["M"]; g["floor"] += r.get("floor_work", 0.0)
+        # the launches of the group's largest shape (full-batch passes), kept apart
+        if g["big"] is None or r["M"] > g["big"]["M"]:
+            g["big"] = dict(M=r["M"], n=0, ms=0.0, work=0.0)
+        if r["M"] == g["big"]["M"]:
+            g["big"]["n"] += 1; g["big"]["ms"] += r["ms"]; g["big"]["work"] += r["work"]
     out = {}
     for key, g in groups.items():
         name, n, ms, work = g["family"], g["n"], g["ms"], g["work"]
@@ -156,11 +215,19 @@ def kernel_rooflines(sess, dtype, steps, traffic, cfg=None):
                 out[key]["achieved_gbs_per_cu"] = wbytes * cfg.K / (ms * 1e-3 / n) / 1e9
             continue
         hbm = name in ("attn", "accept", "route")
+        floor_work = g["floor"] if g["floor"] > 0 else None
         achieved = work / (ms * 1e-3) / (1e9 if hbm else 1e12)
         peak = HBM_PEAK if hbm else PEAK[dtype]
         out[key] = dict(bound="hbm" if hbm else ("mfma" if dtype == "bf16" else "alu"), achieved=achieved, peak=peak,
                         unit="GB/s" if hbm else "TFLOP/s", frac=achieved / peak, launches=n, avg_us=ms * 1e3 / n,
                         total_ms=ms, avg_rows=g["rows"] / n, work_per_launch=work / n, traffic=traffic.get(key))
+        big = g["big"]
+        if big and big["n"] < n:   # the group's largest launches alone (the full-batch passes)
+            a_big = big["work"] / (big["ms"] * 1e-3) / (1e9 if hbm else 1e12)
+            out[key]["largest_launches"] = dict(rows=big["M"], launches=big["n"], avg_us=big["ms"] * 1e3 / big["n"],
+                                                achieved=a_big, frac=a_big / peak)
+        if floor_work is not None:
+            out[key]["achieved_at_shortest_history"] = floor_work / (ms * 1e-3) / 1e9
         if out[key]["traffic"]:
             out[key]["hbm_frac_of_traffic"] = out[key]["traffic"] / (ms * 1e-3 / n) / 1e9 / HBM_PEAK
     return out
@@ -247,21 +314,26 @@ def run_config(torch, tsd, synth, a, name, steps, warmup, fam_steps, flags, case
     if case is None:
         case = synth.Inputs(name, sigma=a.sigma if full else None, B=a.batch if full else None)
     c = case.cfg
+    log(f"{c.name}: weights to the device")
     sess = tsd.session_for(case, flags=flags, fallback_r=a.fallback_r if full else 0.0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     sess.prefill(case.context, c.n_ctx, c.horizon)
     torch.cuda.synchronize()
     prefill_ms = (time.perf_counter() - t0) * 1e3
+    log(f"{c.name}: prefill {prefill_ms:.1f} ms; speculative decodes")
     for _ in range(warmup):
         decode_spec(sess)
     rounds = decode_spec(sess)
     st = sess.get_stats()
     t_spec = timed(torch, lambda: decode_spec(sess), steps)
+    log(f"{c.name}: {t_spec * 1e3:.2f} ms per speculative decode; target-only decodes")
     for _ in range(max(1, warmup // 2)):
         decode_target_only(sess, c.T)
     t_base = timed(torch, lambda: decode_target_only(sess, c.T), steps)
+    log(f"{c.name}: {t_base * 1e3:.2f} ms per target-only decode; phases")
     ph = phase_times(torch, sess, reps=10 if full else 5)
+    log(f"{c.name}: kernel-by-kernel timing pass")
     standard = full and a.sigma is None and a.batch is None and flags == 0 and a.fallback_r == 0.0
     traffic, traffic_src = measured_traffic(c.name if (standard or not full) else None)
     fam = kernel_rooflines(sess, c.dtype, fam_steps, traffic, cfg=c)
@@ -300,6 +372,8 @@ def run_config(torch, tsd, synth, a, name, steps, warmup, fam_steps, flags, case
 
 def main():
     a = parse()
+    global DRAIN_EVERY
+    DRAIN_EVERY = a.drain_every
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -314,6 +388,7 @@ def main():
         except AttributeError:
             avail = os.cpu_count() or 1
         workers = a.cpu_workers or min(16, avail)
+        log(f"oracle on {workers} worker processes, about {a.cpu_seconds:.0f} s")
         cpu = cpu_baseline(case, workers, a.cpu_seconds, sample_proposals=a.sample_proposals, fallback_r=a.fallback_r,
                            single_pass=not a.naive_verify, rule="threshold" if a.threshold_rule else "ratio",
                            batch_sync=a.batch_sync)

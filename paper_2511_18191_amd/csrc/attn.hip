@@ -217,6 +217,9 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
 }
 
 // ---- bf16, head_dim 64: attention on the matrix cores (core in attn_mfma.h) ---------------------
+// MODEL (TSD_TARGET / TSD_DRAFT) changes nothing in the code: the two models' passes run under two kernel names so
+// that a profiler's per-kernel statistics keep the target's large passes apart from the draft's small ones.
+template <int MODEL>
 __global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnP p) {
   __shared__ __attribute__((aligned(16))) bf16 vt[2 * 32 * 64];  // the V rows of two 32-key steps
   const int lane = threadIdx.x;
@@ -283,7 +286,10 @@ hipError_t launch_attention(int dtype, const AttnP& p, int s_max, hipStream_t st
   if (p.B <= 0 || p.nq <= 0 || s_max <= 0) return hipErrorInvalidValue;
   if (p.mfma) {
     if (dtype != TSD_BF16 || p.hd != 64 || p.PT < 8) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(attn_mfma_kernel, dim3((unsigned)(p.B * p.Hh)), dim3(64), 0, st, p);
+    if (p.model == TSD_DRAFT)
+      hipLaunchKernelGGL(attn_mfma_kernel<TSD_DRAFT>, dim3((unsigned)(p.B * p.Hh)), dim3(64), 0, st, p);
+    else
+      hipLaunchKernelGGL(attn_mfma_kernel<TSD_TARGET>, dim3((unsigned)(p.B * p.Hh)), dim3(64), 0, st, p);
     return hipGetLastError();
   }
   const int s_pad = (s_max + 3) & ~3;

@@ -98,6 +98,30 @@ __device__ __forceinline__ void epilogue_pass(const GemmP& p, ReadC read_c4, con
     }
     return;
   }
+  if constexpr (EP == EP_GELU && kBf && BN % 8 == 0 && (64 * (BN / 8)) % NT == 0) {
+    // eight columns per lane: one 16-byte store instead of two 8-byte ones (N is a multiple of 8 here: d_ff is)
+    constexpr int G8 = BN / 8;
+#pragma unroll
+    for (int it = 0; it < 64 * G8 / NT; ++it) {
+      const int g = tid + it * NT;
+      const int row = g / G8, col = (g % G8) * 8;
+      const int gm = m0 + pass * 64 + row, gn = n0 + col;
+      if (gm >= m_lim || gn >= N) continue;
+      const float4 v0 = read_c4(row, col), v1 = read_c4(row, col + 4);
+      const float rs = kNorm ? row_scale[pass * 64 + row] : 1.f;
+      bf16x8 o;
+      o[0] = (bf16)gelu_tanh(v0.x * rs);
+      o[1] = (bf16)gelu_tanh(v0.y * rs);
+      o[2] = (bf16)gelu_tanh(v0.z * rs);
+      o[3] = (bf16)gelu_tanh(v0.w * rs);
+      o[4] = (bf16)gelu_tanh(v1.x * rs);
+      o[5] = (bf16)gelu_tanh(v1.y * rs);
+      o[6] = (bf16)gelu_tanh(v1.z * rs);
+      o[7] = (bf16)gelu_tanh(v1.w * rs);
+      *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(p.Ct) + (long)gm * N + gn) = o;
+    }
+    return;
+  }
 #pragma unroll
   for (int it = 0; it < 64 * GPR / NT; ++it) {
     const int g = tid + it * NT;

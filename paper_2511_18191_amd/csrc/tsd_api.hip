@@ -482,6 +482,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     a.PT = c.page_tokens;
     a.pt_shift = __builtin_ctz(c.page_tokens);
     a.mfma = md.mfma_attn;
+    a.model = ps.which;
     a.scale = 1.0f / std::sqrt((float)md.hd);
     // K and V rows of the shortest history this pass can see (N-1 cached tokens + the new ones), q and output rows
     const double attn_bytes = (double)ps.B * D * ctx->es * (2.0 * (ctx->N - 1 + ps.nq + (ps.base_pos ? ps.pos_off : 1 - ctx->N)) + 2.0 * ps.nq);

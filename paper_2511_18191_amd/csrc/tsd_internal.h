@@ -21,12 +21,15 @@ constexpr float kNormEps = 1e-5f;  // inside the root of the instance normalisat
 constexpr double kRopeBase = 10000.0;
 
 #if defined(__HIPCC__)
-// tanh-GELU, 0.5 z (1 + tanh(u)) with u = sqrt(2/pi) (z + 0.044715 z^3), evaluated as z / (1 + exp(-2u)):
-// one hardware exponential and one reciprocal instead of a library tanh (a few ulp apart, an
-// order of magnitude cheaper in the epilogue of the FFN-up GEMM, where every output element pays it).
+// tanh-GELU, 0.5 z (1 + tanh(u)) with u = sqrt(2/pi) (z + 0.044715 z^3), evaluated as z / (1 + exp(-2u)) with the
+// exponent formed directly in base 2: -2 u log2(e) = z (a + b z^2).  Three multiplications, one fused multiply-add,
+// one addition, one hardware exponential and one reciprocal: every output element of the FFN-up GEMM pays it in the
+// epilogue, where the matrix cores wait, so it is written out to the instruction (a library tanh costs ten times that).
 __device__ __forceinline__ float gelu_tanh(float z) {
-  const float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
-  return z * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
+  constexpr float a = -2.0f * 0.7978845608028654f * 1.4426950408889634f;  // -2 sqrt(2/pi) log2(e)
+  constexpr float b = a * 0.044715f;
+  const float q = z * fmaf(z * z, b, a);
+  return z * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(q));
 }
 #endif
 
@@ -102,6 +105,7 @@ struct AttnP {
   int nq, B, Hh, hd, D, PT;
   int pt_shift;  // log2(PT)
   int mfma;          // bf16, head_dim 64, pages of at least 8 tokens: the matrix-core kernel
+  int model;         // TSD_TARGET / TSD_DRAFT: selects the kernel's name only (profilers then keep the two models apart)
   float scale;
 };
 
