@@ -346,7 +346,11 @@ int gemm_wide_bm(int dtype, int amode, int epi, const GemmP& p) {
   if (dtype != TSD_BF16 || p.no_wide) return 0;
   const bool combo = (amode == A_ACT && (epi == EP_STORE || epi == EP_RESID)) ||
                      (amode == A_NORM && (epi == EP_STORE || epi == EP_GELU || epi == EP_QKV));
-  if (!combo || p.tile_map || p.src_row || p.force_bm || (p.K % 64) || p.K < 192 || (p.N % 128)) return 0;
+  if (!combo || (p.K % 64) || p.K < 192 || (p.N % 128)) return 0;
+  // grouped products of the routed FFN: their tile map was built for force_bm-row tiles, and the 128-row map exists
+  // only where the product already has 1.5 tiles per compute unit
+  if (p.tile_map) return p.force_bm == 128 ? 128 : 0;
+  if (p.src_row || p.force_bm) return 0;
   static const int forced = [] { const char* e = getenv("TSD_WIDE_FORCE"); return e ? atoi(e) : 0; }();  // A/B timing aid
   if (forced == 256 || forced == 128) return forced;
   const long cols = p.N / 128;
@@ -364,7 +368,7 @@ int gemm_wide_bm(int dtype, int amode, int epi, const GemmP& p) {
 
 template <int AM, int EP, typename S>
 static hipError_t launch_wide_t(const GemmP& p, hipStream_t st) {
-  const long tiles = (long)((p.M + S::BM - 1) / S::BM) * (p.N / S::BN);
+  const long tiles = (long)(p.tile_map ? p.n_mtiles : (p.M + S::BM - 1) / S::BM) * (p.N / S::BN);
   const unsigned grid = (unsigned)(((tiles + 7) / 8) * 8);
   constexpr size_t smem = S::SMEM;
   hipLaunchKernelGGL((gemm_wide_kernel<AM, EP, S>), dim3(grid), dim3(S::NT), smem, st, p);

@@ -529,6 +529,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
       f1.w_stride = (long)F * D;
       f1.n_mtiles = n_mtiles;
       f1.force_bm = bm;
+      f1.no_wide = (c.flags & TSD_FLAG_NO_WIDE_GEMM) ? 1 : 0;
       HIP_TRY(ctx, timed_launch(ctx, TSD_K_GELU, 2.0 * slots * D * F, st, [&] { return launch_gemm(c.dtype, A_NORM, EP_GELU, f1, st); },
                                 shape_of(ctx, ps.which, A_NORM, EP_GELU, f1)));
       GemmP f2;
@@ -544,6 +545,7 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
       f2.w_stride = (long)D * F;
       f2.n_mtiles = n_mtiles;
       f2.force_bm = bm;
+      f2.no_wide = (c.flags & TSD_FLAG_NO_WIDE_GEMM) ? 1 : 0;
       HIP_TRY(ctx, timed_launch(ctx, TSD_K_RESID, 2.0 * slots * D * F, st, [&] { return launch_gemm(c.dtype, A_ACT, EP_STORE, f2, st); },
                                 shape_of(ctx, ps.which, A_ACT, EP_STORE, f2)));
       HIP_TRY(ctx, timed_launch(ctx, TSD_K_ROUTE, 4.0 * D * (2.0 * M + slots), st, [&] {

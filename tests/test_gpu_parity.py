@@ -431,6 +431,56 @@ def test_gemm_tap_matches_fp64_product(M, N, K):
         assert err < tol * (K ** 0.5), f"{dt}: {err:.3e}"
 
 
+@pytest.mark.parametrize("M,N,K,variant", [(7168, 1024, 1024, 2), (7168, 1024, 4096, 2), (3585, 4096, 1024, 3), (7000, 3072, 1024, 1),
+                                           (4607, 2304, 768, 1), (7168, 4096, 1024, 0)])
+def test_wide_tile_gemm_same_bits_as_register_staged_and_fp64(M, N, K, variant):
+    # the direct-to-LDS wide-tile kernels (256 x 128 and 128 x 128 tiles; picked by the product's shape) against the
+    # register-staged kernels (bit for bit: same summation order, same row-sum chains) and against a float64
+    # evaluation of the same epilogue on sampled rows (first tile, a middle tile, the ragged last rows)
+    import paper_2511_18191_amd as tsd
+    g = torch.Generator().manual_seed(M + N + K + variant)
+    A = torch.randn(M, K, generator=g).to(torch.bfloat16).cuda()
+    W = (torch.randn(N, K, generator=g) * 0.05).to(torch.bfloat16).cuda()
+    out_dt = torch.bfloat16 if variant == 3 else torch.float32
+    outs = []
+    for no_wide in (0, 8):
+        out = torch.full((M, N), 0.5, dtype=out_dt, device="cuda")     # variant 2 adds the product to what is there
+        tsd.bench_gemm(A, W, out=out, variant=variant + no_wide)
+        torch.cuda.synchronize()
+        outs.append(out.cpu())
+    assert torch.equal(outs[0], outs[1]), f"{(outs[0].float() - outs[1].float()).abs().max():.3e}"
+    rows = torch.cat([torch.arange(0, 130), torch.arange(M // 2 - 3, M // 2 + 70), torch.arange(M - 140, M)])
+    a, w = A.cpu()[rows].double(), W.cpu().double()
+    ref = a @ w.T
+    if variant in (1, 3):
+        ref = ref * torch.rsqrt((a * a).mean(-1, keepdim=True) + 1e-6)
+    if variant == 3:
+        ref = torch.nn.functional.gelu(ref, approximate="tanh")
+    if variant == 2:
+        ref = ref + 0.5
+    err = (outs[0][rows].double() - ref).abs().max() / ref.abs().max()
+    assert err < (6e-3 if variant == 3 else 2e-6 * K ** 0.5), f"{err:.3e}"
+
+
+def test_wide_tile_kernels_change_no_bit_of_a_routed_pass():
+    # cfg 5 at full size: the grouped expert products of the verification pass run on the wide 128 x 128 tiles
+    # (their tile map is built for 128-row tiles there); with TSD_FLAG_NO_WIDE_GEMM they run on the
+    # register-staged tiles.  Both handles must produce the same bits.
+    import paper_2511_18191_amd as tsd
+    case = Case("cfg5")
+    c = case.cfg
+    res = []
+    for flags in (0, tsd.TSD_FLAG_NO_WIDE_GEMM):
+        sess = case.session(flags=flags)
+        sess.prefill(case.context, c.n_ctx, c.horizon)
+        sess.round()
+        io = sess.get_round_io()
+        res.append({k: io[k].cpu() for k in ("X", "mu_p", "n_acc")})
+        sess.close()
+    for k in res[0]:
+        assert torch.equal(res[0][k], res[1][k]), k
+
+
 @pytest.mark.parametrize("name", ["mini3", "mini5"])
 def test_active_list_compaction_changes_nothing(name):
     # after tsd_num_active the passes cover only the listed series; finished series stop costing
