@@ -219,9 +219,14 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnP p, int s_pad) {
 // ---- bf16, head_dim 64: attention on the matrix cores (core in attn_mfma.h) ---------------------
 // MODEL (TSD_TARGET / TSD_DRAFT) changes nothing in the code: the two models' passes run under two kernel names so
 // that a profiler's per-kernel statistics keep the target's large passes apart from the draft's small ones.
+// Three wavefronts per SIMD asked for: the kernel needs 142 registers, which allows three, and told so the compiler
+// schedules for it (66 against 69 us for 1024 series x 16 heads x 66 keys; four costs spills and 76 us).  Two 32-key
+// steps per trip: three (one trip for 65 .. 96 keys instead of a full and an all but empty one) took 174 registers
+// and 72 us.
 template <int MODEL>
-__global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnP p) {
-  __shared__ __attribute__((aligned(16))) bf16 vt[2 * 32 * 64];  // the V rows of two 32-key steps
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(3, 3))) void attn_mfma_kernel(const AttnP p) {
+  constexpr int NST = 2;
+  __shared__ __attribute__((aligned(16))) bf16 vt[NST * 32 * 64];  // the V rows of a trip's 32-key steps
   const int lane = threadIdx.x;
   const int bl = blockIdx.x / p.Hh, h = blockIdx.x % p.Hh;
   const int b = p.act ? p.act[bl] : p.s0 + bl;  // (entries past the active count are stale but valid series)
@@ -235,7 +240,7 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnP p) {
     const int nqt = min(16, p.nq - q0);
     const bf16* qt = q + ((long)bl * p.nq + q0) * p.D + h * 64;
     bf16* ot = out + ((long)bl * p.nq + q0) * p.D + h * 64;
-    attn_tile_mfma(pool, h, p.Hh, p.PT, p.pt_shift, my_page, base + q0, nqt, p.scale,
+    attn_tile_mfma<true, NST>(pool, h, p.Hh, p.PT, p.pt_shift, my_page, base + q0, nqt, p.scale,
                        [&](int r) { return qt + (long)r * p.D; }, [&](int r) { return ot + (long)r * p.D; }, vt);
   }
 }
@@ -286,10 +291,9 @@ hipError_t launch_attention(int dtype, const AttnP& p, int s_max, hipStream_t st
   if (p.B <= 0 || p.nq <= 0 || s_max <= 0) return hipErrorInvalidValue;
   if (p.mfma) {
     if (dtype != TSD_BF16 || p.hd != 64 || p.PT < 8) return hipErrorInvalidValue;
-    if (p.model == TSD_DRAFT)
-      hipLaunchKernelGGL(attn_mfma_kernel<TSD_DRAFT>, dim3((unsigned)(p.B * p.Hh)), dim3(64), 0, st, p);
-    else
-      hipLaunchKernelGGL(attn_mfma_kernel<TSD_TARGET>, dim3((unsigned)(p.B * p.Hh)), dim3(64), 0, st, p);
+    const dim3 grid((unsigned)(p.B * p.Hh)), block(64);
+    if (p.model == TSD_DRAFT) hipLaunchKernelGGL(attn_mfma_kernel<TSD_DRAFT>, grid, block, 0, st, p);
+    else hipLaunchKernelGGL(attn_mfma_kernel<TSD_TARGET>, grid, block, 0, st, p);
     return hipGetLastError();
   }
   const int s_pad = (s_max + 3) & ~3;

@@ -9,7 +9,7 @@
 //   online softmax in fp32 (running max / sum per query, shared by its 4 lanes);
 //   O += P V      four 16x16x32 MFMAs (one per 16 output dims).  Their B operand wants, per lane,
 //                 eight consecutive tokens of one dim: the 32 V rows of a step are fetched with
-//                 coalesced 16-byte loads, parked in LDS (8 KB per wavefront for two steps) and
+//                 coalesced 16-byte loads, parked in LDS (4 KB per wavefront and step) and
 //                 picked up transposed with ds_read_b64_tr_b16.
 // Every K and V byte of the head is read exactly once per tile.
 // (A cache that keeps V transposed, [head][dim][token], makes that operand a plain 16-byte load, but
@@ -24,11 +24,12 @@ namespace tsd {
 // pool: this layer's KV pool; my_page: this lane's entry of the series' page table (lane i holds
 // page i); base: absolute position of the tile's first query; nqt: queries in the tile (1..16);
 // q_row(r) / out_row(r): pointers to the 64 dims of query / output row r of the tile.
-// vt: LDS, bf16 [2][32][64], private to the wavefront.  kOneWave: the workgroup is this one wavefront
+// vt: LDS, bf16 [NST][32][64], private to the wavefront.  NST: 32-key steps per trip (the loads of a trip are issued
+// together; a step past the tile's last key is skipped, loads included).  kOneWave: the workgroup is this one wavefront
 // (then a workgroup barrier orders the tile's LDS traffic); otherwise the wavefront may be one of
 // several that run different trip counts, and only its own LDS operations, which the hardware
 // executes in issue order, are fenced.
-template <bool kOneWave = true, typename QRow, typename ORow>
+template <bool kOneWave = true, int NST = 2, typename QRow, typename ORow>
 __device__ __forceinline__ void attn_tile_mfma(const bf16* pool, int h, int Hh, int PT, int pts, int my_page, int base,
                                                int nqt, float scale, QRow q_row, ORow out_row, bf16* vt) {
   const int lane = threadIdx.x & 63;
@@ -55,11 +56,12 @@ __device__ __forceinline__ void attn_tile_mfma(const bf16* pool, int h, int Hh, 
     }
   };
 
-  for (int s0 = 0; s0 < total; s0 += 64) {  // two 32-key steps per trip, loads issued together
-    bf16x8 kf[2][2][2], vf[2][4];
+  for (int s0 = 0; s0 < total; s0 += 32 * NST) {  // NST 32-key steps per trip, loads issued together
+    bf16x8 kf[NST][2][2], vf[NST][4];
 #pragma unroll
-    for (int st = 0; st < 2; ++st) {
+    for (int st = 0; st < NST; ++st) {
       const int sb = s0 + st * 32;
+      if (sb >= total) break;  // (uniform across the wavefront) nothing is fetched for a step past the last key
 #pragma unroll
       for (int bi = 0; bi < 2; ++bi) {
         // A-operand row qi of block bi holds key sb + 8*(qi/4) + 4*bi + qi%4
@@ -83,10 +85,12 @@ __device__ __forceinline__ void attn_tile_mfma(const bf16* pool, int h, int Hh, 
       // transposed read fall on different banks
       lds_order();  // the previous trip's reads before these writes
 #pragma unroll
-      for (int st = 0; st < 2; ++st)
+      for (int st = 0; st < NST; ++st) {
+        if (s0 + st * 32 >= total) break;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
           *reinterpret_cast<bf16x8*>(vt + (st * 32 + (lane >> 3) + 8 * i) * 64 + (((lane & 7) * 8 + 16 * i) & 63)) = vf[st][i];
+      }
       lds_order();
       // LDS transpose read (ds_read_b64_tr_b16): within 16 lanes, lane i receives element i % 4 of the
       // 8-byte chunks addressed by lanes i / 4, i / 4 + 4, i / 4 + 8, i / 4 + 12.  Lane L of key group g
@@ -95,7 +99,8 @@ __device__ __forceinline__ void attn_tile_mfma(const bf16* pool, int h, int Hh, 
       typedef short short4v __attribute__((ext_vector_type(4)));
       typedef short short8v __attribute__((ext_vector_type(8)));
 #pragma unroll
-      for (int st = 0; st < 2; ++st)
+      for (int st = 0; st < NST; ++st) {
+        if (s0 + st * 32 >= total) break;
 #pragma unroll
         for (int nb = 0; nb < 4; ++nb) {
           short4v hv[2];
@@ -107,9 +112,10 @@ __device__ __forceinline__ void attn_tile_mfma(const bf16* pool, int h, int Hh, 
           const short8v both = __builtin_shufflevector(hv[0], hv[1], 0, 1, 2, 3, 4, 5, 6, 7);
           vf[st][nb] = __builtin_bit_cast(bf16x8, both);
         }
+      }
     }
 #pragma unroll
-    for (int st = 0; st < 2; ++st) {
+    for (int st = 0; st < NST; ++st) {
       const int sb = s0 + st * 32;
       if (sb >= total) break;  // uniform across the wavefront
       f32x4 sc[2];
