@@ -108,6 +108,9 @@ typedef struct {
 
 /* Bytes of device memory tsd_create needs for `cfg` (weights in internal layout, rotary
  * tables, both paged KV pools, page table, per-series state, activation workspace).
+ * One size for one arena: the KV pools and the scratch share an allocation the caller makes
+ * once, instead of a KV size and a scratch size for two; the library carves it (256-byte
+ * aligned parts) and never allocates device memory itself.
  * Host-only; never touches the GPU. */
 int tsd_workspace_bytes(const tsd_config* cfg, size_t* bytes_host);
 

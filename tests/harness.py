@@ -193,3 +193,93 @@ def lockstep(case, sess, max_rounds=None, sigma_q=None, check=True, per_pass=Tru
     rep["rounds"] = rounds
     rep["Y"] = Y
     return rep
+
+
+def free_running_replay(case, sess, subset, max_rounds=None, route_aligned=False):
+    """The decode as the benchmark times it (tsd_round replayed from the library's graphs, the active list compacted,
+    one poll per round, the GPU committing its OWN accepted lengths), audited by the oracle for the series in
+    `subset`: every round, from the history the GPU itself committed, the oracle re-evaluates the draft's K steps and
+    the target's single pass on the GPU's proposals (per-pass tolerance), re-takes every acceptance decision from its
+    own float64 statistic and the same uniform (a different length only inside the decision window), and checks
+    the books (committed count, the patches that went into the forecast).  Returns a report dict."""
+    c = case.cfg
+    B, K, P, T = c.batch, c.K, c.patch, c.T
+    tap = None
+    if route_aligned:
+        import paper_2511_18191_amd as tsd
+        tap = sess.route_tap(tsd.TSD_TARGET)
+    sess.prefill(case.context, c.n_ctx, c.horizon)
+    stats = {b: case.oracle_hist(b) for b in subset}
+    hg = {b: stats[b][0].copy() for b in subset}          # normalised history as the GPU committed it
+    done = {b: 0 for b in subset}
+    rep = dict(rounds=0, pass_rel_q=0.0, pass_rel_p=0.0, tested=0, mismatched=0, near_ties=0, ell_excess=0.0,
+               route_flips=0, route_choices=0, active=[])
+    tol = PASS_TOL[c.dtype]
+    while max_rounds is None or rep["rounds"] < max_rounds:
+        sess.round()
+        n_active = sess.num_active()
+        rep["active"].append(n_active)
+        io = {k: v.cpu().numpy() for k, v in sess.get_round_io().items()}
+        committed = sess.get_state()["committed"].cpu().numpy()
+        ids = tap.cpu().numpy() if tap is not None else None
+        r = rep["rounds"]
+        for b in subset:
+            if done[b] >= T:
+                assert committed[b] == T
+                continue
+            Kc = min(K, T - done[b])
+            Xg, n0 = io["X"][b][:Kc].astype(np.float64), hg[b].shape[0]
+            assert np.array_equal(io["X"][b][:Kc], io["mu_q"][b][:Kc])       # mean propagation: x_i = mu_q^(i)
+            for i in range(Kc):
+                q_ref = orc.forward(case.Wd, c.draft, np.vstack([hg[b], Xg[:i]]))[-1]
+                rep["pass_rel_q"] = max(rep["pass_rel_q"], rel_err(io["mu_q"][b][i], q_ref))
+            info = [] if ids is not None else None
+            p_ref = orc.forward(case.Wt, c.target, np.vstack([hg[b], Xg]), forced_experts=None if ids is None else ids[:, b],
+                                route_info=info)[n0 - 1:]
+            mu_p = io["mu_p"][b][:Kc + 1]
+            rep["pass_rel_p"] = max(rep["pass_rel_p"], rel_err(mu_p, p_ref).max())
+            assert rep["pass_rel_q"] <= tol and rep["pass_rel_p"] <= tol, \
+                f"series {b} round {r}: per-pass error {rep['pass_rel_q']:.3e} / {rep['pass_rel_p']:.3e}"
+            if info is not None:
+                for l, layer in enumerate(info):
+                    for pos in range(n0 - 1, n0 + Kc):
+                        own, rgap = layer[pos]
+                        rep["route_choices"] += 1
+                        if set(own) != set(int(e) for e in ids[l, b, pos]):
+                            rep["route_flips"] += 1
+                            assert rgap < ROUTE_GAP_WINDOW, f"series {b} layer {l} position {pos}: gap {rgap:.3f}"
+            # the decisions, from the oracle's statistic on the GPU's proposals (x_i = mu_q^(i): Eq. 6)
+            ell = np.array([orc.log_ratio(Xg[i], p_ref[i], Xg[i], c.sigma, c.sigma) for i in range(Kc)])
+            logu = np.array([math.log(orc.uniform(case.seed, b, r, i + 1)) for i in range(Kc)])
+            ok = logu <= np.minimum(0.0, ell)
+            n_o = Kc if ok.all() else int(np.argmin(ok))
+            n_g = int(io["n_acc"][b])
+            tested = min(Kc, min(n_o, n_g) + 1)
+            win = ell_window(Xg, p_ref[:Kc], Xg, mu_p[:Kc], c.sigma, P)
+            d = np.abs(io["ell"][b][:tested] - ell[:tested])
+            rep["ell_excess"] = max(rep["ell_excess"], float((d - win[:tested]).max()))
+            assert np.all(d <= win[:tested]), f"series {b} round {r}: |ell_gpu - ell_oracle| {d} beyond {win[:tested]}"
+            np.testing.assert_allclose(io["logu"][b][:tested], logu[:tested], rtol=2e-6, atol=2e-6)
+            gap = np.abs(np.minimum(0.0, ell) - logu)
+            rep["tested"] += tested
+            rep["near_ties"] += int(np.any(gap[:tested] < 1e-4))
+            if n_g != n_o:
+                i = min(n_g, n_o)
+                rep["mismatched"] += 1
+                assert gap[i] < win[i] + 1e-4, (f"series {b} round {r}: accepted {n_g} vs oracle {n_o}; the oracle's margin "
+                                                 f"{gap[i]:.3e} at position {i + 1} is outside the window {win[i] + 1e-4:.3e}")
+            # the books: x_1 .. x_n, then the target's own patch, cut at the horizon
+            blk = np.vstack([Xg[:n_g], mu_p[n_g].astype(np.float64)[None, :]])[:T - done[b]]
+            hg[b] = np.vstack([hg[b], blk])
+            done[b] += blk.shape[0]
+            assert committed[b] == done[b], f"series {b} round {r}: committed {committed[b]} vs {done[b]}"
+        rep["rounds"] += 1
+        if n_active == 0:
+            break
+    fc = sess.get_forecast().cpu().numpy()
+    for b in subset:
+        _, m, s = stats[b]
+        mine = (hg[b][c.n_ctx:].reshape(-1) * s + m)[:min(done[b] * P, c.horizon)]
+        np.testing.assert_allclose(fc[b][:mine.size], mine, rtol=2e-4, atol=2e-4 * max(1.0, abs(m) + s))
+    rep["done"] = done
+    return rep

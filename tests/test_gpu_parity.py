@@ -431,6 +431,28 @@ def test_gemm_tap_matches_fp64_product(M, N, K):
         assert err < tol * (K ** 0.5), f"{dt}: {err:.3e}"
 
 
+@pytest.mark.parametrize("name,subset,max_rounds,aligned", [("cfg2", [0, 101, 255], None, False), ("cfg3", [7, 1023], None, False),
+                                                             ("cfg5", [3], 2, True)])
+def test_full_size_free_running_decode_audited_by_the_oracle(name, subset, max_rounds, aligned):
+    # The benchmark's own launch configuration at full size (rounds replayed from the library's graphs, one graph per
+    # size class of the active list, compacted passes, wide-tile kernels, the GPU committing its own lengths), with
+    # the oracle auditing sampled series round by round from the history the GPU committed: every draft step and
+    # the verification pass within the per-pass tolerance, every decision re-taken in float64 (a different length
+    # only inside the decision window), committed counts and the forecast buffer equal to the audited blocks.
+    from harness import free_running_replay
+    case = Case(name)
+    c = case.cfg
+    sess = case.session()
+    rep = free_running_replay(case, sess, subset, max_rounds=max_rounds, route_aligned=aligned)
+    print(f"{name}: rounds {rep['rounds']} active {rep['active']} per-pass q {rep['pass_rel_q']:.2e} p {rep['pass_rel_p']:.2e} "
+          f"tested {rep['tested']} mismatched {rep['mismatched']} near ties {rep['near_ties']} ell excess {rep['ell_excess']:.2e} "
+          f"route flips {rep['route_flips']}/{rep['route_choices']}")
+    if max_rounds is None:
+        assert rep["active"][-1] == 0 and all(v == c.T for v in rep["done"].values())
+        assert sorted(rep["active"], reverse=True) == rep["active"]
+    sess.close()
+
+
 @pytest.mark.parametrize("M,N,K,variant", [(7168, 1024, 1024, 2), (7168, 1024, 4096, 2), (3585, 4096, 1024, 3), (7000, 3072, 1024, 1),
                                            (4607, 2304, 768, 1), (7168, 4096, 1024, 0)])
 def test_wide_tile_gemm_same_bits_as_register_staged_and_fp64(M, N, K, variant):
