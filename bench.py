@@ -49,7 +49,8 @@ def parse():
     ap.add_argument("--cpu-workers", type=int, default=0, help="oracle worker processes (default: the CPUs this process may use, at most 16)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="the oracle keeps taking series until about this much wall time has passed")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain 256 MiB copy kernel 5 times (known traffic, to scale profiler memory counters)")
+                    help="also run a plain 256 MiB copy kernel 5 times (known traffic, to scale profiler memory counters) and "
+                         "bracket the kernel-by-kernel timing pass with two marker copies of 28672 bytes")
     return ap.parse_args()
 
 
@@ -108,7 +109,7 @@ HBM_PEAK = 8000.0                        # GB/s
 
 
 def library_sources_hash():
-    """Identifies the kernel sources a profile was taken with (profiles/traffic_*.md carry the same value)."""
+    """Identifies the kernel sources a profile was taken with (profiles/traffic_*.txt carry the same value)."""
     h = hashlib.sha256()
     d = os.path.join(ROOT, "paper_2511_18191_amd", "csrc")
     for f in sorted(os.listdir(d)):
@@ -120,15 +121,17 @@ def library_sources_hash():
 
 def measured_traffic(workload):
     """HBM bytes per launch of each kernel family from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of
-    this workload (profiles/traffic_<workload>_bench.md: commands, raw values, copy-kernel scale factors).  Used
+    this workload (profiles/traffic_<workload>_bench.txt: commands, raw values, copy-kernel scale factors).  Used
     only when that summary was taken with the kernel sources as they are now; otherwise no traffic is reported."""
-    path = os.path.join(ROOT, "profiles", f"traffic_{workload}_bench.md")
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}_bench.txt")
     if workload is None or not os.path.exists(path):
         return {}, "no committed counter summary for this workload"
     text = open(path).read()
     m = re.search(r"kernel sources: ([0-9a-f]{16})", text)
     if not m or m.group(1) != library_sources_hash():
         return {}, "the committed counter summary is of other kernel sources"
+    if "## timing pass only" in text:      # the launch mix `achieved` is computed on, where the summary has it apart
+        text = text[text.index("## timing pass only"):]
     out = {}
     for row in re.findall(r"^\| *([a-z]+(?:\[[0-9a-z]+\])?) *\|(?:[^|]*\|){5} *([0-9.]+) *\|", text, flags=re.M):
         out[row[0]] = int(round(float(row[1]) * 1e6))
@@ -164,6 +167,12 @@ def attention_bytes_per_decode(sess, c, fused_draft):
     return out
 
 
+# --copy-calibration: a callable that launches one small copy of a size nothing else uses (28672 bytes: 7 workgroups),
+# before and after the kernel-by-kernel timing pass, so that a profiler's per-dispatch records of exactly that pass
+# (the launch mix `achieved` is computed on) can be told from the rest of the run
+MARK = None
+
+
 TILE_LABEL = {128: "128x128", 64: "64x64", 464: "64x64k4", 16: "skinny", 2256: "w256x128", 2128: "w128x128"}
 
 
@@ -172,10 +181,14 @@ def kernel_rooflines(sess, dtype, steps, traffic, cfg=None):
     every launch during `steps` speculative decodes (kernel-by-kernel launches on the session's stream, every
     launch bracketed by two events) and the algorithmic work they did."""
     from paper_2511_18191_amd.binding import KERNEL_CLASSES
+    if MARK:
+        MARK()
     sess.profile_begin(len(KERNEL_CLASSES))       # every family at once
     for _ in range(steps):
         decode_spec(sess)
     sess.profile_end()
+    if MARK:
+        MARK()
     launches = sess.profile_launches()
     fused = any(KERNEL_CLASSES[r["kernel_class"]] == "draft" for r in launches)
     exact = attention_bytes_per_decode(sess, cfg, fused) if cfg is not None else []
@@ -372,7 +385,7 @@ def run_config(torch, tsd, synth, a, name, steps, warmup, fam_steps, flags, case
 
 def main():
     a = parse()
-    global DRAIN_EVERY
+    global DRAIN_EVERY, MARK
     DRAIN_EVERY = a.drain_every
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -404,6 +417,14 @@ def main():
         torch.cuda.synchronize()
         assert torch.equal(dst[:1024], src[:1024])
         del src, dst
+        m_src = torch.ones(7 * 256 * 4, dtype=torch.float32, device="cuda")
+        m_dst = torch.empty_like(m_src)
+
+        def mark():
+            torch.cuda.synchronize()
+            tsd.bench_copy(m_dst, m_src)
+            torch.cuda.synchronize()
+        MARK = mark
 
     flags = (tsd.TSD_FLAG_SAMPLE_PROPOSALS if a.sample_proposals else 0) | (tsd.TSD_FLAG_NAIVE_VERIFY if a.naive_verify else 0)
     flags |= (tsd.TSD_FLAG_THRESHOLD_RULE if a.threshold_rule else 0) | (tsd.TSD_FLAG_BATCH_SYNC if a.batch_sync else 0)

@@ -27,19 +27,20 @@ __device__ __forceinline__ void store4<bf16>(bf16* dst, float4 v) {
 // kOld: the old residual values of this lane's items were fetched ahead into oldc[].
 // read_c4(row, col): four consecutive elements of row `row` (0..63 of the pass) of the product tile.
 // row_scale / row_pos / row_page are indexed by the row inside the tile (pass * 64 + row).
-template <typename T, int EP, bool kNorm, int BN, int NT, bool kOld, typename ReadC>
+// kBatchQKV: the RoPE epilogue in batches of four groups per lane (below).
+template <typename T, int EP, bool kNorm, int BN, int NT, bool kOld, bool kBatchQKV = (BN == 64), typename ReadC>
 __device__ __forceinline__ void epilogue_pass(const GemmP& p, ReadC read_c4, const float* row_scale, const int* row_pos,
                                               const int* row_page, int m0, int n0, int pass, int m_lim, int N, int tid,
                                               const float4* oldc) {
   constexpr bool kBf = !std::is_same<T, float>::value;
   constexpr int GPR = BN / 4;  // 4-column groups per row
-  if constexpr (EP == EP_QKV && BN == 64) {
+  if constexpr (EP == EP_QKV && kBatchQKV) {
     // RoPE + q / KV-cache write, four 4-column groups per lane at a time: first every read (accumulators and
     // rotary partners from LDS, positions and pages, cos / sin from global memory, clamped for groups outside
     // the product), then the arithmetic, then the stores.  Written as one read-compute-store body per group,
     // each group's global loads wait for the previous group's stores to issue and pay a full round trip.
-    // (64-column tiles only: in the 128 x 128 kernel the extra live registers cost occupancy and 9 % of a
-    //  verification pass at 7168 rows.)
+    // (Not in the register-staged 128 x 128 kernel: there the extra live registers cost occupancy and 9 % of a
+    //  verification pass at 7168 rows.  The wide-tile kernels, which hold no staging registers, take it.)
     constexpr int ITS = 64 * GPR / NT, BATCH = ITS < 4 ? ITS : 4;
     const int D = p.D, hd = p.hd, half = hd >> 1;
 #pragma unroll

@@ -308,7 +308,23 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_wide_kernel(const GemmP p) {
   }
 
   // ---- epilogue, 64 rows at a time through LDS ------------------------------------------------------------------
+  // EP_RESID: the old residual values of a pass are requested one pass ahead (those of pass 0 before the accumulators'
+  // trip through LDS), so that their latency hides behind LDS traffic and the previous pass's stores instead of being
+  // paid once per item (a read that follows a store to the same array cannot be moved up by the compiler).
   auto read_c4 = [&](int row, int col) { return *reinterpret_cast<const float4*>(Cs + row * LDC + col); };
+  constexpr int NPRE = (EP == EP_RESID) ? 64 * (BN / 4) / S::NT : 1;
+  float4 oldc[2][NPRE];
+  auto fetch_old = [&](int pass, float4* dst) {
+    if constexpr (EP == EP_RESID) {
+#pragma unroll
+      for (int it = 0; it < NPRE; ++it) {
+        const int g = tid + it * S::NT;
+        const int gm = min(m0 + pass * 64 + g / (BN / 4), m_lim - 1), gn = n0 + (g % (BN / 4)) * 4;  // (N is a multiple of BN)
+        dst[it] = *reinterpret_cast<const float4*>(p.Cf + (long)gm * N + gn);
+      }
+    }
+  };
+  fetch_old(0, oldc[0]);
 #pragma unroll
   for (int pass = 0; pass < BM / 64; ++pass) {
     __syncthreads();  // the stages (or the previous pass's rows) are no longer read
@@ -326,8 +342,10 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_wide_kernel(const GemmP p) {
           }
       }
     }
+    if (pass + 1 < BM / 64) fetch_old(pass + 1, oldc[(pass + 1) & 1]);
     __syncthreads();
-    epilogue_pass<bf16, EP, kNorm, BN, S::NT, false>(p, read_c4, row_scale, row_pos, row_page, m0, n0, pass, m_lim, N, tid, nullptr);
+    epilogue_pass<bf16, EP, kNorm, BN, S::NT, EP == EP_RESID, true>(p, read_c4, row_scale, row_pos, row_page, m0, n0, pass, m_lim, N,
+                                                                    tid, oldc[pass & 1]);
   }
 }
 
