@@ -27,7 +27,8 @@
 #include "tsd_internal.h"
 
 // Timing experiments (never defined in the library build): bits of TSD_WIDE_PROBE switch pieces of the k loop off
-// to price them; the results are then garbage, every access stays in bounds and every wavefront meets the same barriers.
+// to price them (1 loads, 2 fragment reads, 4 MFMAs, 8 barrier, 16 epilogue arithmetic and stores, 32 the whole epilogue);
+// the results are then garbage, every access stays in bounds and every wavefront meets the same barriers.
 #ifndef TSD_WIDE_PROBE
 #define TSD_WIDE_PROBE 0
 #endif
@@ -324,6 +325,15 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_wide_kernel(const GemmP p) {
       }
     }
   };
+  if constexpr (TSD_WIDE_PROBE & 32) {  // probe: no epilogue at all (the accumulators are still produced)
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) asm volatile("" ::"v"(acc[i][j][r]));
+    return;
+  }
   fetch_old(0, oldc[0]);
 #pragma unroll
   for (int pass = 0; pass < BM / 64; ++pass) {
@@ -344,6 +354,7 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_wide_kernel(const GemmP p) {
     }
     if (pass + 1 < BM / 64) fetch_old(pass + 1, oldc[(pass + 1) & 1]);
     __syncthreads();
+    if constexpr (TSD_WIDE_PROBE & 16) continue;  // probe: the accumulators' trip through LDS, but no epilogue arithmetic or stores
     epilogue_pass<bf16, EP, kNorm, BN, S::NT, EP == EP_RESID, true>(p, read_c4, row_scale, row_pos, row_page, m0, n0, pass, m_lim, N,
                                                                     tid, oldc[pass & 1]);
   }
