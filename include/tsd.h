@@ -240,7 +240,10 @@ int tsd_accept_commit_static(const float* X_dev, const float* mu_q_dev, const fl
 
 /* tsd_draft_propose; tsd_target_verify; tsd_accept_commit(NULL).  On a non-NULL stream that is not
  * being captured by the caller, the launch sequence is captured into a HIP graph on first use and
- * replayed afterwards (same for tsd_target_step); TSD_FLAG_NO_GRAPH switches that off. */
+ * replayed afterwards (same for tsd_target_step); TSD_FLAG_NO_GRAPH switches that off.  Graphs are
+ * kept per number of positions the round runs and per size class of the active list (launches
+ * sized for 1/32 .. 32/32 of the batch); the class is chosen from the last length the host has
+ * seen, looked up without waiting, and every launch is capped by the device-side length. */
 int tsd_round(tsd_ctx* ctx, void* stream);
 
 /* Rounds until no series needs patches any more (or max_rounds rounds have run): the loop
@@ -258,9 +261,13 @@ int tsd_run_rounds(tsd_ctx* ctx, int32_t max_rounds, int32_t* rounds_host, int32
  * pending token, whose output is committed for every active series. */
 int tsd_target_step(tsd_ctx* ctx, void* stream);
 
-/* Number of series that still need patches.  Synchronises `stream`.  Also rebuilds the list of
- * active series; until the next prefill/reset, passes then cover only the listed series (those
- * that finish later stay listed and are masked, so the list stays valid without further calls).
+/* Number of series that still need patches.  Synchronises `stream`.  Passes cover only the series
+ * on the active list, which the last kernel of every round rebuilds on the device together with
+ * its length; this call brings the length to the host.  Launches issued before the next call are
+ * sized from the length the host knows (an older, larger one at worst) and capped by the
+ * device-side one, so a series that finishes in between costs at most workgroups that leave at
+ * once, never a second visit.  Handles whose passes are sized on the host (routed models) keep
+ * reading the list as of this call until the next one.
  * Results are identical with or without it; finished series simply stop costing work.
  * The counts reach the host through a few pinned host words that the compaction kernel writes
  * itself (tsd_round already ends with that kernel), so this call normally launches nothing and
