@@ -17,12 +17,13 @@ def _oracle_forecast(case, s, slot, round0, trace=None):
                              case.seed, slot, round0=round0, trace=trace)
 
 
-@pytest.mark.parametrize("name,slots,sigma", [("mini2_fp32", 3, 0.5), ("cfg1", 4, 0.3)])
-def test_stream_through_refilled_slots_matches_oracle_fp32(name, slots, sigma):
+@pytest.mark.parametrize("name,slots,sigma,min_refill", [("mini2_fp32", 3, 0.5, 1), ("cfg1", 4, 0.3, 1), ("cfg1", 4, 0.3, 3)])
+def test_stream_through_refilled_slots_matches_oracle_fp32(name, slots, sigma, min_refill):
+    # (min_refill > 1: freed slots wait for company before they are refilled, so newcomers start at other rounds)
     case = Case(name, B=11, sigma=sigma)
     c = case.cfg
     sess = case.session(max_batch=slots)
-    out, placement = serve.run_stream(sess, case.context, c.n_ctx, c.horizon, track=True)
+    out, placement = serve.run_stream(sess, case.context, c.n_ctx, c.horizon, track=True, min_refill=min_refill)
     out = out.cpu().numpy()
     assert sorted(p[0] for p in placement[:slots]) == list(range(slots)) and all(p is not None for p in placement)
     assert any(p[1] > 0 for p in placement[slots:])           # later series started at a running round counter
