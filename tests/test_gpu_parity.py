@@ -454,7 +454,10 @@ def test_full_size_free_running_decode_audited_by_the_oracle(name, subset, max_r
 
 
 @pytest.mark.parametrize("M,N,K,variant", [(7168, 1024, 1024, 2), (7168, 1024, 4096, 2), (3585, 4096, 1024, 3), (7000, 3072, 1024, 1),
-                                           (4607, 2304, 768, 1), (7168, 4096, 1024, 0)])
+                                           (4607, 2304, 768, 1), (7168, 4096, 1024, 0),
+                                           # the shortest contraction the wide tiles take (three k-tiles: one steady, two tail),
+                                           # an odd number of k-tiles, a last row tile of one row, a single tile column
+                                           (300, 32768, 192, 1), (8193, 1024, 320, 2), (16385, 512, 2048, 3), (65537, 128, 256, 0), (6999, 1024, 1024, 2)])
 def test_wide_tile_gemm_same_bits_as_register_staged_and_fp64(M, N, K, variant):
     # the direct-to-LDS wide-tile kernels (256 x 128 and 128 x 128 tiles; picked by the product's shape) against the
     # register-staged kernels (bit for bit: same summation order, same row-sum chains) and against a float64
