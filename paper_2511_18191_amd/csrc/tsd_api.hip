@@ -612,9 +612,9 @@ struct Cover {
   int n;
   const int* n_dev;  // launches being captured into a graph: the count is read on the device at replay
 };
-// Dense models can replay one graph however many series are still active: the launches are sized
-// for the whole batch and every kernel caps its work by the device-side count that
-// tsd_num_active maintains (the routed FFN sizes its expert runs on the host, so it cannot).
+// Dense models can replay a graph however many series are still active: its launches are sized for
+// a size class of the active list (see class_rows) and every kernel caps its work by the device-side
+// count that the compaction maintains (the routed FFN sizes its expert runs on the host, so it cannot).
 bool device_counts(const tsd_ctx* ctx) {
   return !(ctx->cfg.flags & TSD_FLAG_NO_COMPACT) && ctx->cfg.target.n_experts == 0 && ctx->cfg.draft.n_experts == 0 &&
          ctx->B > 1;
