@@ -346,6 +346,28 @@ def run_config(torch, tsd, synth, a, name, steps, warmup, fam_steps, flags, case
     t_base = timed(torch, lambda: decode_target_only(sess, c.T), steps)
     log(f"{c.name}: {t_base * 1e3:.2f} ms per target-only decode; phases")
     ph = phase_times(torch, sess, reps=10 if full else 5)
+    # the method's own choice of block size (Proposition "Marginal-gain condition for K"): Eq. 8 maximised over the
+    # measured cost table c(K), v(K) for K up to the configured one, and a decode at that K
+    alpha = st["accepted"] / max(1, st["tested"])
+    planned = None
+    if c.K > 1 and flags == 0:
+        from paper_2511_18191_amd import planner
+        log(f"{c.name}: cost table for K = 1..{c.K}")
+        costs = planner.cost_table(sess, c.K, reps=4)
+        k_star = planner.plan(alpha, costs, min(2, c.K))["k_table"]
+        planned = {"K": k_star, "rule": "argmax over K <= configured K of E[L](acceptance, K) / (c(K) K + v(K)), measured cost table",
+                   "v_of_K": {str(k): round(costs[k]["v"], 3) for k in costs}, "c_of_K": {str(k): round(costs[k]["c"], 4) for k in costs}}
+        if k_star != c.K:
+            sess.set_block_size(k_star)
+            decode_spec(sess)
+            st_k = sess.get_stats()
+            t_k = timed(torch, lambda: decode_spec(sess), max(2, steps // 2))
+            sess.set_block_size(c.K)
+            planned.update(value=c.batch * c.horizon / t_k, ms_per_step=t_k * 1e3, speedup_vs_target_only=t_base / t_k,
+                           acceptance=st_k["accepted"] / max(1, st_k["tested"]),
+                           mean_committed_per_round=st_k["committed"] / max(1, st_k["rounds"]))
+        else:
+            planned.update(value=c.batch * c.horizon / t_spec, ms_per_step=t_spec * 1e3, speedup_vs_target_only=t_base / t_spec)
     log(f"{c.name}: kernel-by-kernel timing pass")
     standard = full and a.sigma is None and a.batch is None and flags == 0 and a.fallback_r == 0.0
     traffic, traffic_src = measured_traffic(c.name if (standard or not full) else None)
@@ -354,7 +376,6 @@ def run_config(torch, tsd, synth, a, name, steps, warmup, fam_steps, flags, case
     # the one-launch draft kernel is listed with its own bound; the headline roofline goes to the largest
     # family that one of the published peaks (MFMA, HBM) bounds
     dominant = max((k for k in fam if fam[k]["bound"] != "cu_stream"), key=lambda k: fam[k]["total_ms"])
-    alpha = st["accepted"] / max(1, st["tested"])
     mean_L = st["committed"] / max(1, st["rounds"])
     cc = ph["draft"] / c.K / ph["target_step"]
     v = (ph["verify"] + ph["accept"]) / ph["target_step"]
@@ -374,6 +395,7 @@ def run_config(torch, tsd, synth, a, name, steps, warmup, fam_steps, flags, case
         # figure above also pays for rounds in which only the slowest series are still decoding)
         "patch_rate_speedup": mean_L * ph["target_step"] / (ph["draft"] + ph["verify"] + ph["accept"]),
         "near_ties": st["near_ties"],
+        "planned_block_size": planned,
         "roofline": dict({k: v_ for k, v_ in fam[dominant].items()
                           if k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "hbm_frac_of_traffic")},
                          kernel=dominant, avg_us=fam[dominant]["avg_us"], launches=fam[dominant]["launches"],
@@ -449,7 +471,8 @@ def main():
     }
     out.update({k: head[k] for k in ("speedup_vs_target_only", "target_only_steps_per_s", "target_only_ms", "prefill_ms",
                                      "rounds_per_decode", "acceptance", "mean_committed_per_round", "phase_ms", "c", "v",
-                                     "predicted_speedup_eq8", "near_ties", "patch_rate_speedup", "roofline", "kernel_families")})
+                                     "predicted_speedup_eq8", "near_ties", "patch_rate_speedup", "planned_block_size", "roofline",
+                                     "kernel_families")})
     out["measured_peaks"] = peaks
     if cpu is not None:
         out["cpu_baseline"] = cpu
@@ -457,7 +480,7 @@ def main():
         # the five configurations, each in the deployed scheme (no ablation flags), fewer repetitions
         short = ("workload", "dtype", "value", "ms_per_step", "steps", "speedup_vs_target_only", "target_only_ms", "rounds_per_decode",
                  "acceptance", "mean_committed_per_round", "phase_ms", "c", "v", "predicted_speedup_eq8", "patch_rate_speedup",
-                 "roofline")
+                 "planned_block_size", "roofline")
         block = {}
         for name in ALL_CONFIGS:
             if name == a.config and flags == 0 and a.sigma is None and a.batch is None and a.fallback_r == 0.0:
