@@ -271,6 +271,60 @@ def measured_peaks(torch, tsd):
     return {"mfma_bf16_tflops": mfma, "hbm_copy_gbs": copy}
 
 
+def batch_level_prediction(torch, sess, case, c, t_base):
+    """The whole-batch decode time the capped-geometric law predicts once the batch's lock-step is modelled
+    (law.simulate_batch_rounds: every series draws its blocks with its own measured acceptance, the batch runs until
+    the slowest is done), priced with measured round times: one round (graph replay and the delivery of the count) from
+    the post-prefill state of a batch of n series, for n at the size classes of the active list, at the configured
+    number of positions and at one, linear in between.  Leaves the handle prefilled with the whole batch again."""
+    import numpy as np
+    from paper_2511_18191_amd import law
+    per = sess.get_series_stats().cpu().numpy().astype(np.float64)            # of the last decode: rounds, tested, accepted, ...
+    pooled = per[:, 2].sum() / max(1.0, per[:, 1].sum())
+    raw = np.where(per[:, 1] > 0, per[:, 2] / np.maximum(per[:, 1], 1.0), pooled)   # each series' own accepted / tested
+    sizes = sorted({max(1, (c.batch * f + 31) // 32) for f in (32, 24, 16, 12, 8, 4, 2, 1)}, reverse=True)
+    ks = sorted({c.K, 1})
+    cost = {}
+    for n in sizes:
+        sess.prefill(case.context[:n], c.n_ctx, c.horizon)
+        for k in ks:
+            sess.set_block_size(k)
+            ts = []
+            for _ in range(4):
+                sess.reset_decode()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                sess.round()
+                sess.num_active()
+                torch.cuda.synchronize()
+                ts.append(time.perf_counter() - t0)
+            cost[(n, k)] = min(ts[1:])
+        sess.set_block_size(c.K)
+    sess.prefill(case.context, c.n_ctx, c.horizon)
+    ns = np.array(sorted(sizes), dtype=np.float64)
+    at = {k: np.array([cost[(int(n), k)] for n in ns]) for k in ks}
+
+    def price(n, k):
+        hi = np.interp(n, ns, at[c.K])
+        if c.K == 1:
+            return hi
+        lo = np.interp(n, ns, at[1])
+        return lo + (hi - lo) * (k - 1) / (c.K - 1)
+    out = {"model": "capped-geometric blocks per series, the batch runs until its slowest series is done (100 Monte Carlo batches); rounds "
+                    "priced with measured round times by active count and positions.  Two acceptance models bracket a real batch: "
+                    "every series at the pooled measured rate (the law's i.i.d. assumption), and every series at its own measured "
+                    "accepted / tested (which adds the sampling noise of a dozen tests per series to the real spread)",
+           "round_ms_by_active": {str(n): round(cost[(n, c.K)] * 1e3, 4) for n in sizes},
+           "acceptance_spread_5_50_95": [float(np.quantile(raw, q)) for q in (0.05, 0.5, 0.95)]}
+    for name, alpha_b in (("pooled_acceptance", np.full(c.batch, pooled)), ("per_series_acceptance", raw)):
+        act, pos = law.simulate_batch_rounds(alpha_b, c.K, c.T, reps=100, seed=0)
+        on = act > 0
+        t = np.where(on, price(act.astype(np.float64), pos.astype(np.float64)), 0.0).sum(axis=1)
+        out[name] = {"predicted_rounds": float(on.sum(axis=1).mean()), "predicted_ms": float(t.mean() * 1e3),
+                     "predicted_speedup_vs_target_only": float(t_base / t.mean())}
+    return out
+
+
 # ---- the CPU oracle on a bounded sample: runs BEFORE anything touches the GPU (forked workers) -------------
 _ORC = {}
 
@@ -368,6 +422,12 @@ def run_config(torch, tsd, synth, a, name, steps, warmup, fam_steps, flags, case
                            mean_committed_per_round=st_k["committed"] / max(1, st_k["rounds"]))
         else:
             planned.update(value=c.batch * c.horizon / t_spec, ms_per_step=t_spec * 1e3, speedup_vs_target_only=t_base / t_spec)
+    batch_pred = None
+    if flags == 0:
+        log(f"{c.name}: round times by active count, batch-level prediction")
+        decode_spec(sess)                                                     # per-series counters of a whole decode at the configured K
+        batch_pred = batch_level_prediction(torch, sess, case, c, t_base)
+        batch_pred.update(measured_ms=t_spec * 1e3, measured_rounds=rounds, measured_speedup_vs_target_only=t_base / t_spec)
     log(f"{c.name}: kernel-by-kernel timing pass")
     standard = full and a.sigma is None and a.batch is None and flags == 0 and a.fallback_r == 0.0
     traffic, traffic_src = measured_traffic(c.name if (standard or not full) else None)
@@ -396,6 +456,7 @@ def run_config(torch, tsd, synth, a, name, steps, warmup, fam_steps, flags, case
         "patch_rate_speedup": mean_L * ph["target_step"] / (ph["draft"] + ph["verify"] + ph["accept"]),
         "near_ties": st["near_ties"],
         "planned_block_size": planned,
+        "batch_level_prediction": batch_pred,
         "roofline": dict({k: v_ for k, v_ in fam[dominant].items()
                           if k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "hbm_frac_of_traffic")},
                          kernel=dominant, avg_us=fam[dominant]["avg_us"], launches=fam[dominant]["launches"],
@@ -471,8 +532,8 @@ def main():
     }
     out.update({k: head[k] for k in ("speedup_vs_target_only", "target_only_steps_per_s", "target_only_ms", "prefill_ms",
                                      "rounds_per_decode", "acceptance", "mean_committed_per_round", "phase_ms", "c", "v",
-                                     "predicted_speedup_eq8", "near_ties", "patch_rate_speedup", "planned_block_size", "roofline",
-                                     "kernel_families")})
+                                     "predicted_speedup_eq8", "near_ties", "patch_rate_speedup", "planned_block_size",
+                                     "batch_level_prediction", "roofline", "kernel_families")})
     out["measured_peaks"] = peaks
     if cpu is not None:
         out["cpu_baseline"] = cpu
@@ -480,7 +541,7 @@ def main():
         # the five configurations, each in the deployed scheme (no ablation flags), fewer repetitions
         short = ("workload", "dtype", "value", "ms_per_step", "steps", "speedup_vs_target_only", "target_only_ms", "rounds_per_decode",
                  "acceptance", "mean_committed_per_round", "phase_ms", "c", "v", "predicted_speedup_eq8", "patch_rate_speedup",
-                 "planned_block_size", "roofline")
+                 "planned_block_size", "batch_level_prediction", "roofline")
         block = {}
         for name in ALL_CONFIGS:
             if name == a.config and flags == 0 and a.sigma is None and a.batch is None and a.fallback_r == 0.0:
