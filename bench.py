@@ -316,12 +316,19 @@ def batch_level_prediction(torch, sess, case, c, t_base):
                     "accepted / tested (which adds the sampling noise of a dozen tests per series to the real spread)",
            "round_ms_by_active": {str(n): round(cost[(n, c.K)] * 1e3, 4) for n in sizes},
            "acceptance_spread_5_50_95": [float(np.quantile(raw, q)) for q in (0.05, 0.5, 0.95)]}
-    for name, alpha_b in (("pooled_acceptance", np.full(c.batch, pooled)), ("per_series_acceptance", raw)):
-        act, pos = law.simulate_batch_rounds(alpha_b, c.K, c.T, reps=100, seed=0)
+    def predict(alpha_b, K, reps=100):
+        act, pos = law.simulate_batch_rounds(alpha_b, K, c.T, reps=reps, seed=0)
         on = act > 0
         t = np.where(on, price(act.astype(np.float64), pos.astype(np.float64)), 0.0).sum(axis=1)
-        out[name] = {"predicted_rounds": float(on.sum(axis=1).mean()), "predicted_ms": float(t.mean() * 1e3),
-                     "predicted_speedup_vs_target_only": float(t_base / t.mean())}
+        return float(on.sum(axis=1).mean()), float(t.mean())
+    for name, alpha_b in (("pooled_acceptance", np.full(c.batch, pooled)), ("per_series_acceptance", raw)):
+        r, t = predict(alpha_b, c.K)
+        out[name] = {"predicted_rounds": r, "predicted_ms": t * 1e3, "predicted_speedup_vs_target_only": t_base / t}
+    # the same model as a planner: the block size K' <= K with the shortest predicted decode of the whole batch (the
+    # mean of the two acceptance models; a round of K' positions priced on the line between one and K positions)
+    by_k = {k: 0.5 * (predict(np.full(c.batch, pooled), k, 40)[1] + predict(raw, k, 40)[1]) for k in range(1, c.K + 1)}
+    out["predicted_ms_by_block_size"] = {str(k): round(v * 1e3, 3) for k, v in by_k.items()}
+    out["best_block_size"] = min(by_k, key=by_k.get)
     return out
 
 
@@ -400,34 +407,34 @@ def run_config(torch, tsd, synth, a, name, steps, warmup, fam_steps, flags, case
     t_base = timed(torch, lambda: decode_target_only(sess, c.T), steps)
     log(f"{c.name}: {t_base * 1e3:.2f} ms per target-only decode; phases")
     ph = phase_times(torch, sess, reps=10 if full else 5)
-    # the method's own choice of block size (Proposition "Marginal-gain condition for K"): Eq. 8 maximised over the
-    # measured cost table c(K), v(K) for K up to the configured one, and a decode at that K
     alpha = st["accepted"] / max(1, st["tested"])
-    planned = None
-    if c.K > 1 and flags == 0:
-        from paper_2511_18191_amd import planner
-        log(f"{c.name}: cost table for K = 1..{c.K}")
-        costs = planner.cost_table(sess, c.K, reps=4)
-        k_star = planner.plan(alpha, costs, min(2, c.K))["k_table"]
-        planned = {"K": k_star, "rule": "argmax over K <= configured K of E[L](acceptance, K) / (c(K) K + v(K)), measured cost table",
-                   "v_of_K": {str(k): round(costs[k]["v"], 3) for k in costs}, "c_of_K": {str(k): round(costs[k]["c"], 4) for k in costs}}
-        if k_star != c.K:
-            sess.set_block_size(k_star)
-            decode_spec(sess)
-            st_k = sess.get_stats()
-            t_k = timed(torch, lambda: decode_spec(sess), max(2, steps // 2))
-            sess.set_block_size(c.K)
-            planned.update(value=c.batch * c.horizon / t_k, ms_per_step=t_k * 1e3, speedup_vs_target_only=t_base / t_k,
-                           acceptance=st_k["accepted"] / max(1, st_k["tested"]),
-                           mean_committed_per_round=st_k["committed"] / max(1, st_k["rounds"]))
-        else:
-            planned.update(value=c.batch * c.horizon / t_spec, ms_per_step=t_spec * 1e3, speedup_vs_target_only=t_base / t_spec)
-    batch_pred = None
+    batch_pred, planned = None, None
     if flags == 0:
         log(f"{c.name}: round times by active count, batch-level prediction")
         decode_spec(sess)                                                     # per-series counters of a whole decode at the configured K
         batch_pred = batch_level_prediction(torch, sess, case, c, t_base)
         batch_pred.update(measured_ms=t_spec * 1e3, measured_rounds=rounds, measured_speedup_vs_target_only=t_base / t_spec)
+    # the method's own choice of block size (Proposition "Marginal-gain condition for K"), two ways: Eq. 8 maximised
+    # over the measured cost table c(K), v(K) (committed patches per unit time of one series), and the shortest predicted
+    # decode of the whole batch (the lock-step model above); a decode at each
+    if c.K > 1 and flags == 0:
+        from paper_2511_18191_amd import planner
+        log(f"{c.name}: cost table for K = 1..{c.K}")
+        costs = planner.cost_table(sess, c.K, reps=4)
+        planned = {"v_of_K": {str(k): round(costs[k]["v"], 3) for k in costs}, "c_of_K": {str(k): round(costs[k]["c"], 4) for k in costs}}
+        timed_at = {c.K: (t_spec, st)}
+        for rule, k_star in (("eq8_over_measured_cost_table", planner.plan(alpha, costs, min(2, c.K))["k_table"]),
+                             ("shortest_predicted_batch_decode", batch_pred["best_block_size"])):
+            if k_star not in timed_at:
+                sess.set_block_size(k_star)
+                decode_spec(sess)
+                st_k = sess.get_stats()
+                timed_at[k_star] = (timed(torch, lambda: decode_spec(sess), max(2, steps // 2)), st_k)
+                sess.set_block_size(c.K)
+            t_k, st_k = timed_at[k_star]
+            planned[rule] = {"K": k_star, "value": c.batch * c.horizon / t_k, "ms_per_step": t_k * 1e3, "speedup_vs_target_only": t_base / t_k,
+                             "acceptance": st_k["accepted"] / max(1, st_k["tested"]),
+                             "mean_committed_per_round": st_k["committed"] / max(1, st_k["rounds"])}
     log(f"{c.name}: kernel-by-kernel timing pass")
     standard = full and a.sigma is None and a.batch is None and flags == 0 and a.fallback_r == 0.0
     traffic, traffic_src = measured_traffic(c.name if (standard or not full) else None)
