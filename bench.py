@@ -272,63 +272,15 @@ def measured_peaks(torch, tsd):
 
 
 def batch_level_prediction(torch, sess, case, c, t_base):
-    """The whole-batch decode time the capped-geometric law predicts once the batch's lock-step is modelled
-    (law.simulate_batch_rounds: every series draws its blocks with its own measured acceptance, the batch runs until
-    the slowest is done), priced with measured round times: one round (graph replay and the delivery of the count) from
-    the post-prefill state of a batch of n series, for n at the size classes of the active list, at the configured
-    number of positions and at one, linear in between.  Leaves the handle prefilled with the whole batch again."""
-    import numpy as np
-    from paper_2511_18191_amd import law
-    per = sess.get_series_stats().cpu().numpy().astype(np.float64)            # of the last decode: rounds, tested, accepted, ...
-    pooled = per[:, 2].sum() / max(1.0, per[:, 1].sum())
-    raw = np.where(per[:, 1] > 0, per[:, 2] / np.maximum(per[:, 1], 1.0), pooled)   # each series' own accepted / tested
-    sizes = sorted({max(1, (c.batch * f + 31) // 32) for f in (32, 24, 16, 12, 8, 4, 2, 1)}, reverse=True)
-    ks = sorted({c.K, 1})
-    cost = {}
-    for n in sizes:
-        sess.prefill(case.context[:n], c.n_ctx, c.horizon)
-        for k in ks:
-            sess.set_block_size(k)
-            ts = []
-            for _ in range(4):
-                sess.reset_decode()
-                torch.cuda.synchronize()
-                t0 = time.perf_counter()
-                sess.round()
-                sess.num_active()
-                torch.cuda.synchronize()
-                ts.append(time.perf_counter() - t0)
-            cost[(n, k)] = min(ts[1:])
-        sess.set_block_size(c.K)
-    sess.prefill(case.context, c.n_ctx, c.horizon)
-    ns = np.array(sorted(sizes), dtype=np.float64)
-    at = {k: np.array([cost[(int(n), k)] for n in ns]) for k in ks}
-
-    def price(n, k):
-        hi = np.interp(n, ns, at[c.K])
-        if c.K == 1:
-            return hi
-        lo = np.interp(n, ns, at[1])
-        return lo + (hi - lo) * (k - 1) / (c.K - 1)
-    out = {"model": "capped-geometric blocks per series, the batch runs until its slowest series is done (100 Monte Carlo batches); rounds "
-                    "priced with measured round times by active count and positions.  Two acceptance models bracket a real batch: "
-                    "every series at the pooled measured rate (the law's i.i.d. assumption), and every series at its own measured "
-                    "accepted / tested (which adds the sampling noise of a dozen tests per series to the real spread)",
-           "round_ms_by_active": {str(n): round(cost[(n, c.K)] * 1e3, 4) for n in sizes},
-           "acceptance_spread_5_50_95": [float(np.quantile(raw, q)) for q in (0.05, 0.5, 0.95)]}
-    def predict(alpha_b, K, reps=100):
-        act, pos = law.simulate_batch_rounds(alpha_b, K, c.T, reps=reps, seed=0)
-        on = act > 0
-        t = np.where(on, price(act.astype(np.float64), pos.astype(np.float64)), 0.0).sum(axis=1)
-        return float(on.sum(axis=1).mean()), float(t.mean())
-    for name, alpha_b in (("pooled_acceptance", np.full(c.batch, pooled)), ("per_series_acceptance", raw)):
-        r, t = predict(alpha_b, c.K)
-        out[name] = {"predicted_rounds": r, "predicted_ms": t * 1e3, "predicted_speedup_vs_target_only": t_base / t}
-    # the same model as a planner: the block size K' <= K with the shortest predicted decode of the whole batch (the
-    # mean of the two acceptance models; a round of K' positions priced on the line between one and K positions)
-    by_k = {k: 0.5 * (predict(np.full(c.batch, pooled), k, 40)[1] + predict(raw, k, 40)[1]) for k in range(1, c.K + 1)}
-    out["predicted_ms_by_block_size"] = {str(k): round(v * 1e3, 3) for k, v in by_k.items()}
-    out["best_block_size"] = min(by_k, key=by_k.get)
+    """The whole-batch decode time the capped-geometric law predicts once the batch's lock-step is modelled, and the
+    block size with the shortest predicted decode (planner.batch_decode_model; measured round times by active count).
+    Leaves the handle prefilled with the whole batch again."""
+    from paper_2511_18191_amd import planner
+    per = sess.get_series_stats().cpu().numpy()                               # of the last decode: rounds, tested, accepted, ...
+    cost = planner.round_times(sess, case.context, c.n_ctx, c.horizon, c.K)
+    out = planner.batch_decode_model(per[:, 1], per[:, 2], cost, c.K, c.T)
+    for name in ("pooled_acceptance", "per_series_acceptance"):
+        out[name]["predicted_speedup_vs_target_only"] = t_base * 1e3 / out[name]["predicted_ms"]
     return out
 
 

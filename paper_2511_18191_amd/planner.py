@@ -14,7 +14,9 @@ Steps, all on one handle created with K = k_max (`tsd_set_block_size` moves K be
   3. the paper's rule with the pair (alpha, c, v) measured at k_probe, and the same maximisation of
      Eq. 8 with the measured c(K), v(K) (here verification is K + 1 tokens against a KV cache, so v
      grows with K once the batch fills the GPU);
-  4. --validate: time whole decodes at every K and show where the measured optimum lies.
+  4. --validate: time whole decodes at every K and show where the measured optimum lies;
+  5. the lock-step model of the whole batch (batch_decode_model): the block size with the shortest predicted decode,
+     which, unlike Eq. 8, pays for the rounds in which only the slowest series are still decoding.
 """
 import argparse
 import sys
@@ -68,6 +70,75 @@ def plan(alpha, costs, k_probe):
     return dict(k_rule=k_rule, k_table=max(S, key=S.get), S_table=S, S_rule={K: law.speedup(alpha, K, c0, v0) for K in costs})
 
 
+def round_times(sess, context, n_ctx, horizon, K, reps=4):
+    """Wall time of one round (graph replay and the delivery of the count) from the post-prefill state of a batch of n
+    series, for n at the size classes of the active list (32, 24, 16, 12, 8, 4, 2, 1 thirty-seconds of the batch), at K
+    positions and at one.  Returns {(n, k): seconds}.  Leaves the handle prefilled with the whole batch at block size K."""
+    import time
+    import torch
+    B = context.shape[0]
+    sizes = sorted({max(1, (B * f + 31) // 32) for f in (32, 24, 16, 12, 8, 4, 2, 1)}, reverse=True)
+    cost = {}
+    for n in sizes:
+        sess.prefill(context[:n], n_ctx, horizon)
+        for k in sorted({K, 1}):
+            sess.set_block_size(k)
+            ts = []
+            for _ in range(reps):
+                sess.reset_decode()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                sess.round()
+                sess.num_active()
+                torch.cuda.synchronize()
+                ts.append(time.perf_counter() - t0)
+            cost[(n, k)] = min(ts[1:])
+        sess.set_block_size(K)
+    sess.prefill(context, n_ctx, horizon)
+    return cost
+
+
+def batch_decode_model(tested, accepted, cost, K, T, reps=100):
+    """Decode time of a whole batch as the capped-geometric law predicts it once the lock-step is modelled
+    (law.simulate_batch_rounds: every series draws its blocks, the batch runs until its slowest series has its T
+    patches), each simulated round priced with `cost` (round_times: linear in the active count between the measured
+    sizes and in the positions between one and K).  tested, accepted: per-series counters of a decode.  Two acceptance
+    models bracket a real batch: every series at the pooled measured rate (the law's i.i.d. assumption), and every series
+    at its own accepted / tested (which adds the sampling noise of a dozen tests per series to the real spread).
+    Also the block size K' <= K with the shortest predicted decode (mean of the two models)."""
+    tested, accepted = np.asarray(tested, dtype=np.float64), np.asarray(accepted, dtype=np.float64)
+    B = tested.shape[0]
+    pooled = float(accepted.sum() / max(1.0, tested.sum()))
+    raw = np.where(tested > 0, accepted / np.maximum(tested, 1.0), pooled)
+    sizes = sorted({n for n, _ in cost})
+    ns = np.array(sizes, dtype=np.float64)
+    hi_t, lo_t = np.array([cost[(n, K)] for n in sizes]), np.array([cost[(n, 1)] for n in sizes])
+
+    def price(n, k):
+        hi = np.interp(n, ns, hi_t)
+        if K == 1:
+            return hi
+        lo = np.interp(n, ns, lo_t)
+        return lo + (hi - lo) * (k - 1) / (K - 1)
+
+    def predict(alpha_b, k_block, n_rep):
+        act, pos = law.simulate_batch_rounds(alpha_b, k_block, T, reps=n_rep, seed=0)
+        on = act > 0
+        t = np.where(on, price(act.astype(np.float64), pos.astype(np.float64)), 0.0).sum(axis=1)
+        return float(on.sum(axis=1).mean()), float(t.mean())
+    out = {"model": "capped-geometric blocks per series, the batch runs until its slowest series is done (Monte Carlo); rounds priced "
+                    "with measured round times by active count and positions; acceptance either pooled (i.i.d.) or per series",
+           "round_ms_by_active": {str(n): round(cost[(n, K)] * 1e3, 4) for n in reversed(sizes)},
+           "acceptance_spread_5_50_95": [float(np.quantile(raw, q)) for q in (0.05, 0.5, 0.95)]}
+    for name, alpha_b in (("pooled_acceptance", np.full(B, pooled)), ("per_series_acceptance", raw)):
+        r, t = predict(alpha_b, K, reps)
+        out[name] = {"predicted_rounds": r, "predicted_ms": t * 1e3}
+    by_k = {k: 0.5 * (predict(np.full(B, pooled), k, 40)[1] + predict(raw, k, 40)[1]) for k in range(1, K + 1)}
+    out["predicted_ms_by_block_size"] = {str(k): round(v * 1e3, 3) for k, v in by_k.items()}
+    out["best_block_size"] = min(by_k, key=by_k.get)
+    return out
+
+
 def main(argv=None):
     import torch
     ap = argparse.ArgumentParser()
@@ -111,6 +182,13 @@ def main(argv=None):
             row += (f" {st['accepted'] / max(1, st['tested']):.3f} | {L:.2f} | {t_spec * 1e3:.2f} | {t_base * 1e3:.2f} | "
                     f"{t_base / t_spec:.2f} | {L * t['step'] / (t['draft'] + t['verify'] + t['accept']):.2f} |")
         print(row, flush=True)
+    if c.batch > 1:
+        sess.set_block_size(a.k_max)
+        _decode_spec(sess)
+        per = sess.get_series_stats().cpu().numpy()
+        m = batch_decode_model(per[:, 1], per[:, 2], round_times(sess, inputs.context, c.n_ctx, c.horizon, a.k_max), a.k_max, c.T)
+        print(f"\nlock-step model of the whole batch (capped-geometric blocks per series until the slowest is done, measured round "
+              f"times by active count): predicted decode ms by block size {m['predicted_ms_by_block_size']}; shortest at K = {m['best_block_size']}")
     sess.close()
 
 

@@ -166,3 +166,27 @@ def test_run_rounds_is_the_written_out_loop(name):
     r2, left2 = b.run_rounds()
     assert left2 == 0 and r + r2 >= rounds - 1
     assert np.isfinite(b.get_forecast().cpu().numpy()).all()
+
+
+def test_batch_decode_model_is_well_formed_and_counts_rounds_like_the_gpu():
+    # the lock-step model of a whole batch: its round-time table covers the size classes at K positions and at one,
+    # its predicted round counts bracket what the GPU needed (pooled acceptance: fewer stragglers; per-series fractions:
+    # more), and the chosen block size is one the handle can run.  (No assertion on times: those are measurements.)
+    from paper_2511_18191_amd import planner
+    case = Case("mini3", B=29, horizon=96 * 14, sigma=0.45)
+    c = case.cfg
+    sess = case.session()
+    sess.prefill(case.context, c.n_ctx, c.horizon)
+    rounds, left = sess.run_rounds()
+    assert left == 0
+    per = sess.get_series_stats().cpu().numpy()
+    cost = planner.round_times(sess, case.context, c.n_ctx, c.horizon, c.K, reps=2)
+    sizes = sorted({n for n, _ in cost})
+    assert sizes[-1] == 29 and sizes[0] == 1 and all((n, k) in cost and cost[(n, k)] > 0 for n in sizes for k in (1, c.K))
+    m = planner.batch_decode_model(per[:, 1], per[:, 2], cost, c.K, c.T)
+    lo, hi = m["pooled_acceptance"]["predicted_rounds"], m["per_series_acceptance"]["predicted_rounds"]
+    assert lo <= hi + 0.5 and lo - 2.0 <= rounds <= hi + 2.0, (lo, rounds, hi)
+    assert 1 <= m["best_block_size"] <= c.K and len(m["predicted_ms_by_block_size"]) == c.K
+    # the handle is back at the whole batch and the configured block size: a decode gives the same books as before
+    r2, left = sess.run_rounds()
+    assert (r2, left) == (rounds, 0) and np.array_equal(sess.get_series_stats().cpu().numpy(), per)
