@@ -214,6 +214,28 @@ __global__ __launch_bounds__(256 * G) void gemm_kernel(const GemmP p) {
       for (int j = 0; j < 4; ++j) accf[i][j] = 0.f;
   }
   const int ty = gt >> 4, tx = gt & 15;  // fp32 path: 4x4 micro-tile at (ty*4, tx*4)
+  // Long contractions of activations (K >= kQuarterK) are summed in four runs of ceil(nk / 4) k-steps, each from
+  // zero, the runs added in order: the order the split workgroups (G = 4) produce by construction.  Every bf16
+  // kernel that can take such a product (this one, the split one, the wide-tile ones) keeps to it, so which of them
+  // the launcher picks, which follows the rows still active, changes no bit.
+  constexpr bool kQuarters = kBf && AM == A_ACT && G == 1 && BM == 64;
+  f32x16 tot[kQuarters ? TM : 1][kQuarters ? TN : 1];
+  const bool quarters = kQuarters && p.K >= kQuarterK;
+  auto fold = [&](int done) {  // `done` k-steps are in acc: at a run's end move them into the running sum
+    if constexpr (kQuarters) {
+      const int nk_all = (p.K + BK - 1) / BK, run = (nk_all + 3) / 4;
+      if (!quarters || done % run != 0 || done >= nk_all) return;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            tot[i][j][r] = done == run ? acc[i][j][r] : tot[i][j][r] + acc[i][j][r];
+            acc[i][j][r] = 0.f;
+          }
+    }
+  };
 
   // ---- main loop ----------------------------------------------------------------------------
   auto compute = [&](int buf) {
@@ -295,19 +317,32 @@ __global__ __launch_bounds__(256 * G) void gemm_kernel(const GemmP p) {
     load_global(kt0 + kt + 2, ra0, rb0);
     __builtin_amdgcn_sched_barrier(0);
     compute(0);
+    fold(kt + 1);
     store_lds(kt0 + kt + 1, 1, ra1, rb1);
     __syncthreads();
     load_global(kt0 + kt + 3, ra1, rb1);
     __builtin_amdgcn_sched_barrier(0);
     compute(1);
+    fold(kt + 2);
     store_lds(kt0 + kt + 2, 0, ra0, rb0);
     __syncthreads();
   }
   compute(0);
+  fold(kt + 1);
   if (kt + 1 < nkl) {
     store_lds(kt0 + kt + 1, 1, ra1, rb1);
     __syncthreads();
     compute(1);
+  }
+  if constexpr (kQuarters) {
+    if (quarters) {  // the last run joins the sum of the first three
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] = tot[i][j][r] + acc[i][j][r];
+    }
   }
 
   if constexpr (EP == EP_QKV) {
@@ -410,14 +445,18 @@ int gemm_row_tile(int dtype, int M, int N, int force_bm) {
 // the choice depends on the shape of the product alone.
 static bool gemm_split(const GemmP& p) {
   const long t64 = (long)(p.tile_map ? p.n_mtiles : (p.M + 63) / 64) * ((p.N + 63) / 64);
-  return p.K >= 1024 && t64 <= 256;
+  return p.K >= kQuarterK && t64 <= 256;
 }
 
 template <typename T, int AM, int EP>
 static hipError_t launch_cfg(const GemmP& p, hipStream_t st) {
   constexpr bool kBf = !std::is_same<T, float>::value;
   if constexpr (kBf) {
-    if (gemm_row_tile(TSD_BF16, p.M, p.N, p.force_bm) == 128) return launch_tile<T, AM, EP, 128, 128, 64>(p, st);
+    // (the 128-row register-staged tiles have no room for the running sum of a long contraction's four runs: such
+    //  products of activations go to the wide-tile kernels or stay on 64-row tiles)
+    const bool long_act = AM == A_ACT && p.K >= kQuarterK;
+    if (long_act && p.tile_map && p.force_bm == 128) return hipErrorInvalidValue;  // (the caller builds 64-row maps for these)
+    if (!long_act && gemm_row_tile(TSD_BF16, p.M, p.N, p.force_bm) == 128) return launch_tile<T, AM, EP, 128, 128, 64>(p, st);
     if constexpr (AM == A_ACT) {
       if (gemm_split(p)) return launch_tile<T, AM, EP, 64, 64, 64, 4>(p, st);
     }
@@ -471,7 +510,7 @@ int gemm_variant(int dtype, int amode, int epi, const GemmP& p) {
   if (p.allow_skinny && skinny_applicable(dtype, amode, epi, p)) return 16;
   if (dtype != TSD_BF16) return 64;
   if (const int bm = gemm_wide_bm(dtype, amode, epi, p)) return 2000 + bm;
-  if (gemm_row_tile(TSD_BF16, p.M, p.N, p.force_bm) == 128) return 128;
+  if (!(amode == A_ACT && p.K >= kQuarterK) && gemm_row_tile(TSD_BF16, p.M, p.N, p.force_bm) == 128) return 128;
   return (amode == A_ACT && gemm_split(p)) ? 464 : 64;
 }
 

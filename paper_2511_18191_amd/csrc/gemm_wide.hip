@@ -162,6 +162,10 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_wide_kernel(const GemmP p) {
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  // Long contractions of activations are summed in four runs of ceil(nk / 4) k-tiles, each from zero, the runs added in
+  // order (the order of the split workgroups of gemm.hip, which every kernel that can take such a product keeps to)
+  constexpr bool kQuarters = (AM == A_ACT) && BK == 64;
+  f32x16 tot[kQuarters ? TM : 1][kQuarters ? TN : 1];
   float ss[TM][4];  // row-sum chains of this lane: chunk positions hi, 2 + hi, 4 + hi, 6 + hi of a 64-wide k-run
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -273,17 +277,49 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_wide_kernel(const GemmP p) {
   // steady state: k-tiles 0 .. nk - NS - 1 (each refills its slot); then the last NS k-tiles
   constexpr int STEADY_PEND = (NS - 2) * NL;
   const int n_steady = nk - NS;
+  const bool quarters = kQuarters && K >= kQuarterK;
+  const int run = (nk + 3) / 4;
+  auto fold = [&](int done) {  // `done` k-tiles are in acc: at a run's end move them into the running sum
+    if constexpr (kQuarters) {
+      if (!quarters || done % run != 0 || done >= nk) return;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            tot[i][j][r] = done == run ? acc[i][j][r] : tot[i][j][r] + acc[i][j][r];
+            acc[i][j][r] = 0.f;
+          }
+    }
+  };
   int kt = 0;
   if constexpr (NPAR == 1) {
-    for (; kt < n_steady; ++kt) tile(IC<0>{}, kt, IC<STEADY_PEND>{}, IC<1>{});
+    for (; kt < n_steady; ++kt) {
+      tile(IC<0>{}, kt, IC<STEADY_PEND>{}, IC<1>{});
+      fold(kt + 1);
+    }
     // tail: k-tile nk - NS + t leaves NS - 2 - t stages in flight at its barrier; the last one has no barrier
     if constexpr (NS == 2) {
       tile(IC<0>{}, kt, IC<0>{}, IC<0>{});
+      fold(kt + 1);
       tile(IC<0>{}, kt + 1, IC<-1>{}, IC<0>{});
     } else {
       tile(IC<0>{}, kt, IC<NL>{}, IC<0>{});
+      fold(kt + 1);
       tile(IC<0>{}, kt + 1, IC<0>{}, IC<0>{});
+      fold(kt + 2);
       tile(IC<0>{}, kt + 2, IC<-1>{}, IC<0>{});
+    }
+    if constexpr (kQuarters) {
+      if (quarters) {  // the last run joins the sum of the first three
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = tot[i][j][r] + acc[i][j][r];
+      }
     }
   } else {
     static_assert(NPAR == 1 || NS == 3, "32-wide k-tiles run with three stages");

@@ -504,7 +504,20 @@ int run_pass(tsd_ctx* ctx, const Pass& ps, hipStream_t st) {
     if (md.c.n_experts > 0) {
       // routed FFN: router -> stable sort of (token, choice) by expert -> grouped up/down GEMMs -> gated combine
       const int E = md.c.n_experts, topk = md.c.top_k, slots = M * topk;
-      const int bm = gemm_row_tile(c.dtype, slots, F, 0);
+      int bm = gemm_row_tile(c.dtype, slots, F, 0);
+      if (bm == 128 && F >= kQuarterK) {
+        // the experts' second product is a long contraction of activations: at 128-row tiles only the wide-tile
+        // kernels take it (they keep the running sum of its four runs); where they do not apply, 64-row tiles
+        GemmP probe;
+        std::memset(&probe, 0, sizeof(probe));
+        probe.M = slots;
+        probe.N = D;
+        probe.K = F;
+        probe.tile_map = ctx->moe_tmap;
+        probe.force_bm = 128;
+        probe.no_wide = (c.flags & TSD_FLAG_NO_WIDE_GEMM) ? 1 : 0;
+        if (gemm_wide_bm(c.dtype, A_ACT, EP_STORE, probe) != 128) bm = 64;
+      }
       const int n_mtiles = (slots + bm - 1) / bm + E;
       HIP_TRY(ctx, timed_launch(ctx, TSD_K_ROUTE, 4.0 * M * D, st, [&] {
         return launch_router(ctx->x, md.layers[l].Wr, M, D, E, topk, ctx->moe_ids, ctx->moe_gates, st);

@@ -112,6 +112,8 @@ struct AttnP {
 // ---- launchers (each returns the hipError_t of the launch) ---------------------------------
 hipError_t launch_gemm(int dtype, int amode, int epi, const GemmP& p, hipStream_t st);
 hipError_t prepare_gemm(int dtype);
+// bf16 products of activations with K >= kQuarterK are summed in four runs of k-steps (see gemm.hip)
+constexpr int kQuarterK = 1024;
 // skinny path (at most 32 rows): see gemm_skinny.hip
 bool skinny_applicable(int dtype, int amode, int epi, const GemmP& p);
 hipError_t launch_gemm_skinny(int amode, int epi, const GemmP& p, hipStream_t st);

@@ -487,6 +487,52 @@ def test_wide_tile_gemm_same_bits_as_register_staged_and_fp64(M, N, K, variant):
     assert err < (6e-3 if variant == 3 else 2e-6 * K ** 0.5), f"{err:.3e}"
 
 
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg5"])
+def test_full_size_decode_same_bits_with_and_without_compaction_and_graphs(name):
+    # The benchmark's decode at full size (graphs per size class, compacted passes, kernels picked by the rows still
+    # active) against handles that never compact (every pass over the whole batch) and that never replay graphs:
+    # forecasts, round counts and counters equal to the bit.  Which kernel a shrinking pass runs on must not show.
+    import paper_2511_18191_amd as tsd
+    case = Case(name)
+    c = case.cfg
+    outs = []
+    for flags in (0, tsd.TSD_FLAG_NO_COMPACT, tsd.TSD_FLAG_NO_GRAPH):
+        sess = case.session(flags=flags)
+        sess.prefill(case.context, c.n_ctx, c.horizon)
+        rounds, left = sess.run_rounds()
+        assert left == 0
+        outs.append((sess.get_forecast().cpu(), sess.get_stats(), rounds, sess.get_series_stats().cpu()))
+        sess.close()
+    for o in outs[1:]:
+        assert torch.equal(o[0], outs[0][0]) and o[1] == outs[0][1] and o[2] == outs[0][2] and torch.equal(o[3], outs[0][3])
+    assert outs[0][1]["committed"] == c.batch * c.T
+
+
+@pytest.mark.parametrize("N,K", [(1024, 4096), (1024, 1024), (768, 3072), (512, 2048)])
+def test_long_contractions_give_the_same_bits_whatever_kernel_takes_them(N, K):
+    # A product of activations with K >= 1024 is summed in four runs of k-steps by every bf16 kernel that can take it
+    # (64-row tiles, the split workgroups that take over when few rows are left, both wide tiles), so the rows of a
+    # small product equal, to the bit, the same rows inside a large one: which kernel runs follows the rows still
+    # active, and must not show in the result.
+    import paper_2511_18191_amd as tsd
+    g = torch.Generator().manual_seed(N + K)
+    A = torch.randn(7168, K, generator=g).to(torch.bfloat16).cuda()
+    W = (torch.randn(N, K, generator=g) * 0.05).to(torch.bfloat16).cuda()
+    res = {}
+    for M in (7168, 4000, 1024, 200, 33):
+        for variant in (0, 2):                               # plain store, residual add
+            out = torch.full((M, N), 0.25, dtype=torch.float32, device="cuda")
+            tsd.bench_gemm(A[:M].contiguous(), W, out=out, variant=variant)
+            torch.cuda.synchronize()
+            res[(M, variant)] = out.cpu()
+    for variant in (0, 2):
+        for M in (4000, 1024, 200, 33):
+            assert torch.equal(res[(M, variant)], res[(7168, variant)][:M]), (M, variant)
+    ref = A.cpu()[:64].double() @ W.cpu().double().T
+    err = (res[(7168, 0)][:64].double() - ref).abs().max() / ref.abs().max()
+    assert err < 2e-6 * K ** 0.5
+
+
 def test_wide_tile_kernels_change_no_bit_of_a_routed_pass():
     # cfg 5 at full size: the grouped expert products of the verification pass run on the wide 128 x 128 tiles
     # (their tile map is built for 128-row tiles there); with TSD_FLAG_NO_WIDE_GEMM they run on the
