@@ -268,7 +268,8 @@ int tsd_target_step(tsd_ctx* ctx, void* stream);
  * device-side one, so a series that finishes in between costs at most workgroups that leave at
  * once, never a second visit.  Handles whose passes are sized on the host (routed models) keep
  * reading the list as of this call until the next one.
- * Results are identical with or without it; finished series simply stop costing work.
+ * Results are identical, to the bit, with or without it (every kernel a shrinking pass may be
+ * handed sums in the same order); finished series simply stop costing work.
  * The counts reach the host through a few pinned host words that the compaction kernel writes
  * itself (tsd_round already ends with that kernel), so this call normally launches nothing and
  * waits for nothing but those words; it falls back to a copy and a stream wait when pinned
