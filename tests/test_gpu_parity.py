@@ -508,7 +508,7 @@ def test_full_size_decode_same_bits_with_and_without_compaction_and_graphs(name)
     assert outs[0][1]["committed"] == c.batch * c.T
 
 
-@pytest.mark.parametrize("N,K", [(1024, 4096), (1024, 1024), (768, 3072), (512, 2048)])
+@pytest.mark.parametrize("N,K", [(1024, 4096), (1024, 1024), (768, 3072), (512, 2048), (1024, 1088), (896, 1216), (1024, 1056)])
 def test_long_contractions_give_the_same_bits_whatever_kernel_takes_them(N, K):
     # A product of activations with K >= 1024 is summed in four runs of k-steps by every bf16 kernel that can take it
     # (64-row tiles, the split workgroups that take over when few rows are left, both wide tiles), so the rows of a
