@@ -129,6 +129,7 @@ def batch_decode_model(tested, accepted, cost, K, T, reps=100):
     out = {"model": "capped-geometric blocks per series, the batch runs until its slowest series is done (Monte Carlo); rounds priced "
                     "with measured round times by active count and positions; acceptance either pooled (i.i.d.) or per series",
            "round_ms_by_active": {str(n): round(cost[(n, K)] * 1e3, 4) for n in reversed(sizes)},
+           "round_ms_by_active_at_one_position": {str(n): round(cost[(n, 1)] * 1e3, 4) for n in reversed(sizes)},
            "acceptance_spread_5_50_95": [float(np.quantile(raw, q)) for q in (0.05, 0.5, 0.95)]}
     for name, alpha_b in (("pooled_acceptance", np.full(B, pooled)), ("per_series_acceptance", raw)):
         r, t = predict(alpha_b, K, reps)
